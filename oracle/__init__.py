@@ -1,0 +1,260 @@
+"""CPU oracle for the atom-to-grid path -- TEST INFRASTRUCTURE, not product code.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  It shares nothing with the HIP library
+(``paper_1912_04822_amd``) and neither imports the other.
+
+The arithmetic lives in ``molgrid_oracle.c`` (plain C, double precision, one
+fixed float sequence for the binary predicate); this module only compiles that
+file with gcc and marshals numpy arrays into it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "molgrid_oracle.c")
+_LIB = os.path.join(_HERE, "libmolgrid_oracle.so")
+
+_lib: Optional[ctypes.CDLL] = None
+
+_f32p = ctypes.POINTER(ctypes.c_float)
+_f64p = ctypes.POINTER(ctypes.c_double)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  -ffp-contract=off: no fused multiply-add."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+               "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        L.orc_cutoff.restype = ctypes.c_double
+        L.orc_cutoff.argtypes = [ctypes.c_double]
+        L.orc_density.restype = ctypes.c_double
+        L.orc_density.argtypes = [ctypes.c_double, ctypes.c_double]
+        L.orc_density_deriv.restype = ctypes.c_double
+        L.orc_density_deriv.argtypes = [ctypes.c_double, ctypes.c_double]
+        L.orc_points_per_side.restype = ctypes.c_int
+        L.orc_points_per_side.argtypes = [ctypes.c_double, ctypes.c_double]
+        L.orc_quat_to_matrix.restype = None
+        L.orc_quat_to_matrix.argtypes = [_f32p, _f64p]
+        _lib = L
+    return _lib
+
+
+def _f32(a, shape=None):
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if shape is not None:
+        assert a.shape == tuple(shape), (a.shape, shape)
+    return a
+
+
+def _i32(a, shape=None):
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    if shape is not None:
+        assert a.shape == tuple(shape), (a.shape, shape)
+    return a
+
+
+def _p(a, typ):
+    return a.ctypes.data_as(typ) if a is not None else typ()
+
+
+# --------------------------------------------------------------------------
+# scalar functions
+# --------------------------------------------------------------------------
+
+def cutoff(g: float) -> float:
+    return lib().orc_cutoff(float(g))
+
+
+def density(x: float, g: float = 1.0) -> float:
+    return lib().orc_density(float(x), float(g))
+
+
+def density_deriv(x: float, g: float = 1.0) -> float:
+    return lib().orc_density_deriv(float(x), float(g))
+
+
+def points_per_side(resolution: float, dimension: float) -> int:
+    return lib().orc_points_per_side(float(resolution), float(dimension))
+
+
+def quat_to_matrix(q) -> np.ndarray:
+    q = _f32(q, (4,))
+    R = np.empty(9, dtype=np.float64)
+    lib().orc_quat_to_matrix(_p(q, _f32p), _p(R, _f64p))
+    return R.reshape(3, 3)
+
+
+# --------------------------------------------------------------------------
+# batch functions
+# --------------------------------------------------------------------------
+
+def transform(coords, centers=None, quats=None, translations=None, as_float=True):
+    """x' = R(q)(x - c) + c + t per example.  Returns float32 (rounded once) or float64."""
+    coords = _f32(coords)
+    B, N, _ = coords.shape
+    centers = _f32(centers, (B, 3))
+    quats = _f32(quats, (B, 4))
+    translations = _f32(translations, (B, 3))
+    o32 = np.empty((B, N, 3), np.float32) if as_float else None
+    o64 = None if as_float else np.empty((B, N, 3), np.float64)
+    lib().orc_transform(ctypes.c_int(B), ctypes.c_int(N), _p(coords, _f32p),
+                        _p(centers, _f32p), _p(quats, _f32p), _p(translations, _f32p),
+                        _p(o32, _f32p), _p(o64, _f64p))
+    return o32 if as_float else o64
+
+
+def _common(coords, natoms, centers, quats, translations):
+    coords = _f32(coords)
+    B, N, three = coords.shape
+    assert three == 3
+    return (coords, B, N, _i32(natoms, (B,)), _f32(centers, (B, 3)), _f32(quats, (B, 4)),
+            _f32(translations, (B, 3)))
+
+
+def forward_index(coords, types, radii, T, resolution, dimension, *, grm=1.0,
+                  radius_scale=1.0, radius_type_indexed=True, natoms=None, centers=None,
+                  quats=None, translations=None, box=True, coords_as_float=True,
+                  out_dtype=np.float32, threads=0, return_threads=False):
+    """Real-valued density grid [B,T,D,D,D] for index-typed atoms."""
+    coords, B, N, natoms, centers, quats, translations = _common(
+        coords, natoms, centers, quats, translations)
+    types = _i32(types, (B, N))
+    radii = _f32(radii, (T,) if radius_type_indexed else (B, N))
+    D = points_per_side(resolution, dimension)
+    f64 = np.dtype(out_dtype) == np.float64
+    out = np.empty((B, T, D, D, D), np.float64 if f64 else np.float32)
+    rc = lib().orc_forward_index(
+        ctypes.c_int(B), ctypes.c_int(N), ctypes.c_int(T), ctypes.c_double(resolution),
+        ctypes.c_double(dimension), ctypes.c_double(grm), ctypes.c_double(radius_scale),
+        ctypes.c_int(int(radius_type_indexed)), ctypes.c_int(int(coords_as_float)),
+        ctypes.c_int(int(box)), _p(coords, _f32p), _p(types, _i32p), _p(radii, _f32p),
+        _p(natoms, _i32p), _p(centers, _f32p), _p(quats, _f32p), _p(translations, _f32p),
+        _p(None if f64 else out, _f32p), _p(out if f64 else None, _f64p),
+        ctypes.c_int(threads))
+    if rc < 0:
+        raise MemoryError("oracle allocation failed")
+    return (out, rc) if return_threads else out
+
+
+def forward_vector(coords, weights, radii, resolution, dimension, *, grm=1.0,
+                   radius_scale=1.0, natoms=None, centers=None, quats=None,
+                   translations=None, box=True, coords_as_float=True,
+                   out_dtype=np.float32, threads=0, return_threads=False):
+    """Real-valued density grid [B,T,D,D,D] for vector-typed atoms (weights [B,N,T])."""
+    coords, B, N, natoms, centers, quats, translations = _common(
+        coords, natoms, centers, quats, translations)
+    weights = _f32(weights)
+    T = weights.shape[2]
+    assert weights.shape == (B, N, T)
+    radii = _f32(radii, (T,))
+    D = points_per_side(resolution, dimension)
+    f64 = np.dtype(out_dtype) == np.float64
+    out = np.empty((B, T, D, D, D), np.float64 if f64 else np.float32)
+    rc = lib().orc_forward_vector(
+        ctypes.c_int(B), ctypes.c_int(N), ctypes.c_int(T), ctypes.c_double(resolution),
+        ctypes.c_double(dimension), ctypes.c_double(grm), ctypes.c_double(radius_scale),
+        ctypes.c_int(int(coords_as_float)), ctypes.c_int(int(box)), _p(coords, _f32p),
+        _p(weights, _f32p), _p(radii, _f32p), _p(natoms, _i32p), _p(centers, _f32p),
+        _p(quats, _f32p), _p(translations, _f32p),
+        _p(None if f64 else out, _f32p), _p(out if f64 else None, _f64p),
+        ctypes.c_int(threads))
+    if rc < 0:
+        raise MemoryError("oracle allocation failed")
+    return (out, rc) if return_threads else out
+
+
+def forward_binary(coords, radii, T, resolution, dimension, *, types=None, weights=None,
+                   radius_scale=1.0, radius_type_indexed=True, natoms=None, centers=None,
+                   quats=None, translations=None, box=True, threads=0):
+    """Binary occupancy grid [B,T,D,D,D] float32 in {0,1} (float predicate, fixed order)."""
+    coords, B, N, natoms, centers, quats, translations = _common(
+        coords, natoms, centers, quats, translations)
+    assert (types is None) != (weights is None)
+    types = _i32(types, (B, N))
+    weights = _f32(weights, (B, N, T)) if weights is not None else None
+    radii = _f32(radii, (T,) if (radius_type_indexed or types is None) else (B, N))
+    D = points_per_side(resolution, dimension)
+    out = np.empty((B, T, D, D, D), np.float32)
+    lib().orc_forward_binary(
+        ctypes.c_int(B), ctypes.c_int(N), ctypes.c_int(T), ctypes.c_float(resolution),
+        ctypes.c_float(dimension), ctypes.c_float(radius_scale),
+        ctypes.c_int(int(radius_type_indexed)), ctypes.c_int(int(box)), _p(coords, _f32p),
+        _p(types, _i32p), _p(weights, _f32p), _p(radii, _f32p), _p(natoms, _i32p),
+        _p(centers, _f32p), _p(quats, _f32p), _p(translations, _f32p), _p(out, _f32p),
+        ctypes.c_int(threads))
+    return out
+
+
+def _grad_ptrs(grad_out, shape):
+    if grad_out.dtype == np.float64:
+        G = np.ascontiguousarray(grad_out)
+        assert G.shape == shape
+        return G, _f32p(), _p(G, _f64p)
+    G = _f32(grad_out, shape)
+    return G, _p(G, _f32p), _f64p()
+
+
+def backward_index(coords, types, radii, T, resolution, dimension, grad_out, *, grm=1.0,
+                   radius_scale=1.0, radius_type_indexed=True, natoms=None, centers=None,
+                   quats=None, translations=None, box=True, coords_as_float=True,
+                   threads=0):
+    """dL/dcoords [B,N,3] float64 for L = sum(grad_out * forward_index(...))."""
+    coords, B, N, natoms, centers, quats, translations = _common(
+        coords, natoms, centers, quats, translations)
+    types = _i32(types, (B, N))
+    radii = _f32(radii, (T,) if radius_type_indexed else (B, N))
+    D = points_per_side(resolution, dimension)
+    G, g32, g64 = _grad_ptrs(grad_out, (B, T, D, D, D))
+    out = np.empty((B, N, 3), np.float64)
+    lib().orc_backward_index(
+        ctypes.c_int(B), ctypes.c_int(N), ctypes.c_int(T), ctypes.c_double(resolution),
+        ctypes.c_double(dimension), ctypes.c_double(grm), ctypes.c_double(radius_scale),
+        ctypes.c_int(int(radius_type_indexed)), ctypes.c_int(int(coords_as_float)),
+        ctypes.c_int(int(box)), _p(coords, _f32p), _p(types, _i32p), _p(radii, _f32p),
+        _p(natoms, _i32p), _p(centers, _f32p), _p(quats, _f32p), _p(translations, _f32p),
+        g32, g64, _p(out, _f64p), ctypes.c_int(threads))
+    return out
+
+
+def backward_vector(coords, weights, radii, resolution, dimension, grad_out, *, grm=1.0,
+                    radius_scale=1.0, natoms=None, centers=None, quats=None,
+                    translations=None, box=True, coords_as_float=True, threads=0):
+    """(dL/dcoords [B,N,3], dL/dweights [B,N,T]) float64 for vector-typed atoms."""
+    coords, B, N, natoms, centers, quats, translations = _common(
+        coords, natoms, centers, quats, translations)
+    weights = _f32(weights)
+    T = weights.shape[2]
+    radii = _f32(radii, (T,))
+    D = points_per_side(resolution, dimension)
+    G, g32, g64 = _grad_ptrs(grad_out, (B, T, D, D, D))
+    gc = np.empty((B, N, 3), np.float64)
+    gw = np.empty((B, N, T), np.float64)
+    lib().orc_backward_vector(
+        ctypes.c_int(B), ctypes.c_int(N), ctypes.c_int(T), ctypes.c_double(resolution),
+        ctypes.c_double(dimension), ctypes.c_double(grm), ctypes.c_double(radius_scale),
+        ctypes.c_int(int(coords_as_float)), ctypes.c_int(int(box)), _p(coords, _f32p),
+        _p(weights, _f32p), _p(radii, _f32p), _p(natoms, _i32p), _p(centers, _f32p),
+        _p(quats, _f32p), _p(translations, _f32p), g32, g64, _p(gc, _f64p), _p(gw, _f64p),
+        ctypes.c_int(threads))
+    return gc, gw

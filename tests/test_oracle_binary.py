@@ -1,0 +1,94 @@
+"""Pins for the oracle's binary-occupancy mode (voxel = 1 iff some atom of the channel is within r)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1912_04822_amd import workloads
+
+
+@pytest.mark.parametrize("r,res", [(1.6, 0.5), (2.0, 0.5), (1.5, 0.5), (1.2, 0.25), (1.0, 0.75)])
+def test_single_atom_ball_count(r, res):
+    """One on-lattice atom: the ones are the lattice points of a ball, counted in integers."""
+    reach = int(np.ceil(r / res)) + 1
+    D = 2 * reach + 1
+    out = oracle.forward_binary(np.zeros((1, 1, 3), np.float32), np.array([r], np.float32), 1,
+                                res, (D - 1) * res, types=np.zeros((1, 1), np.int32))
+    assert set(np.unique(out)) <= {0.0, 1.0}
+    # exact rational test: (i^2+j^2+k^2) * res^2 <= r^2, with r the float value
+    from fractions import Fraction
+    r2 = Fraction(float(np.float32(r))) ** 2
+    res2 = Fraction(res) ** 2
+    n = sum(1 for i in range(-reach, reach + 1) for j in range(-reach, reach + 1)
+            for k in range(-reach, reach + 1) if (i * i + j * j + k * k) * res2 <= r2)
+    assert int(out.sum()) == n
+    assert out[0, 0, reach, reach, reach] == 1.0
+
+
+def test_box_equals_brute_force_and_or_not_count():
+    for w in (workloads.tiny(), workloads.ragged_small()):
+        kw = dict(types=w.types, natoms=w.extra.get("natoms"), centers=w.centers, quats=w.quats,
+                  translations=w.translations)
+        a = oracle.forward_binary(w.coords, w.radii, w.T, w.resolution, w.dimension, box=True, **kw)
+        b = oracle.forward_binary(w.coords, w.radii, w.T, w.resolution, w.dimension, box=False,
+                                  **kw)
+        assert np.array_equal(a, b)
+        assert set(np.unique(a)) == {0.0, 1.0}      # overlaps saturate at 1
+
+
+def test_matches_dense_numpy_distance_test_away_from_knife_edges():
+    w = workloads.ragged_small()
+    nat = w.extra["natoms"]
+    out = oracle.forward_binary(w.coords, w.radii, w.T, w.resolution, w.dimension, types=w.types,
+                                natoms=nat, centers=w.centers, quats=w.quats,
+                                translations=w.translations)
+    pos = oracle.transform(w.coords, w.centers, w.quats, w.translations).astype(np.float64)
+    ax = np.arange(w.D) * w.resolution - 0.5 * (w.D - 1) * w.resolution
+    checked = 0
+    for b in range(w.B):
+        inside = np.zeros((w.T, w.D, w.D, w.D), bool)
+        edge = np.zeros_like(inside)
+        for a in range(int(nat[b])):
+            t = int(w.types[b, a])
+            if t < 0 or t >= w.T:
+                continue
+            d2 = ((w.centers[b, 0] + ax)[:, None, None] - pos[b, a, 0]) ** 2 \
+                + ((w.centers[b, 1] + ax)[None, :, None] - pos[b, a, 1]) ** 2 \
+                + ((w.centers[b, 2] + ax)[None, None, :] - pos[b, a, 2]) ** 2
+            r2 = float(w.radii[t]) ** 2
+            inside[t] |= d2 <= r2
+            edge[t] |= np.abs(d2 - r2) < 1e-4
+        ok = ~edge
+        assert np.array_equal(out[b][ok] == 1.0, inside[ok])
+        checked += int(ok.sum())
+    assert checked > 0.99 * out.size
+
+
+def test_monotone_in_radius_and_consistent_with_real_mode():
+    w = workloads.tiny()
+    small = oracle.forward_binary(w.coords, w.radii, w.T, w.resolution, w.dimension, types=w.types)
+    big = oracle.forward_binary(w.coords, w.radii, w.T, w.resolution, w.dimension, types=w.types,
+                                radius_scale=1.2)
+    assert (big >= small).all() and big.sum() > small.sum()
+    # radius_scale multiplies the radius: same as scaled radii (1.25 * r exact in float here)
+    r2 = (w.radii * np.float32(1.25)).astype(np.float32)
+    a = oracle.forward_binary(w.coords, w.radii, w.T, w.resolution, w.dimension, types=w.types,
+                              radius_scale=1.25)
+    b = oracle.forward_binary(w.coords, r2, w.T, w.resolution, w.dimension, types=w.types)
+    assert np.array_equal(a, b)
+    # a voxel within r of an atom has real-mode density >= rho(1) = exp(-2) (grm = 1)
+    real = oracle.forward_index(w.coords, w.types, w.radii, w.T, w.resolution, w.dimension,
+                                out_dtype=np.float64)
+    assert (real[small == 1.0] >= np.exp(-2.0) - 1e-6).all()
+    # and a voxel with zero real density is never occupied
+    assert (small[real == 0.0] == 0.0).all()
+
+
+def test_vector_typed_binary_uses_positive_weights_and_channel_radii():
+    w = workloads.ragged_small()
+    types = np.clip(w.types, 0, w.T - 1)
+    onehot = np.eye(w.T, dtype=np.float32)[types]
+    kw = dict(centers=w.centers, quats=w.quats, translations=w.translations)
+    a = oracle.forward_binary(w.coords, w.radii, w.T, w.resolution, w.dimension, types=types, **kw)
+    b = oracle.forward_binary(w.coords, w.radii, w.T, w.resolution, w.dimension, weights=onehot,
+                              **kw)
+    assert np.array_equal(a, b)

@@ -1,0 +1,168 @@
+/*
+ * molgrid_hip.h -- C ABI of the MI355X (gfx950) atom-to-grid library.
+ *
+ * The calls follow the problem statement of the libmolgrid paper (arXiv
+ * 1912.04822): a GridMaker is built from (resolution, dimension, binary,
+ * radius_type_indexed, radius_scale, gaussian_radius_multiple) -- GridMaker
+ * constructor listing -- and its forward call turns a batch of typed atoms,
+ * each example with an optional rotation/translation (Transformations
+ * section), into an N x C x L x W x H float grid (GridMaker usage figure);
+ * backward turns a gradient on that grid into atomic gradients (GridMaker
+ * section).
+ *
+ * Conventions for every call
+ *   - Returns MG_OK (0) or a negative MG_E* code; nothing throws.  Arguments
+ *     are checked on the host before anything is enqueued.
+ *   - All array arguments are DEVICE pointers owned by the caller.  The
+ *     library allocates nothing: outputs and the workspace are the caller's.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without synchronising.  Calls that
+ *     share a workspace must be ordered by the caller (same stream).
+ *   - Layouts are dense row-major.  A grid is [B][T][D][D][D] float with the
+ *     last (z) index contiguous; grid point (i,j,k) of example b sits at
+ *       centers[b] - (D-1)*resolution/2 + resolution*(i,j,k),
+ *     D = round(dimension/resolution) + 1 points per side, both ends included.
+ *   - natoms[b] (optional) limits example b to its first natoms[b] atoms.
+ *     Atoms with a type outside [0,T), a non-positive radius or a non-finite
+ *     coordinate contribute nothing and receive zero gradient.
+ *   - centers == NULL means the origin, quats == NULL the identity,
+ *     translations == NULL zero.  A quaternion is (w,x,y,z) and need not be
+ *     normalised; (0,0,0,0) means no rotation.
+ *   - Device-side data errors (bad type ids, NaNs) are skipped, not reported.
+ */
+#ifndef MOLGRID_HIP_H
+#define MOLGRID_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MG_OK = 0,
+    MG_ENULL = -1,       /* a required pointer is NULL                          */
+    MG_ESHAPE = -2,      /* B, N, T < 1, D outside [1, MG_MAX_POINTS], overflow */
+    MG_EPARAM = -3,      /* non-finite / non-positive resolution, scale, grm... */
+    MG_EWORKSPACE = -4,  /* workspace NULL, misaligned or too small             */
+    MG_EHIP = -5,        /* the HIP runtime refused a launch (see mg_last_hip_error) */
+    MG_EMODE = -6,       /* call not defined for this GridMaker (e.g. backward in binary mode) */
+    MG_EALIGN = -7       /* a float array is not 4-byte / workspace not 16-byte aligned */
+};
+
+#define MG_MAX_POINTS 1024      /* largest supported D (points per side) */
+
+typedef struct mg_gridmaker mg_gridmaker;   /* opaque, host-side, immutable after create */
+
+/*
+ * GridMaker constructor (constructor listing; defaults there are 0.5, 23.5,
+ * 0, 0, 1.0, 1.0).  binary: density is a 0/1 indicator of a voxel lying
+ * within radius_scale*radius of an atom instead of the Gaussian-plus-
+ * quadratic density.  radius_type_indexed: `radii` is [T], looked up by type
+ * id; otherwise it is [B][N], one radius per atom (index types only).
+ * gaussian_radius_multiple (grm): the Gaussian runs to grm*r, the quadratic
+ * tail reaches zero at r*(1+2grm^2)/(2grm).
+ * The handle lives until mg_gridmaker_destroy; *out is set only on MG_OK.
+ */
+int mg_gridmaker_create(mg_gridmaker **out, float resolution, float dimension,
+                        int binary, int radius_type_indexed, float radius_scale,
+                        float gaussian_radius_multiple);
+void mg_gridmaker_destroy(mg_gridmaker *gm);
+
+/* D = round(dimension/resolution) + 1. */
+int mg_gridmaker_points_per_side(const mg_gridmaker *gm, int *D);
+
+/*
+ * Bytes of caller-provided device workspace a forward/backward call with this
+ * (B, N, T) needs (transformed, culled, channel-binned atom records).  The
+ * workspace must be 16-byte aligned; its contents are scratch.
+ */
+int mg_workspace_bytes(const mg_gridmaker *gm, int B, int N, int T, size_t *bytes);
+
+/*
+ * Transform alone (Transformations section):
+ *   out[b][a] = R(quats[b]) (coords[b][a] - centers[b]) + centers[b] + translations[b]
+ * coords, out: [B][N][3] float.  The arithmetic is double, in a fixed order,
+ * rounded once to float: these are the coordinates forward/backward use.
+ */
+int mg_transform_forward(int B, int N, const float *coords, const float *centers,
+                         const float *quats, const float *translations,
+                         float *out, void *stream);
+
+/*
+ * Forward, index types (GridMaker section):
+ *   out[b][t][p] = sum over atoms a of example b with types[b][a] == t of
+ *                  rho(|p - x'_a| / r_a),         r_a = radius_scale * radius
+ * or, for a binary GridMaker, 1.0f if any such atom has |p - x'_a| <= r_a
+ * (float arithmetic, fixed order) else 0.0f.
+ * coords [B][N][3] float; types [B][N] int32; radii [T] or [B][N] float (see
+ * create); out [B][T][D][D][D] float, every element written (no need to
+ * zero it first).
+ */
+int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T,
+                     const float *coords, const int32_t *types, const float *radii,
+                     const int32_t *natoms, const float *centers, const float *quats,
+                     const float *translations, float *out,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Forward, vector types (Atom Typing section: a type may be a vector):
+ *   out[b][t][p] = sum_a weights[b][a][t] * rho(|p - x'_a| / (radius_scale * radii[t]))
+ * weights [B][N][T] float; radii [T] float, indexed by type id (the GridMaker
+ * must have radius_type_indexed set).  Binary GridMaker: 1.0f if any atom
+ * with weights[b][a][t] > 0 lies within radius_scale*radii[t].
+ */
+int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T,
+                      const float *coords, const float *weights, const float *radii,
+                      const int32_t *natoms, const float *centers, const float *quats,
+                      const float *translations, float *out,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Backward, index types ("computes atomic gradients", GridMaker section):
+ * with L = sum(grad_out * out),
+ *   grad_coords[b][a] = dL / d coords[b][a]
+ *     = R(q_b)^T  sum_p grad_out[b][t_a][p] rho'(d/r_a) (x'_a - p) / (r_a d)
+ * grad_out [B][T][D][D][D] float; grad_coords [B][N][3] float, every element
+ * written (zero for skipped atoms).  Not defined for a binary GridMaker
+ * (MG_EMODE).
+ */
+int mg_backward_index(const mg_gridmaker *gm, int B, int N, int T,
+                      const float *coords, const int32_t *types, const float *radii,
+                      const int32_t *natoms, const float *centers, const float *quats,
+                      const float *translations, const float *grad_out,
+                      float *grad_coords,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Backward, vector types: grad_coords [B][N][3] and grad_weights [B][N][T]
+ * (either may be NULL, not both):
+ *   grad_coords[b][a]     = R^T sum_t w[b][a][t] sum_p G[b][t][p] rho'(d/r_t)(x'_a - p)/(r_t d)
+ *   grad_weights[b][a][t] = sum_p G[b][t][p] rho(d/r_t)
+ */
+int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T,
+                       const float *coords, const float *weights, const float *radii,
+                       const int32_t *natoms, const float *centers, const float *quats,
+                       const float *translations, const float *grad_out,
+                       float *grad_coords, float *grad_weights,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* Text for an MG_* code (static storage). */
+const char *mg_strerror(int code);
+
+/* hipError_t (as int) of the last launch this thread's call refused, 0 if none. */
+int mg_last_hip_error(void);
+
+/*
+ * Tuning knobs of the forward kernel, for measurement only (results do not
+ * depend on them).  key "xcd_map": 0 = workgroup i takes tile group i;
+ * 1 = each of the 8 XCDs takes one contiguous eighth of the output.
+ * Returns MG_EPARAM for an unknown key or value.
+ */
+int mg_set_option(const char *key, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOLGRID_HIP_H */

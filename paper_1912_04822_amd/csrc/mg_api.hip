@@ -1,0 +1,255 @@
+// The C ABI (include/molgrid_hip.h): argument validation on the host, then the
+// launches.  No allocation, no synchronisation, no host<->device copies.
+#include "../../include/molgrid_hip.h"
+
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "mg_common.h"
+
+struct mg_gridmaker {
+    mg::GridSpec gs;
+    float dimension;
+    float grm;
+};
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+int g_xcd_map = 1;
+
+bool finite_pos(float v) { return std::isfinite(v) && v > 0.0f; }
+
+int check_shape(const mg_gridmaker *gm, int B, int N, int T)
+{
+    if (!gm) return MG_ENULL;
+    if (B < 1 || N < 1 || T < 1) return MG_ESHAPE;
+    if (B > 65535) return MG_ESHAPE;                      // grid.y of the per-example launches
+    const long long D = gm->gs.D;
+    const long long tiles = (long long)B * T * D * D;     // upper bound on forward tiles
+    if (tiles > 0x7fffffffLL) return MG_ESHAPE;
+    if ((long long)B * N > 0x7fffffffLL / 32) return MG_ESHAPE;
+    return MG_OK;
+}
+
+int check_workspace(const mg_gridmaker *gm, int B, int N, int T, void *ws, size_t ws_bytes)
+{
+    (void)gm;
+    if (!ws) return MG_EWORKSPACE;
+    if (((uintptr_t)ws & 15u) != 0) return MG_EWORKSPACE;
+    if (ws_bytes < mg::workspace_bytes(B, N, T)) return MG_EWORKSPACE;
+    return MG_OK;
+}
+
+bool misaligned4(const void *p) { return p && (((uintptr_t)p & 3u) != 0); }
+
+int hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return MG_OK;
+    g_last_hip_error = (int)e;
+    return MG_EHIP;
+}
+
+mg::Batch make_batch(int B, int N, int T, const float *coords, const int32_t *types,
+                     const float *weights, const float *radii, const int32_t *natoms,
+                     const float *centers, const float *quats, const float *translations)
+{
+    mg::Batch bt;
+    bt.B = B; bt.N = N; bt.T = T;
+    bt.coords = coords; bt.types = types; bt.weights = weights; bt.radii = radii;
+    bt.natoms = natoms; bt.centers = centers; bt.quats = quats; bt.translations = translations;
+    return bt;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mg_gridmaker_create(mg_gridmaker **out, float resolution, float dimension, int binary,
+                        int radius_type_indexed, float radius_scale, float gaussian_radius_multiple)
+{
+    if (!out) return MG_ENULL;
+    if (!finite_pos(resolution) || !std::isfinite(dimension) || dimension < 0.0f ||
+        !finite_pos(radius_scale) || !finite_pos(gaussian_radius_multiple))
+        return MG_EPARAM;
+    const double dd = std::floor((double)dimension / (double)resolution + 0.5) + 1.0;
+    if (!(dd >= 1.0) || dd > (double)MG_MAX_POINTS) return MG_ESHAPE;
+    mg_gridmaker *gm = new (std::nothrow) mg_gridmaker;
+    if (!gm) return MG_EHIP;
+    const int D = (int)dd;
+    const double g = (double)gaussian_radius_multiple;
+    const double c = (1.0 + 2.0 * g * g) / (2.0 * g);
+    gm->gs.res = resolution;
+    gm->gs.half = (float)(0.5 * (D - 1) * (double)resolution);
+    gm->gs.inv_res = (float)(1.0 / (double)resolution);
+    gm->gs.D = D;
+    gm->gs.binary = binary ? 1 : 0;
+    gm->gs.radius_type_indexed = radius_type_indexed ? 1 : 0;
+    gm->gs.radius_scale = radius_scale;
+    gm->gs.g2 = (float)(g * g);
+    gm->gs.c = (float)c;
+    gm->gs.c2 = (float)(c * c);
+    gm->gs.A = (float)(4.0 * g * g * std::exp(-2.0 * g * g));
+    gm->dimension = dimension;
+    gm->grm = gaussian_radius_multiple;
+    *out = gm;
+    return MG_OK;
+}
+
+void mg_gridmaker_destroy(mg_gridmaker *gm) { delete gm; }
+
+int mg_gridmaker_points_per_side(const mg_gridmaker *gm, int *D)
+{
+    if (!gm || !D) return MG_ENULL;
+    *D = gm->gs.D;
+    return MG_OK;
+}
+
+int mg_workspace_bytes(const mg_gridmaker *gm, int B, int N, int T, size_t *bytes)
+{
+    if (!bytes) return MG_ENULL;
+    const int rc = check_shape(gm, B, N, T);
+    if (rc != MG_OK) return rc;
+    *bytes = mg::workspace_bytes(B, N, T);
+    return MG_OK;
+}
+
+int mg_transform_forward(int B, int N, const float *coords, const float *centers,
+                         const float *quats, const float *translations, float *out, void *stream)
+{
+    if (!coords || !out) return MG_ENULL;
+    if (B < 1 || N < 1 || B > 65535) return MG_ESHAPE;
+    if (misaligned4(coords) || misaligned4(out) || misaligned4(centers) || misaligned4(quats) ||
+        misaligned4(translations))
+        return MG_EALIGN;
+    return hip_status(mg::launch_transform(B, N, coords, centers, quats, translations, out,
+                                           (hipStream_t)stream));
+}
+
+int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
+                     const int32_t *types, const float *radii, const int32_t *natoms,
+                     const float *centers, const float *quats, const float *translations,
+                     float *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!gm || !coords || !types || !radii || !out) return MG_ENULL;
+    int rc = check_shape(gm, B, N, T);
+    if (rc != MG_OK) return rc;
+    if (misaligned4(coords) || misaligned4(types) || misaligned4(radii) || misaligned4(out) ||
+        misaligned4(natoms) || misaligned4(centers) || misaligned4(quats) ||
+        misaligned4(translations))
+        return MG_EALIGN;
+    rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
+    if (rc != MG_OK) return rc;
+    const mg::Batch bt = make_batch(B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
+                                    translations);
+    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T);
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
+    if (rc != MG_OK) return rc;
+    return hip_status(mg::launch_forward(gm->gs, bt, ws, out, g_xcd_map, (hipStream_t)stream));
+}
+
+int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
+                      const float *weights, const float *radii, const int32_t *natoms,
+                      const float *centers, const float *quats, const float *translations,
+                      float *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!gm || !coords || !weights || !radii || !out) return MG_ENULL;
+    if (!gm->gs.radius_type_indexed) return MG_EMODE;     // vector types need radii per type
+    int rc = check_shape(gm, B, N, T);
+    if (rc != MG_OK) return rc;
+    if (misaligned4(coords) || misaligned4(weights) || misaligned4(radii) || misaligned4(out) ||
+        misaligned4(natoms) || misaligned4(centers) || misaligned4(quats) ||
+        misaligned4(translations))
+        return MG_EALIGN;
+    rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
+    if (rc != MG_OK) return rc;
+    const mg::Batch bt = make_batch(B, N, T, coords, nullptr, weights, radii, natoms, centers,
+                                    quats, translations);
+    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T);
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
+    if (rc != MG_OK) return rc;
+    return hip_status(mg::launch_forward(gm->gs, bt, ws, out, g_xcd_map, (hipStream_t)stream));
+}
+
+int mg_backward_index(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
+                      const int32_t *types, const float *radii, const int32_t *natoms,
+                      const float *centers, const float *quats, const float *translations,
+                      const float *grad_out, float *grad_coords, void *workspace,
+                      size_t workspace_bytes, void *stream)
+{
+    if (!gm || !coords || !types || !radii || !grad_out || !grad_coords) return MG_ENULL;
+    if (gm->gs.binary) return MG_EMODE;
+    int rc = check_shape(gm, B, N, T);
+    if (rc != MG_OK) return rc;
+    if (misaligned4(coords) || misaligned4(types) || misaligned4(radii) || misaligned4(grad_out) ||
+        misaligned4(grad_coords) || misaligned4(natoms) || misaligned4(centers) ||
+        misaligned4(quats) || misaligned4(translations))
+        return MG_EALIGN;
+    rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
+    if (rc != MG_OK) return rc;
+    const mg::Batch bt = make_batch(B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
+                                    translations);
+    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T);
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, nullptr, (hipStream_t)stream));
+    if (rc != MG_OK) return rc;
+    return hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, nullptr,
+                                          (hipStream_t)stream));
+}
+
+int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
+                       const float *weights, const float *radii, const int32_t *natoms,
+                       const float *centers, const float *quats, const float *translations,
+                       const float *grad_out, float *grad_coords, float *grad_weights,
+                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!gm || !coords || !weights || !radii || !grad_out) return MG_ENULL;
+    if (!grad_coords && !grad_weights) return MG_ENULL;
+    if (gm->gs.binary || !gm->gs.radius_type_indexed) return MG_EMODE;
+    int rc = check_shape(gm, B, N, T);
+    if (rc != MG_OK) return rc;
+    if (misaligned4(coords) || misaligned4(weights) || misaligned4(radii) ||
+        misaligned4(grad_out) || misaligned4(grad_coords) || misaligned4(grad_weights) ||
+        misaligned4(natoms) || misaligned4(centers) || misaligned4(quats) ||
+        misaligned4(translations))
+        return MG_EALIGN;
+    rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
+    if (rc != MG_OK) return rc;
+    const mg::Batch bt = make_batch(B, N, T, coords, nullptr, weights, radii, natoms, centers,
+                                    quats, translations);
+    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T);
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, grad_weights, (hipStream_t)stream));
+    if (rc != MG_OK) return rc;
+    return hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, grad_weights,
+                                          (hipStream_t)stream));
+}
+
+const char *mg_strerror(int code)
+{
+    switch (code) {
+    case MG_OK: return "ok";
+    case MG_ENULL: return "a required pointer is NULL";
+    case MG_ESHAPE: return "bad shape: B, N, T must be >= 1, B <= 65535, 1 <= D <= 1024, sizes must fit";
+    case MG_EPARAM: return "bad parameter: resolution, radius_scale and gaussian_radius_multiple must be finite and positive";
+    case MG_EWORKSPACE: return "workspace is NULL, not 16-byte aligned, or smaller than mg_workspace_bytes";
+    case MG_EHIP: return "the HIP runtime refused a launch (mg_last_hip_error has the hipError_t)";
+    case MG_EMODE: return "call not defined for this GridMaker (binary backward, or vector types without radius_type_indexed)";
+    case MG_EALIGN: return "an array argument is not 4-byte aligned";
+    default: return "unknown error code";
+    }
+}
+
+int mg_last_hip_error(void) { return g_last_hip_error; }
+
+int mg_set_option(const char *key, int value)
+{
+    if (!key) return MG_ENULL;
+    if (std::strcmp(key, "xcd_map") == 0) {
+        if (value != 0 && value != 1) return MG_EPARAM;
+        g_xcd_map = value;
+        return MG_OK;
+    }
+    return MG_EPARAM;
+}
+
+}  // extern "C"

@@ -1,0 +1,218 @@
+// Step 6 of the path: the backward pass (GridMaker section: "computes atomic
+// gradients").  With L = sum G*out, u = x'_a - p, d = |u|, x = d/r:
+//   dL/dx'_a = sum_p G[p] rho'(x) u / (r d)
+//            = (1/r^2) sum_p G[p] f(x^2) u,
+//   f = -4 exp(-2x^2)            x <= g      (rho' = -4x exp(-2x^2))
+//     = 2A (1 - c/x)             g < x < c   (rho' = 2A (x - c))
+//     = 0                        x >= c
+// (dividing rho' by x removes the square root from the Gaussian branch and makes
+// d = 0 contribute exactly 0 through u = 0).  The gradient with respect to the
+// caller's coordinates is R^T times that sum.
+//
+// One workgroup (4 wavefronts) per atom record: the 256 lanes spread over the
+// atom's cutoff box (x-planes x rows x 4-voxel z-segments), read the upstream
+// gradient with 16-byte loads, and the three partial sums are reduced with
+// wavefront shuffles, then across the wavefronts through LDS, in a fixed order.
+// Records are grouped by channel (and, within a channel, keep atom order), so
+// neighbouring workgroups read the same channel volume.
+#include "mg_common.h"
+
+namespace mg {
+
+namespace {
+
+struct BwdParams {
+    GridSpec gs;
+    const float4 *rec;
+    const int *idx;
+    const int2 *meta;
+    const float *rot;
+    const int32_t *types;
+    const float *weights;
+    const float *radii;
+    const float *centers;
+    const float *G;
+    float *grad_coords;
+    float *grad_weights;
+    int B, N, T;
+    float kexp;
+};
+
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+struct Box {
+    int ilo, jlo, seg0;
+    int np, nr, ns;
+};
+
+// grid points within `reach` of the atom along each axis, padded by 1e-3 steps
+__device__ inline bool atom_box(const GridSpec &gs, float reach, const float4 &a, float ox, float oy,
+                                float oz, Box &bx)
+{
+    const float hv = reach * gs.inv_res + 1.0e-3f;
+    const float fx = (a.x - ox) * gs.inv_res, fy = (a.y - oy) * gs.inv_res,
+                fz = (a.z - oz) * gs.inv_res;
+    const int D = gs.D;
+    const int ilo = max(0, (int)ceilf(fx - hv)), ihi = min(D - 1, (int)floorf(fx + hv));
+    const int jlo = max(0, (int)ceilf(fy - hv)), jhi = min(D - 1, (int)floorf(fy + hv));
+    const int klo = max(0, (int)ceilf(fz - hv)), khi = min(D - 1, (int)floorf(fz + hv));
+    bx.ilo = ilo; bx.jlo = jlo; bx.seg0 = klo >> 2;
+    bx.np = ihi - ilo + 1; bx.nr = jhi - jlo + 1; bx.ns = (khi >> 2) - (klo >> 2) + 1;
+    return bx.np > 0 && bx.nr > 0 && bx.ns > 0 && khi >= klo;
+}
+
+// Accumulate over one channel volume.  gsum: sum G f u (3), vsum: sum G rho.
+template <bool ALIGNED, bool WANT_VALUE>
+__device__ inline void reduce_channel(const BwdParams &p, const float *Gc, const float4 &a, float inv_r2,
+                                      const Box &bx, float ox, float oy, float oz, float &sx,
+                                      float &sy, float &sz, float &sv)
+{
+    const GridSpec &gs = p.gs;
+    const int D = gs.D;
+    const int per_plane = bx.nr * bx.ns;
+    const int slots = bx.np * per_plane;
+    const float inv_pp = 1.0f / (float)per_plane, inv_ns = 1.0f / (float)bx.ns;
+    for (int s = threadIdx.x; s < slots; s += blockDim.x) {
+        const int pi = (int)(((float)s + 0.5f) * inv_pp);
+        const int rem = s - pi * per_plane;
+        const int row = (int)(((float)rem + 0.5f) * inv_ns);
+        const int seg = rem - row * bx.ns;
+        const int i = bx.ilo + pi, j = bx.jlo + row, k4 = (bx.seg0 + seg) << 2;
+        const float *src = Gc + ((size_t)i * D + j) * D + k4;
+        float gv[4];
+        if (ALIGNED) {
+            const float4 g4 = *reinterpret_cast<const float4 *>(src);
+            gv[0] = g4.x; gv[1] = g4.y; gv[2] = g4.z; gv[3] = g4.w;
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) gv[u] = (k4 + u < D) ? src[u] : 0.0f;
+        }
+        const float ux = a.x - (ox + (float)i * gs.res);
+        const float uy = a.y - (oy + (float)j * gs.res);
+        const float b2 = ux * ux + uy * uy;
+        float fsum = 0.0f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float uz = a.z - (oz + (float)(k4 + u) * gs.res);
+            const float x2 = fmaf(uz, uz, b2) * inv_r2;
+            const float e = __builtin_amdgcn_exp2f(x2 * p.kexp);
+            const float rs = __builtin_amdgcn_rsqf(x2);
+            float f = x2 <= gs.g2 ? -4.0f * e : 2.0f * gs.A * (1.0f - gs.c * rs);
+            f = x2 < gs.c2 ? f : 0.0f;
+            const float gf = gv[u] * f;
+            fsum += gf;
+            sz = fmaf(gf, uz, sz);
+            if (WANT_VALUE) {
+                const float tl = x2 * rs - gs.c;            // x - c
+                float rho = x2 <= gs.g2 ? e : gs.A * tl * tl;
+                rho = x2 < gs.c2 ? rho : 0.0f;
+                sv = fmaf(gv[u], rho, sv);
+            }
+        }
+        sx = fmaf(fsum, ux, sx);
+        sy = fmaf(fsum, uy, sy);
+    }
+}
+
+// Sum v over the block; the result is valid in thread 0.  s_part: [4] floats.
+__device__ inline float block_sum(float v, float *s_part)
+{
+    v = wave_sum(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane == 0) s_part[wave] = v;
+    __syncthreads();
+    return ((s_part[0] + s_part[1]) + s_part[2]) + s_part[3];
+}
+
+template <bool VECTOR, bool ALIGNED>
+__global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
+{
+    __shared__ float s_part[4];
+    const GridSpec &gs = p.gs;
+    const int b = blockIdx.y, slot = blockIdx.x;
+    const int N = p.N, T = p.T, D = gs.D;
+    const int2 last = p.meta[(size_t)b * T + (VECTOR ? 0 : T - 1)];
+    if (slot >= last.x + last.y) return;            // uniform for the block
+    const float4 a = p.rec[(size_t)b * N + slot];
+    if (!(a.w > 0.0f)) return;                      // dead record: the prep kernel wrote its zeros
+    const int ai = p.idx[(size_t)b * N + slot];
+    const size_t D3 = (size_t)D * D * D;
+    const float ox = (p.centers ? p.centers[3 * b + 0] : 0.0f) - gs.half;
+    const float oy = (p.centers ? p.centers[3 * b + 1] : 0.0f) - gs.half;
+    const float oz = (p.centers ? p.centers[3 * b + 2] : 0.0f) - gs.half;
+
+    float tx = 0.0f, ty = 0.0f, tz = 0.0f;          // gradient in the transformed frame
+    if (!VECTOR) {
+        const int t = p.types[(size_t)b * N + ai];
+        const float r = a.w;
+        Box bx;
+        float sx = 0.0f, sy = 0.0f, sz = 0.0f, sv = 0.0f;
+        if (atom_box(gs, r * gs.c, a, ox, oy, oz, bx))
+            reduce_channel<ALIGNED, false>(p, p.G + ((size_t)b * T + t) * D3, a, 1.0f / (r * r), bx, ox,
+                                           oy, oz, sx, sy, sz, sv);
+        const float inv_r2 = 1.0f / (r * r);
+        tx = block_sum(sx, s_part) * inv_r2;
+        ty = block_sum(sy, s_part) * inv_r2;
+        tz = block_sum(sz, s_part) * inv_r2;
+    } else {
+        for (int t = 0; t < T; ++t) {
+            const float r = gs.radius_scale * p.radii[t];
+            const float w = p.weights[((size_t)b * N + ai) * T + t];
+            float sx = 0.0f, sy = 0.0f, sz = 0.0f, sv = 0.0f;
+            Box bx;
+            if (r > 0.0f && atom_box(gs, r * gs.c, a, ox, oy, oz, bx))
+                reduce_channel<ALIGNED, true>(p, p.G + ((size_t)b * T + t) * D3, a, 1.0f / (r * r), bx,
+                                              ox, oy, oz, sx, sy, sz, sv);
+            const float inv_r2 = r > 0.0f ? 1.0f / (r * r) : 0.0f;
+            if (p.grad_coords) {
+                tx = fmaf(w * inv_r2, block_sum(sx, s_part), tx);
+                ty = fmaf(w * inv_r2, block_sum(sy, s_part), ty);
+                tz = fmaf(w * inv_r2, block_sum(sz, s_part), tz);
+            }
+            if (p.grad_weights) {
+                const float val = block_sum(sv, s_part);
+                if (threadIdx.x == 0) p.grad_weights[((size_t)b * N + ai) * T + t] = val;
+            }
+        }
+    }
+    if (threadIdx.x == 0 && p.grad_coords) {
+        const float *R = p.rot + b * 12;
+        float *o = p.grad_coords + ((size_t)b * N + ai) * 3;
+        o[0] = (R[0] * tx + R[3] * ty) + R[6] * tz;
+        o[1] = (R[1] * tx + R[4] * ty) + R[7] * tz;
+        o[2] = (R[2] * tx + R[5] * ty) + R[8] * tz;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
+                           const float *grad_out, float *grad_coords, float *grad_weights,
+                           hipStream_t stream)
+{
+    BwdParams p;
+    p.gs = gs;
+    p.rec = ws.rec; p.idx = ws.idx; p.meta = ws.meta; p.rot = ws.rot;
+    p.types = bt.types; p.weights = bt.weights; p.radii = bt.radii; p.centers = bt.centers;
+    p.G = grad_out; p.grad_coords = grad_coords; p.grad_weights = grad_weights;
+    p.B = bt.B; p.N = bt.N; p.T = bt.T;
+    p.kexp = -2.8853900817779268f;
+    const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)grad_out & 15u) == 0);
+    const dim3 grd(bt.N, bt.B), blk(256);
+    if (bt.weights) {
+        if (aligned) hipLaunchKernelGGL((backward_kernel<true, true>), grd, blk, 0, stream, p);
+        else hipLaunchKernelGGL((backward_kernel<true, false>), grd, blk, 0, stream, p);
+    } else {
+        if (aligned) hipLaunchKernelGGL((backward_kernel<false, true>), grd, blk, 0, stream, p);
+        else hipLaunchKernelGGL((backward_kernel<false, false>), grd, blk, 0, stream, p);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace mg

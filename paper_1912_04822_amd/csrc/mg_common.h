@@ -1,0 +1,95 @@
+// Internal declarations shared by the HIP translation units of the library.
+// Not part of the C ABI (that is include/molgrid_hip.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace mg {
+
+// ---------------------------------------------------------------------------
+// GridMaker: host-side, immutable.  Constants of the density (GridMaker
+// section of the paper): with x = d/r and g = gaussian_radius_multiple,
+//   rho(x) = exp(-2 x^2)           x <= g
+//          = A (x - c)^2           g < x < c,   c = (1+2g^2)/(2g)
+//          = 0                     x >= c
+// A = 4 g^2 exp(-2 g^2) makes value and slope continuous at x = g: a Gaussian
+// exp(-a x^2) meets a quadratic with a double root at c smoothly only when
+// c = g + 1/(a g), which matches the paper's c for a = 2.
+// ---------------------------------------------------------------------------
+struct GridSpec {
+    float res;          // grid spacing
+    float half;         // (D-1)*res/2, rounded once from double
+    float inv_res;
+    int   D;            // points per side
+    int   binary;
+    int   radius_type_indexed;
+    float radius_scale;
+    float g2;           // g^2            (Gaussian region is x^2 <= g2)
+    float c;            // cutoff multiple (1+2g^2)/(2g)
+    float c2;           // c^2
+    float A;            // tail coefficient
+};
+
+// ---------------------------------------------------------------------------
+// Workspace layout (device, caller-provided, 16-byte aligned):
+//   rec   [B][N] float4   transformed atom records {x', y', z', r}; r = 0 marks
+//                         an atom that contributes nothing.  Index types: the
+//                         records of example b are grouped by type, group t
+//                         starting at meta[b][t].x with meta[b][t].y entries,
+//                         in atom order.  Vector types: one group per example
+//                         (meta[b][0]), r unused (1 = live, 0 = dead).
+//   idx   [B][N] int32    original atom index of each record
+//   meta  [B][T] int2     {first record, number of records}
+//   rot   [B][12] float   rotation matrix rows (9 used), for the backward pass
+// ---------------------------------------------------------------------------
+struct Workspace {
+    float4 *rec;
+    int    *idx;
+    int2   *meta;
+    float  *rot;
+};
+
+size_t workspace_bytes(int B, int N, int T);
+Workspace carve_workspace(void *base, int B, int N, int T);
+
+struct Batch {
+    int B, N, T;
+    const float   *coords;        // [B][N][3]
+    const int32_t *types;         // [B][N] or null (vector types)
+    const float   *weights;       // [B][N][T] or null (index types)
+    const float   *radii;         // [T] or [B][N]
+    const int32_t *natoms;        // [B] or null
+    const float   *centers;       // [B][3] or null
+    const float   *quats;         // [B][4] or null
+    const float   *translations;  // [B][3] or null
+};
+
+// Tile geometry of the forward kernel: every wavefront owns `rows` consecutive
+// z-rows of one x-plane of one channel (a contiguous run of rows*D floats).
+struct Tiling {
+    int rows;           // rows per tile
+    int strips;         // tiles per x-plane = ceil(D / rows)
+    int pitch;          // floats per row in LDS (D rounded up to 4)
+    long long units;    // B*T*D*strips tiles in total
+};
+Tiling make_tiling(int B, int T, int D);
+
+constexpr int kTileFloats = 2304;       // LDS floats per wavefront tile (9216 B)
+constexpr int kWavesPerGroup = 4;
+
+// Launchers (each enqueues on `stream`, returns the hipError_t of the launch).
+hipError_t launch_transform(int B, int N, const float *coords, const float *centers,
+                            const float *quats, const float *translations, float *out,
+                            hipStream_t stream);
+hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
+                       float *grad_coords_to_clear, float *grad_weights_to_clear,
+                       hipStream_t stream);
+hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
+                          float *out, int xcd_map, hipStream_t stream);
+hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
+                           const float *grad_out, float *grad_coords, float *grad_weights,
+                           hipStream_t stream);
+
+}  // namespace mg

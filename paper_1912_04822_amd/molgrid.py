@@ -1,0 +1,235 @@
+"""Thin ctypes binding over the C-ABI HIP library (``include/molgrid_hip.h``).
+
+Argument marshalling only: every step of the path runs in the library's
+kernels.  PyTorch supplies device memory and the stream.  There is no CPU
+fallback: if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmolgrid_hip.so")
+
+MG_OK = 0
+EXPORTS = [
+    "mg_gridmaker_create", "mg_gridmaker_destroy", "mg_gridmaker_points_per_side",
+    "mg_workspace_bytes", "mg_transform_forward", "mg_forward_index", "mg_forward_vector",
+    "mg_backward_index", "mg_backward_vector", "mg_strerror", "mg_last_hip_error",
+    "mg_set_option",
+]
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+class MolgridError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s: %s (code %d)" % (where, strerror(code), code))
+
+
+def lib() -> ctypes.CDLL:
+    """Load libmolgrid_hip.so (built by ``paper_1912_04822_amd.build``); raise if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "HIP library not built: %s (run python -m paper_1912_04822_amd.build)" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ci, cf, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+        L.mg_gridmaker_create.restype = ci
+        L.mg_gridmaker_create.argtypes = [ctypes.POINTER(vp), cf, cf, ci, ci, cf, cf]
+        L.mg_gridmaker_destroy.restype = None
+        L.mg_gridmaker_destroy.argtypes = [vp]
+        L.mg_gridmaker_points_per_side.restype = ci
+        L.mg_gridmaker_points_per_side.argtypes = [vp, ctypes.POINTER(ci)]
+        L.mg_workspace_bytes.restype = ci
+        L.mg_workspace_bytes.argtypes = [vp, ci, ci, ci, ctypes.POINTER(sz)]
+        L.mg_transform_forward.restype = ci
+        L.mg_transform_forward.argtypes = [ci, ci, vp, vp, vp, vp, vp, vp]
+        L.mg_forward_index.restype = ci
+        L.mg_forward_index.argtypes = [vp, ci, ci, ci] + [vp] * 8 + [vp, sz, vp]
+        L.mg_forward_vector.restype = ci
+        L.mg_forward_vector.argtypes = [vp, ci, ci, ci] + [vp] * 8 + [vp, sz, vp]
+        L.mg_backward_index.restype = ci
+        L.mg_backward_index.argtypes = [vp, ci, ci, ci] + [vp] * 9 + [vp, sz, vp]
+        L.mg_backward_vector.restype = ci
+        L.mg_backward_vector.argtypes = [vp, ci, ci, ci] + [vp] * 10 + [vp, sz, vp]
+        L.mg_strerror.restype = ctypes.c_char_p
+        L.mg_strerror.argtypes = [ci]
+        L.mg_last_hip_error.restype = ci
+        L.mg_last_hip_error.argtypes = []
+        L.mg_set_option.restype = ci
+        L.mg_set_option.argtypes = [ctypes.c_char_p, ci]
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().mg_strerror(int(code)).decode()
+
+
+def set_option(key: str, value: int) -> None:
+    rc = lib().mg_set_option(key.encode(), int(value))
+    if rc != MG_OK:
+        raise MolgridError(rc, "mg_set_option")
+
+
+def _ptr(t: Optional[torch.Tensor], dtype, name: str, shape=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("%s must be a device tensor" % name)
+    if t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def mg_transform_forward(coords, centers=None, quats=None, translations=None, out=None):
+    """x' = R(q)(x - c) + c + t per example; [B,N,3] float32 device tensors."""
+    B, N, _ = coords.shape
+    if out is None:
+        out = torch.empty_like(coords)
+    rc = lib().mg_transform_forward(
+        B, N, _ptr(coords, torch.float32, "coords", (B, N, 3)),
+        _ptr(centers, torch.float32, "centers", (B, 3)), _ptr(quats, torch.float32, "quats", (B, 4)),
+        _ptr(translations, torch.float32, "translations", (B, 3)),
+        _ptr(out, torch.float32, "out", (B, N, 3)), _stream())
+    if rc != MG_OK:
+        raise MolgridError(rc, "mg_transform_forward")
+    return out
+
+
+class GridMaker:
+    """Handle over ``mg_gridmaker`` (GridMaker constructor listing of the paper)."""
+
+    def __init__(self, resolution=0.5, dimension=23.5, binary=False, radius_type_indexed=False,
+                 radius_scale=1.0, gaussian_radius_multiple=1.0):
+        self._h = ctypes.c_void_p()
+        rc = lib().mg_gridmaker_create(ctypes.byref(self._h), resolution, dimension, int(binary),
+                                       int(radius_type_indexed), radius_scale,
+                                       gaussian_radius_multiple)
+        if rc != MG_OK:
+            self._h = ctypes.c_void_p()
+            raise MolgridError(rc, "mg_gridmaker_create")
+        d = ctypes.c_int()
+        lib().mg_gridmaker_points_per_side(self._h, ctypes.byref(d))
+        self.D = d.value
+        self.binary = bool(binary)
+        self.radius_type_indexed = bool(radius_type_indexed)
+        self._ws: Optional[torch.Tensor] = None
+
+    def __del__(self):
+        h = getattr(self, "_h", None)
+        if h is not None and h.value and _lib is not None:
+            _lib.mg_gridmaker_destroy(h)
+            self._h = ctypes.c_void_p()
+
+    def workspace_bytes(self, B: int, N: int, T: int) -> int:
+        n = ctypes.c_size_t()
+        rc = lib().mg_workspace_bytes(self._h, B, N, T, ctypes.byref(n))
+        if rc != MG_OK:
+            raise MolgridError(rc, "mg_workspace_bytes")
+        return n.value
+
+    def _workspace(self, B, N, T, device, workspace):
+        need = self.workspace_bytes(B, N, T)
+        if workspace is not None:
+            return workspace, workspace.numel() * workspace.element_size()
+        if self._ws is None or self._ws.numel() < need or self._ws.device != device:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=device)
+        return self._ws, self._ws.numel()
+
+    def _common(self, coords, natoms, centers, quats, translations):
+        B, N, _ = coords.shape
+        return (B, N, _ptr(coords, torch.float32, "coords", (B, N, 3)),
+                _ptr(natoms, torch.int32, "natoms", (B,)),
+                _ptr(centers, torch.float32, "centers", (B, 3)),
+                _ptr(quats, torch.float32, "quats", (B, 4)),
+                _ptr(translations, torch.float32, "translations", (B, 3)))
+
+    def mg_forward_index(self, coords, types, radii, T, natoms=None, centers=None, quats=None,
+                         translations=None, out=None, workspace=None):
+        B, N, pc, pn, pce, pq, pt = self._common(coords, natoms, centers, quats, translations)
+        D = self.D
+        if out is None:
+            out = torch.empty((B, T, D, D, D), dtype=torch.float32, device=coords.device)
+        ws, wsb = self._workspace(B, N, T, coords.device, workspace)
+        rshape = (T,) if self.radius_type_indexed else (B, N)
+        rc = lib().mg_forward_index(
+            self._h, B, N, T, pc, _ptr(types, torch.int32, "types", (B, N)),
+            _ptr(radii, torch.float32, "radii", rshape), pn, pce, pq, pt,
+            _ptr(out, torch.float32, "out", (B, T, D, D, D)), ctypes.c_void_p(ws.data_ptr()), wsb,
+            _stream())
+        if rc != MG_OK:
+            raise MolgridError(rc, "mg_forward_index")
+        return out
+
+    def mg_forward_vector(self, coords, weights, radii, natoms=None, centers=None, quats=None,
+                          translations=None, out=None, workspace=None):
+        B, N, pc, pn, pce, pq, pt = self._common(coords, natoms, centers, quats, translations)
+        T = weights.shape[2]
+        D = self.D
+        if out is None:
+            out = torch.empty((B, T, D, D, D), dtype=torch.float32, device=coords.device)
+        ws, wsb = self._workspace(B, N, T, coords.device, workspace)
+        rc = lib().mg_forward_vector(
+            self._h, B, N, T, pc, _ptr(weights, torch.float32, "weights", (B, N, T)),
+            _ptr(radii, torch.float32, "radii", (T,)), pn, pce, pq, pt,
+            _ptr(out, torch.float32, "out", (B, T, D, D, D)), ctypes.c_void_p(ws.data_ptr()), wsb,
+            _stream())
+        if rc != MG_OK:
+            raise MolgridError(rc, "mg_forward_vector")
+        return out
+
+    def mg_backward_index(self, coords, types, radii, T, grad_out, natoms=None, centers=None,
+                          quats=None, translations=None, grad_coords=None, workspace=None):
+        B, N, pc, pn, pce, pq, pt = self._common(coords, natoms, centers, quats, translations)
+        D = self.D
+        if grad_coords is None:
+            grad_coords = torch.empty((B, N, 3), dtype=torch.float32, device=coords.device)
+        ws, wsb = self._workspace(B, N, T, coords.device, workspace)
+        rshape = (T,) if self.radius_type_indexed else (B, N)
+        rc = lib().mg_backward_index(
+            self._h, B, N, T, pc, _ptr(types, torch.int32, "types", (B, N)),
+            _ptr(radii, torch.float32, "radii", rshape), pn, pce, pq, pt,
+            _ptr(grad_out, torch.float32, "grad_out", (B, T, D, D, D)),
+            _ptr(grad_coords, torch.float32, "grad_coords", (B, N, 3)),
+            ctypes.c_void_p(ws.data_ptr()), wsb, _stream())
+        if rc != MG_OK:
+            raise MolgridError(rc, "mg_backward_index")
+        return grad_coords
+
+    def mg_backward_vector(self, coords, weights, radii, grad_out, natoms=None, centers=None,
+                           quats=None, translations=None, grad_coords=None, grad_weights=None,
+                           want_coords=True, want_weights=True, workspace=None):
+        B, N, pc, pn, pce, pq, pt = self._common(coords, natoms, centers, quats, translations)
+        T = weights.shape[2]
+        D = self.D
+        if grad_coords is None and want_coords:
+            grad_coords = torch.empty((B, N, 3), dtype=torch.float32, device=coords.device)
+        if grad_weights is None and want_weights:
+            grad_weights = torch.empty((B, N, T), dtype=torch.float32, device=coords.device)
+        ws, wsb = self._workspace(B, N, T, coords.device, workspace)
+        rc = lib().mg_backward_vector(
+            self._h, B, N, T, pc, _ptr(weights, torch.float32, "weights", (B, N, T)),
+            _ptr(radii, torch.float32, "radii", (T,)), pn, pce, pq, pt,
+            _ptr(grad_out, torch.float32, "grad_out", (B, T, D, D, D)),
+            _ptr(grad_coords, torch.float32, "grad_coords", (B, N, 3)),
+            _ptr(grad_weights, torch.float32, "grad_weights", (B, N, T)),
+            ctypes.c_void_p(ws.data_ptr()), wsb, _stream())
+        if rc != MG_OK:
+            raise MolgridError(rc, "mg_backward_vector")
+        return grad_coords, grad_weights

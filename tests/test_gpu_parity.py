@@ -1,0 +1,337 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
+
+Tolerances (the benchmark spec): real-valued grid max-abs 1e-5; binary bit-exact; gradients
+relative 1e-4, taken as max_a |delta_a|_inf <= 1e-4 * max_a |g_ref,a|_inf per example.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1912_04822_amd import workloads
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+GRID_TOL = 1e-5
+GRAD_RTOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def mg():
+    from paper_1912_04822_amd import molgrid
+    molgrid.lib()           # raises if the HIP library is not built: no fallback
+    return molgrid
+
+
+def dev(a, dtype=None):
+    if a is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def run_forward_index(mg, w, *, binary=False, grm=1.0, radius_scale=1.0, natoms=None,
+                      per_atom_radii=False):
+    gm = mg.GridMaker(w.resolution, w.dimension, binary=binary,
+                      radius_type_indexed=not per_atom_radii, radius_scale=radius_scale,
+                      gaussian_radius_multiple=grm)
+    assert gm.D == w.D
+    radii = w.radii[np.clip(w.types, 0, w.T - 1)] if per_atom_radii else w.radii
+    out = gm.mg_forward_index(dev(w.coords), dev(w.types), dev(radii), w.T, natoms=dev(natoms),
+                              centers=dev(w.centers), quats=dev(w.quats),
+                              translations=dev(w.translations))
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def oracle_forward_index(w, *, binary=False, grm=1.0, radius_scale=1.0, natoms=None,
+                         per_atom_radii=False, **kw):
+    radii = w.radii[np.clip(w.types, 0, w.T - 1)] if per_atom_radii else w.radii
+    common = dict(natoms=natoms, centers=w.centers, quats=w.quats, translations=w.translations,
+                  radius_scale=radius_scale, radius_type_indexed=not per_atom_radii)
+    if binary:
+        return oracle.forward_binary(w.coords, radii, w.T, w.resolution, w.dimension,
+                                     types=w.types, **common)
+    return oracle.forward_index(w.coords, w.types, radii, w.T, w.resolution, w.dimension, grm=grm,
+                                **common, **kw)
+
+
+# ---------------------------------------------------------------------------
+# step 1: transform
+# ---------------------------------------------------------------------------
+
+def test_transform_is_bit_identical_to_the_oracle(mg):
+    rng = np.random.default_rng(11)
+    B, N = 37, 1111
+    x = rng.uniform(-40, 40, (B, N, 3)).astype(np.float32)
+    c = rng.uniform(-10, 10, (B, 3)).astype(np.float32)
+    t = rng.uniform(-2, 2, (B, 3)).astype(np.float32)
+    q = (rng.standard_normal((B, 4)) * rng.uniform(0.1, 10, (B, 1))).astype(np.float32)
+    q[3] = 0                    # no rotation given
+    q[4] = [1, 0, 0, 1]         # exact quarter turn
+    got = mg.mg_transform_forward(dev(x), dev(c), dev(q), dev(t)).cpu().numpy()
+    ref = oracle.transform(x, c, q, t)
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    got = mg.mg_transform_forward(dev(x)).cpu().numpy()
+    assert np.array_equal(got, x)
+
+
+# ---------------------------------------------------------------------------
+# steps 2-3: forward, index types
+# ---------------------------------------------------------------------------
+
+def test_forward_tiny(mg):
+    w = workloads.tiny()
+    got = run_forward_index(mg, w)
+    ref = oracle_forward_index(w)
+    assert got.shape == (1, 4, 24, 24, 24)
+    assert np.abs(got - ref).max() <= GRID_TOL
+    # also against the all-double reading (transformed coordinate not rounded to float)
+    ref64 = oracle_forward_index(w, coords_as_float=False, box=False)
+    assert np.abs(got - ref64).max() <= GRID_TOL
+
+
+@pytest.mark.parametrize("grm,scale", [(1.0, 1.0), (0.5, 1.3), (2.0, 0.8)])
+def test_forward_ragged_small_unaligned_grid(mg, grm, scale):
+    """D = 13 (rows not 16-byte aligned), off-origin centers, padded / out-of-range types,
+    natoms = [N, N/2, 0], un-normalised quaternions."""
+    w = workloads.ragged_small()
+    nat = w.extra["natoms"]
+    got = run_forward_index(mg, w, grm=grm, radius_scale=scale, natoms=nat)
+    ref = oracle_forward_index(w, grm=grm, radius_scale=scale, natoms=nat)
+    assert np.abs(got - ref).max() <= GRID_TOL
+    assert got[2].max() == 0.0
+
+
+@pytest.mark.parametrize("D,res", [(1, 1.0), (4, 0.5), (7, 0.3), (50, 0.5), (130, 0.125)])
+def test_forward_odd_grid_sizes(mg, D, res):
+    w = workloads.ragged_small(seed=D, B=2, N=50, T=3, D=D, resolution=res)
+    got = run_forward_index(mg, w)
+    ref = oracle_forward_index(w)
+    assert got.shape == ref.shape
+    assert np.abs(got - ref).max() <= GRID_TOL
+
+
+def test_forward_per_atom_radii(mg):
+    w = workloads.ragged_small()
+    got = run_forward_index(mg, w, per_atom_radii=True)
+    ref = oracle_forward_index(w, per_atom_radii=True)
+    assert np.abs(got - ref).max() <= GRID_TOL
+
+
+def test_forward_protein_ligand_subset_and_determinism(mg):
+    w = workloads.protein_ligand(B=6)
+    got = run_forward_index(mg, w)
+    ref = oracle_forward_index(w)
+    err = np.abs(got - ref).max()
+    assert err <= GRID_TOL, err
+    assert got.max() > 1.0
+    again = run_forward_index(mg, w)
+    assert np.array_equal(got.view(np.uint32), again.view(np.uint32))
+    mg.set_option("xcd_map", 0)
+    try:
+        other = run_forward_index(mg, w)
+    finally:
+        mg.set_option("xcd_map", 1)
+    assert np.array_equal(got.view(np.uint32), other.view(np.uint32))
+
+
+def test_forward_single_type_many_atoms(mg):
+    """All atoms in one channel: the record list of that channel is longer than one LDS round."""
+    w = workloads.protein_ligand(B=2)
+    w.types[:] = 3
+    got = run_forward_index(mg, w)
+    ref = oracle_forward_index(w)
+    assert np.abs(got - ref).max() <= 2 * GRID_TOL      # sums reach ~10 here
+    assert got[:, :3].max() == 0 and got[:, 4:].max() == 0
+
+
+def test_forward_overwrites_output_and_empty_batch(mg):
+    w = workloads.tiny()
+    gm = mg.GridMaker(w.resolution, w.dimension, radius_type_indexed=True)
+    out = torch.full((1, 4, 24, 24, 24), 7.0, device="cuda")
+    far = w.coords + 1000.0
+    gm.mg_forward_index(dev(far), dev(w.types), dev(w.radii), w.T, out=out)
+    torch.cuda.synchronize()
+    assert float(out.abs().max()) == 0.0
+
+
+# ---------------------------------------------------------------------------
+# step 5: binary occupancy (bit-exact)
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("make", ["tiny", "ragged", "protein"])
+def test_binary_is_bit_exact(mg, make):
+    if make == "tiny":
+        w, nat = workloads.tiny(), None
+    elif make == "ragged":
+        w = workloads.ragged_small()
+        nat = w.extra["natoms"]
+    else:
+        w, nat = workloads.protein_ligand(B=6), None
+    got = run_forward_index(mg, w, binary=True, natoms=nat)
+    ref = oracle_forward_index(w, binary=True, natoms=nat)
+    assert set(np.unique(got)) <= {0.0, 1.0}
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    assert got.sum() > 0 or make == "ragged"
+    got2 = run_forward_index(mg, w, binary=True, natoms=nat, radius_scale=1.37)
+    ref2 = oracle_forward_index(w, binary=True, natoms=nat, radius_scale=1.37)
+    assert np.array_equal(got2.view(np.uint32), ref2.view(np.uint32))
+
+
+def test_binary_knife_edges_on_lattice(mg):
+    """Atoms exactly on grid points with radii that put grid points exactly at distance r."""
+    res, D = 0.5, 16
+    dim = (D - 1) * res
+    ax = np.arange(D) * res - dim / 2
+    coords = np.array([[[ax[3], ax[4], ax[5]], [ax[10], ax[10], ax[10]], [ax[0], ax[15], ax[7]]]],
+                      np.float32)
+    types = np.array([[0, 1, 2]], np.int32)
+    radii = np.array([1.5, 2.0, 2.5], np.float32)        # multiples of res
+    w = workloads.Workload("edges", 1, 3, 3, res, dim, D, coords, types, radii,
+                           np.zeros((1, 3), np.float32))
+    got = run_forward_index(mg, w, binary=True)
+    ref = oracle_forward_index(w, binary=True)
+    assert np.array_equal(got, ref)
+    assert got[0, 0, 3, 4, 8] == 1.0 and got[0, 0, 3, 4, 9] == 0.0   # d = 1.5 inside, 2.0 outside
+
+
+# ---------------------------------------------------------------------------
+# step 4: vector types
+# ---------------------------------------------------------------------------
+
+def run_forward_vector(mg, w, binary=False, natoms=None):
+    gm = mg.GridMaker(w.resolution, w.dimension, binary=binary, radius_type_indexed=True)
+    out = gm.mg_forward_vector(dev(w.coords), dev(w.weights), dev(w.radii), natoms=dev(natoms),
+                               centers=dev(w.centers), quats=dev(w.quats),
+                               translations=dev(w.translations))
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def test_forward_vector_small_and_subset(mg):
+    w = workloads.ragged_small()
+    nat = w.extra["natoms"]
+    got = run_forward_vector(mg, w, natoms=nat)
+    ref = oracle.forward_vector(w.coords, w.weights, w.radii, w.resolution, w.dimension,
+                                natoms=nat, centers=w.centers, quats=w.quats,
+                                translations=w.translations)
+    assert np.abs(got - ref).max() <= GRID_TOL
+    w = workloads.protein_ligand(B=2, with_weights=True)
+    got = run_forward_vector(mg, w)
+    ref = oracle.forward_vector(w.coords, w.weights, w.radii, w.resolution, w.dimension,
+                                centers=w.centers, quats=w.quats, translations=w.translations)
+    assert np.abs(got - ref).max() <= GRID_TOL
+    assert got.min() >= 0 and got.max() > 0.1
+
+
+def test_forward_vector_binary_is_bit_exact(mg):
+    w = workloads.ragged_small()
+    wt = w.weights.copy()
+    wt[wt < 0.02] = 0.0                 # exact zeros: those atoms do not mark the channel
+    w.weights = wt
+    got = run_forward_vector(mg, w, binary=True)
+    ref = oracle.forward_binary(w.coords, w.radii, w.T, w.resolution, w.dimension, weights=wt,
+                                centers=w.centers, quats=w.quats, translations=w.translations)
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+
+
+# ---------------------------------------------------------------------------
+# step 6: backward
+# ---------------------------------------------------------------------------
+
+def grad_err(got, ref):
+    worst = 0.0
+    for b in range(ref.shape[0]):
+        scale = np.abs(ref[b]).max()
+        if scale == 0:
+            assert np.abs(got[b]).max() == 0
+            continue
+        worst = max(worst, np.abs(got[b] - ref[b]).max() / scale)
+    return worst
+
+
+def run_backward_index(mg, w, natoms=None, grm=1.0):
+    gm = mg.GridMaker(w.resolution, w.dimension, radius_type_indexed=True,
+                      gaussian_radius_multiple=grm)
+    g = gm.mg_backward_index(dev(w.coords), dev(w.types), dev(w.radii), w.T, dev(w.grad_out),
+                             natoms=dev(natoms), centers=dev(w.centers), quats=dev(w.quats),
+                             translations=dev(w.translations))
+    torch.cuda.synchronize()
+    return g.cpu().numpy()
+
+
+@pytest.mark.parametrize("grm", [1.0, 0.6])
+def test_backward_ragged_small(mg, grm):
+    w = workloads.ragged_small()
+    nat = w.extra["natoms"]
+    got = run_backward_index(mg, w, natoms=nat, grm=grm)
+    ref = oracle.backward_index(w.coords, w.types, w.radii, w.T, w.resolution, w.dimension,
+                                w.grad_out, grm=grm, natoms=nat, centers=w.centers, quats=w.quats,
+                                translations=w.translations)
+    assert grad_err(got, ref) <= GRAD_RTOL
+    for b in range(w.B):
+        dead = (np.arange(w.N) >= nat[b]) | (w.types[b] < 0) | (w.types[b] >= w.T)
+        assert (got[b][dead] == 0).all()
+
+
+def test_backward_protein_ligand_subset_and_finite_differences(mg):
+    w = workloads.protein_ligand(B=3, with_grad=True)
+    got = run_backward_index(mg, w)
+    ref = oracle.backward_index(w.coords, w.types, w.radii, w.T, w.resolution, w.dimension,
+                                w.grad_out, centers=w.centers, quats=w.quats,
+                                translations=w.translations)
+    assert got.shape == (3, 2040, 3)
+    assert grad_err(got, ref) <= GRAD_RTOL
+    # atoms whose cutoff misses the grid get exactly zero
+    assert ((ref == 0) == (got == 0)).all()
+    # central finite differences of the double forward on a few atoms
+    G = w.grad_out.astype(np.float64)
+    rng = np.random.default_rng(3)
+    live = np.argwhere(np.abs(ref[0]).max(axis=1) > 1.0)[:, 0]
+    for a in rng.choice(live, 4, replace=False):
+        for k in range(3):
+            vals = []
+            for s in (+1, -1):
+                c = w.coords[:1].copy()
+                c[0, a, k] += s * 2.5e-4
+                out = oracle.forward_index(c, w.types[:1], w.radii, w.T, w.resolution, w.dimension,
+                                           centers=w.centers[:1], quats=w.quats[:1],
+                                           translations=w.translations[:1], out_dtype=np.float64,
+                                           coords_as_float=False)
+                vals.append(((G[:1] * out).sum(), float(c[0, a, k])))
+            fd = (vals[0][0] - vals[1][0]) / (vals[0][1] - vals[1][1])
+            assert abs(got[0, a, k] - fd) <= 2e-4 * np.abs(ref[0]).max()
+    again = run_backward_index(mg, w)
+    assert np.array_equal(got.view(np.uint32), again.view(np.uint32))
+
+
+def test_backward_vector(mg):
+    w = workloads.ragged_small()
+    nat = w.extra["natoms"]
+    gm = mg.GridMaker(w.resolution, w.dimension, radius_type_indexed=True)
+    gc, gw = gm.mg_backward_vector(dev(w.coords), dev(w.weights), dev(w.radii), dev(w.grad_out),
+                                   natoms=dev(nat), centers=dev(w.centers), quats=dev(w.quats),
+                                   translations=dev(w.translations))
+    torch.cuda.synchronize()
+    rc, rw = oracle.backward_vector(w.coords, w.weights, w.radii, w.resolution, w.dimension,
+                                    w.grad_out, natoms=nat, centers=w.centers, quats=w.quats,
+                                    translations=w.translations)
+    assert grad_err(gc.cpu().numpy(), rc) <= GRAD_RTOL
+    assert grad_err(gw.cpu().numpy(), rw) <= GRAD_RTOL
+    # coordinates only / weights only
+    gc2, none = gm.mg_backward_vector(dev(w.coords), dev(w.weights), dev(w.radii), dev(w.grad_out),
+                                      natoms=dev(nat), centers=dev(w.centers), quats=dev(w.quats),
+                                      translations=dev(w.translations), want_weights=False)
+    assert none is None and torch.equal(gc2, gc)
+
+
+def test_backward_rejects_binary_mode(mg):
+    w = workloads.tiny()
+    gm = mg.GridMaker(w.resolution, w.dimension, binary=True, radius_type_indexed=True)
+    with pytest.raises(mg.MolgridError) as e:
+        gm.mg_backward_index(dev(w.coords), dev(w.types), dev(w.radii), w.T,
+                             torch.zeros(w.out_shape, device="cuda"))
+    assert e.value.code == -6

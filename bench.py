@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Benchmark of the atom-to-grid hot path on one MI355X.
+
+A step is one ``mg_forward_index`` call (transform + cull/bin + forward gather)
+on the protein-ligand batch (B=50, N=2040, T=28, 48^3 points at 0.5 A, a random
+rotation and translation per example), inputs resident in HBM.  The other rows
+of the path (vector types, binary, backward) are timed on the same geometry and
+reported under "rows".  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--rows]
+    python bench.py --copy-calibration   # plain copy kernel of known size, for counter scaling
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import re
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E peak
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+
+
+def hip_runtime():
+    for name in ("libamdhip64.so", "/opt/rocm/lib/libamdhip64.so"):
+        try:
+            return ctypes.CDLL(name)
+        except OSError:
+            continue
+    raise RuntimeError("libamdhip64.so not found")
+
+
+class Events:
+    """hipEvent_t pairs for timing one kernel per step on the launch stream."""
+
+    def __init__(self, n):
+        self.hip = hip_runtime()
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p,
+                                                 ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0
+            assert self.hip.hipEventCreate(ctypes.byref(b)) == 0
+            self.pairs.append((a, b))
+
+    def elapsed_ms(self):
+        out = []
+        for a, b in self.pairs:
+            ms = ctypes.c_float()
+            rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+            assert rc == 0, rc
+            out.append(ms.value)
+        return out
+
+    def close(self):
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
+
+
+def stored_traffic(kernel_tag):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None."""
+    path = os.path.join(ROOT, "profiles", "%s_pmc.md" % kernel_tag)
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
+    return float(m.group(1)) if m else None
+
+
+def time_call(torch, molgrid, fn, steps, warmup):
+    """Whole-call wall time and per-step main-kernel time (HIP events on the launch stream)."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev = Events(steps)
+    t0 = time.perf_counter()
+    for a, b in ev.pairs:
+        molgrid.mg_time_next_kernel(a.value, b.value)
+        fn()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kern = ev.elapsed_ms()
+    ev.close()
+    return (t1 - t0) * 1e3 / steps, float(np.mean(kern)), float(np.min(kern))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--rows", action="store_true", help="also time vector/binary/backward rows")
+    ap.add_argument("--xcd-map", type=int, default=None)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a plain device copy of known size (for scaling rocprofv3 counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by example with no "
+              "collective); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        n = 619315200 // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": n * 4, "copy_bytes_written": n * 4, "launches": 10}))
+        return
+
+    from paper_1912_04822_amd import molgrid, workloads
+    molgrid.lib()                       # raises if the HIP library is missing: no fallback
+    if args.xcd_map is not None:
+        molgrid.set_option("xcd_map", args.xcd_map)
+
+    w = workloads.protein_ligand(B=50, with_weights=args.rows, with_grad=args.rows)
+    dev = lambda a, dt=None: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    coords, types, radii = dev(w.coords), dev(w.types), dev(w.radii)
+    centers, quats, trans = dev(w.centers), dev(w.quats), dev(w.translations)
+    gm = molgrid.GridMaker(w.resolution, w.dimension, radius_type_indexed=True)
+    out = torch.empty(w.out_shape, dtype=torch.float32, device="cuda")
+    ws = torch.empty(gm.workspace_bytes(w.B, w.N, w.T), dtype=torch.uint8, device="cuda")
+
+    def step():
+        gm.mg_forward_index(coords, types, radii, w.T, centers=centers, quats=quats,
+                            translations=trans, out=out, workspace=ws)
+
+    ms_step, ms_kernel, ms_kernel_min = time_call(torch, molgrid, step, args.steps, args.warmup)
+    grids_per_s = w.B / (ms_step * 1e-3)
+    achieved = w.out_bytes / (ms_kernel * 1e-3) / 1e9
+    result = {
+        "metric": "voxel grids/sec (B=50, 28ch, 48^3 fp32)",
+        "value": grids_per_s,
+        "unit": "grids/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "protein-ligand forward (configs[1]): B=50, N=2040 atoms, T=28, "
+                               "48^3 points @0.5A, random rotation + <=2A translation per example",
+                   "out_bytes": w.out_bytes},
+        "roofline": {"bound": "hbm", "kernel": "forward_kernel (index types, real density)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "kernel_ms_avg": ms_kernel, "kernel_ms_min": ms_kernel_min,
+                     "whole_call_GBs": w.out_bytes / (ms_step * 1e-3) / 1e9,
+                     "traffic": stored_traffic("forward_index_protein_ligand")},
+    }
+
+    if args.rows:
+        rows = {}
+        weights, G = dev(w.weights), dev(w.grad_out)
+        gmb = molgrid.GridMaker(w.resolution, w.dimension, binary=True, radius_type_indexed=True)
+        gc = torch.empty((w.B, w.N, 3), dtype=torch.float32, device="cuda")
+        k = max(5, args.steps // 10)
+
+        def add(name, fn, nbytes, steps):
+            ms, mk, mkmin = time_call(torch, molgrid, fn, steps, 3)
+            rows[name] = {"ms_per_call": ms, "kernel_ms_avg": mk, "grids_per_s": w.B / (ms * 1e-3),
+                          "algorithmic_GBs": nbytes / (mk * 1e-3) / 1e9}
+
+        add("forward_binary", lambda: gmb.mg_forward_index(
+            coords, types, radii, w.T, centers=centers, quats=quats, translations=trans, out=out,
+            workspace=ws), w.out_bytes, args.steps)
+        add("forward_vector", lambda: gm.mg_forward_vector(
+            coords, weights, radii, centers=centers, quats=quats, translations=trans, out=out,
+            workspace=ws), w.out_bytes, k)
+        add("backward_index", lambda: gm.mg_backward_index(
+            coords, types, radii, w.T, G, centers=centers, quats=quats, translations=trans,
+            grad_coords=gc, workspace=ws), w.out_bytes, args.steps)
+        result["rows"] = rows
+
+    if not args.no_cpu:
+        import oracle
+        best, threads = None, 0
+        for _ in range(3):
+            t0 = time.perf_counter()
+            _, threads = oracle.forward_index(w.coords, w.types, w.radii, w.T, w.resolution,
+                                              w.dimension, centers=w.centers, quats=w.quats,
+                                              translations=w.translations, return_threads=True)
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+        result["cpu_baseline"] = {
+            "value": w.B / best, "unit": "grids/s", "cores": int(threads), "kind": "oracle",
+            "sample": "all 50 examples of the same batch, cutoff-box variant, OpenMP over "
+                      "examples, best of 3 (%.2f s each)" % best}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -162,6 +162,15 @@ int mg_last_hip_error(void);
  */
 int mg_set_option(const char *key, int value);
 
+/*
+ * Measurement hook: the next forward or backward call made by this thread
+ * records `start` just before and `stop` just after its main kernel (the
+ * forward gather / the backward reduction; not the prep kernel) on the call's
+ * stream.  Both are hipEvent_t handles created by the caller with timing
+ * enabled; the hook is cleared by that call.  Pass NULL, NULL to clear it.
+ */
+int mg_time_next_kernel(void *start_event, void *stop_event);
+
 #ifdef __cplusplus
 }
 #endif

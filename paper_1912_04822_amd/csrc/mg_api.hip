@@ -17,7 +17,21 @@ struct mg_gridmaker {
 namespace {
 
 thread_local int g_last_hip_error = 0;
+thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 int g_xcd_map = 1;
+
+// Runs `launch` (the main kernel of a call) between the caller's timing events, if set.
+template <class F>
+hipError_t timed(hipStream_t stream, F launch)
+{
+    hipEvent_t e0 = g_ev_start, e1 = g_ev_stop;
+    g_ev_start = nullptr;
+    g_ev_stop = nullptr;
+    if (e0) (void)hipEventRecord(e0, stream);
+    const hipError_t rc = launch();
+    if (e1) (void)hipEventRecord(e1, stream);
+    return rc;
+}
 
 bool finite_pos(float v) { return std::isfinite(v) && v > 0.0f; }
 
@@ -146,7 +160,9 @@ int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T, const float *c
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T);
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
-    return hip_status(mg::launch_forward(gm->gs, bt, ws, out, g_xcd_map, (hipStream_t)stream));
+    return hip_status(timed((hipStream_t)stream, [&] {
+        return mg::launch_forward(gm->gs, bt, ws, out, g_xcd_map, (hipStream_t)stream);
+    }));
 }
 
 int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
@@ -169,7 +185,9 @@ int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T);
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
-    return hip_status(mg::launch_forward(gm->gs, bt, ws, out, g_xcd_map, (hipStream_t)stream));
+    return hip_status(timed((hipStream_t)stream, [&] {
+        return mg::launch_forward(gm->gs, bt, ws, out, g_xcd_map, (hipStream_t)stream);
+    }));
 }
 
 int mg_backward_index(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
@@ -193,8 +211,10 @@ int mg_backward_index(const mg_gridmaker *gm, int B, int N, int T, const float *
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T);
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
-    return hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, nullptr,
-                                          (hipStream_t)stream));
+    return hip_status(timed((hipStream_t)stream, [&] {
+        return mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, nullptr,
+                                   (hipStream_t)stream);
+    }));
 }
 
 int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
@@ -220,8 +240,10 @@ int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T, const float 
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T);
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, grad_weights, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
-    return hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, grad_weights,
-                                          (hipStream_t)stream));
+    return hip_status(timed((hipStream_t)stream, [&] {
+        return mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, grad_weights,
+                                   (hipStream_t)stream);
+    }));
 }
 
 const char *mg_strerror(int code)
@@ -240,6 +262,13 @@ const char *mg_strerror(int code)
 }
 
 int mg_last_hip_error(void) { return g_last_hip_error; }
+
+int mg_time_next_kernel(void *start_event, void *stop_event)
+{
+    g_ev_start = (hipEvent_t)start_event;
+    g_ev_stop = (hipEvent_t)stop_event;
+    return MG_OK;
+}
 
 int mg_set_option(const char *key, int value)
 {

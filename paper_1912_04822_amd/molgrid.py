@@ -20,7 +20,7 @@ EXPORTS = [
     "mg_gridmaker_create", "mg_gridmaker_destroy", "mg_gridmaker_points_per_side",
     "mg_workspace_bytes", "mg_transform_forward", "mg_forward_index", "mg_forward_vector",
     "mg_backward_index", "mg_backward_vector", "mg_strerror", "mg_last_hip_error",
-    "mg_set_option",
+    "mg_set_option", "mg_time_next_kernel",
 ]
 
 _lib: Optional[ctypes.CDLL] = None
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.mg_last_hip_error.argtypes = []
         L.mg_set_option.restype = ci
         L.mg_set_option.argtypes = [ctypes.c_char_p, ci]
+        L.mg_time_next_kernel.restype = ci
+        L.mg_time_next_kernel.argtypes = [vp, vp]
         _lib = L
     return _lib
 
@@ -77,6 +79,11 @@ def set_option(key: str, value: int) -> None:
     rc = lib().mg_set_option(key.encode(), int(value))
     if rc != MG_OK:
         raise MolgridError(rc, "mg_set_option")
+
+
+def mg_time_next_kernel(start_event: Optional[int], stop_event: Optional[int]) -> None:
+    """Have the next forward/backward call record these hipEvent_t handles around its main kernel."""
+    lib().mg_time_next_kernel(ctypes.c_void_p(start_event), ctypes.c_void_p(stop_event))
 
 
 def _ptr(t: Optional[torch.Tensor], dtype, name: str, shape=None):

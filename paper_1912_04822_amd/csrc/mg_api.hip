@@ -39,7 +39,7 @@ int check_shape(const mg_gridmaker *gm, int B, int N, int T)
 {
     if (!gm) return MG_ENULL;
     if (B < 1 || N < 1 || T < 1) return MG_ESHAPE;
-    if (B > 65535) return MG_ESHAPE;                      // grid.y of the per-example launches
+    if (B > 65535 || T > 65535) return MG_ESHAPE;         // grid.y, grid.z of the launches
     const long long D = gm->gs.D;
     const long long tiles = (long long)B * T * D * D;     // upper bound on forward tiles
     if (tiles > 0x7fffffffLL) return MG_ESHAPE;
@@ -274,7 +274,7 @@ int mg_set_option(const char *key, int value)
 {
     if (!key) return MG_ENULL;
     if (std::strcmp(key, "xcd_map") == 0) {
-        if (value != 0 && value != 1) return MG_EPARAM;
+        if (value < 0) return MG_EPARAM;
         g_xcd_map = value;
         return MG_OK;
     }

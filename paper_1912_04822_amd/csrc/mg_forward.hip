@@ -43,6 +43,7 @@ struct FwdParams {
     long long units;
     int groups;         // workgroups that own tiles
     int xcd_map;
+    int debug;
     float kexp;         // -2 * log2(e)
 };
 
@@ -67,27 +68,16 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void forward_kernel(FwdParams 
 {
     __shared__ __attribute__((aligned(16))) float lds[kWavesPerGroup * kTileFloats];
 
-    int g = blockIdx.x;
-    if (p.xcd_map) {
-        // consecutive workgroup ids go round-robin over the 8 XCDs: give every
-        // XCD one contiguous eighth of the tile groups
-        const int per = (int)(gridDim.x >> 3);
-        g = (g & 7) * per + (g >> 3);
-    }
-    if (g >= p.groups) return;
+    // grid: x = tile groups of one channel, y = channel, z = example
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long long unit = (long long)g * kWavesPerGroup + wave;
-    if (unit >= p.units) return;
-    float *tile = lds + wave * kTileFloats;
-
     const GridSpec &gs = p.gs;
     const int D = gs.D, T = p.T, N = p.N;
-    const int strip = (int)(unit % p.strips);
-    long long q = unit / p.strips;
-    const int plane = (int)(q % D);
-    q /= D;
-    const int t = (int)(q % T);
-    const int b = (int)(q / T);
+    const int uc = (int)blockIdx.x * kWavesPerGroup + wave;     // tile within the channel
+    if (uc >= D * p.strips) return;
+    const int t = (int)blockIdx.y, b = (int)blockIdx.z;
+    const int plane = p.strips == 1 ? uc : uc / p.strips;
+    const int strip = p.strips == 1 ? 0 : uc - plane * p.strips;
+    float *tile = lds + wave * kTileFloats;
     const int j0 = strip * p.rows;
     const int j1 = min(D, j0 + p.rows);
     const int pitch = p.pitch;
@@ -105,7 +95,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void forward_kernel(FwdParams 
     const float r_chan = VECTOR ? gs.radius_scale * p.radii[t] : 0.0f;
 
     bool any = false;
-    for (int base = 0; base < count; base += 64) {
+    for (int base = 0; base < (p.debug == 2 ? 0 : count); base += 64) {
         const int e = base + lane;
         float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         float w = 1.0f;
@@ -138,6 +128,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void forward_kernel(FwdParams 
         const int nsegs = (khi >> 2) - seg0 + 1;
 
         unsigned long long mask = __ballot(ok);
+        if (p.debug == 1) mask = 0ull;
         if (mask != 0ull && !any) {
             any = true;
             const float4 z4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
@@ -191,11 +182,31 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void forward_kernel(FwdParams 
         float4 *dst4 = reinterpret_cast<float4 *>(dst);
         const float4 *src4 = reinterpret_cast<const float4 *>(tile);
         const float4 z4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        for (int o = lane * 2; o < n4; o += 128) {
-            const float4 v0 = any ? src4[o] : z4;
-            const float4 v1 = (any && o + 1 < n4) ? src4[o + 1] : z4;
-            dst4[o] = v0;
-            if (o + 1 < n4) dst4[o + 1] = v1;
+        // Constant trip count, fully unrolled, and two separate paths (not a select
+        // between an LDS pointer and a zero): a run-time loop bound or a generic-pointer
+        // load makes the compiler wait for all earlier stores before each new one.
+        constexpr int kIters = (kTileFloats / 4 + 127) / 128;
+        if (any) {
+            float4 v0[kIters], v1[kIters];
+#pragma unroll
+            for (int it = 0; it < kIters; ++it) {
+                const int o = min(it * 128 + lane * 2, kTileFloats / 4 - 2);
+                v0[it] = src4[o];
+                v1[it] = src4[o + 1];
+            }
+#pragma unroll
+            for (int it = 0; it < kIters; ++it) {
+                const int o = it * 128 + lane * 2;
+                if (o < n4) dst4[o] = v0[it];
+                if (o + 1 < n4) dst4[o + 1] = v1[it];
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < kIters; ++it) {
+                const int o = it * 128 + lane * 2;
+                if (o < n4) dst4[o] = z4;
+                if (o + 1 < n4) dst4[o + 1] = z4;
+            }
         }
     } else {
         const int n = (j1 - j0) * D;
@@ -238,14 +249,14 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     p.B = bt.B; p.N = bt.N; p.T = bt.T;
     p.rows = tl.rows; p.strips = tl.strips; p.pitch = tl.pitch;
     p.units = tl.units;
-    const long long groups = (tl.units + kWavesPerGroup - 1) / kWavesPerGroup;
-    p.groups = (int)groups;
-    p.xcd_map = xcd_map;
+    p.groups = 0;
+    p.xcd_map = xcd_map & 1;
+    p.debug = xcd_map >> 4;
     p.kexp = -2.8853900817779268f;      // -2 / ln 2
-    long long grid = xcd_map ? ((groups + 7) / 8) * 8 : groups;
+    const int per_channel = (gs.D * tl.strips + kWavesPerGroup - 1) / kWavesPerGroup;
     const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)out & 15u) == 0);
     const bool vec = bt.weights != nullptr;
-    const dim3 blk(64 * kWavesPerGroup), grd((unsigned)grid);
+    const dim3 blk(64 * kWavesPerGroup), grd(per_channel, bt.T, bt.B);
 #define MG_LAUNCH(V, Bn, Al) \
     hipLaunchKernelGGL((forward_kernel<V, Bn, Al>), grd, blk, 0, stream, p)
     if (vec) {

@@ -102,7 +102,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--rows", action="store_true", help="also time vector/binary/backward rows")
-    ap.add_argument("--xcd-map", type=int, default=None)
+    ap.add_argument("--planes-per-wave", type=int, default=None, help="forward kernel tuning knob")
+    ap.add_argument("--debug", type=int, default=None, help="forward kernel timing mode (wrong output)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size (for scaling rocprofv3 counters)")
     args = ap.parse_args()
@@ -129,8 +130,10 @@ def main():
 
     from paper_1912_04822_amd import molgrid, workloads
     molgrid.lib()                       # raises if the HIP library is missing: no fallback
-    if args.xcd_map is not None:
-        molgrid.set_option("xcd_map", args.xcd_map)
+    if args.planes_per_wave is not None:
+        molgrid.set_option("planes_per_wave", args.planes_per_wave)
+    if args.debug is not None:
+        molgrid.set_option("debug", args.debug)
 
     w = workloads.protein_ligand(B=50, with_weights=args.rows, with_grad=args.rows)
     dev = lambda a, dt=None: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()

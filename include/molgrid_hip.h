@@ -156,8 +156,9 @@ int mg_last_hip_error(void);
 
 /*
  * Tuning knobs of the forward kernel, for measurement only (results do not
- * depend on them).  key "xcd_map": 0 = workgroup i takes tile group i;
- * 1 = each of the 8 XCDs takes one contiguous eighth of the output.
+ * depend on them).  key "planes_per_wave" (1..64, default 4): consecutive
+ * x-planes one wavefront produces; key "debug" (0..3): 0 = normal, other
+ * values skip parts of the kernel to time the rest (output then wrong).
  * Returns MG_EPARAM for an unknown key or value.
  */
 int mg_set_option(const char *key, int value);

@@ -18,7 +18,8 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
-int g_xcd_map = 1;
+int g_planes_per_wave = 4;
+int g_debug = 0;
 
 // Runs `launch` (the main kernel of a call) between the caller's timing events, if set.
 template <class F>
@@ -49,10 +50,9 @@ int check_shape(const mg_gridmaker *gm, int B, int N, int T)
 
 int check_workspace(const mg_gridmaker *gm, int B, int N, int T, void *ws, size_t ws_bytes)
 {
-    (void)gm;
-    if (!ws) return MG_EWORKSPACE;
+        if (!ws) return MG_EWORKSPACE;
     if (((uintptr_t)ws & 15u) != 0) return MG_EWORKSPACE;
-    if (ws_bytes < mg::workspace_bytes(B, N, T)) return MG_EWORKSPACE;
+    if (ws_bytes < mg::workspace_bytes(B, N, T, gm->gs.D)) return MG_EWORKSPACE;
     return MG_OK;
 }
 
@@ -125,7 +125,7 @@ int mg_workspace_bytes(const mg_gridmaker *gm, int B, int N, int T, size_t *byte
     if (!bytes) return MG_ENULL;
     const int rc = check_shape(gm, B, N, T);
     if (rc != MG_OK) return rc;
-    *bytes = mg::workspace_bytes(B, N, T);
+    *bytes = mg::workspace_bytes(B, N, T, gm->gs.D);
     return MG_OK;
 }
 
@@ -157,11 +157,11 @@ int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T, const float *c
     if (rc != MG_OK) return rc;
     const mg::Batch bt = make_batch(B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
                                     translations);
-    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
+    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_planes_per_wave, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
-        return mg::launch_forward(gm->gs, bt, ws, out, g_xcd_map, (hipStream_t)stream);
+        return mg::launch_forward(gm->gs, bt, ws, out, g_planes_per_wave, g_debug, (hipStream_t)stream);
     }));
 }
 
@@ -182,11 +182,11 @@ int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *
     if (rc != MG_OK) return rc;
     const mg::Batch bt = make_batch(B, N, T, coords, nullptr, weights, radii, natoms, centers,
                                     quats, translations);
-    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
+    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_planes_per_wave, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
-        return mg::launch_forward(gm->gs, bt, ws, out, g_xcd_map, (hipStream_t)stream);
+        return mg::launch_forward(gm->gs, bt, ws, out, g_planes_per_wave, g_debug, (hipStream_t)stream);
     }));
 }
 
@@ -208,8 +208,8 @@ int mg_backward_index(const mg_gridmaker *gm, int B, int N, int T, const float *
     if (rc != MG_OK) return rc;
     const mg::Batch bt = make_batch(B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
                                     translations);
-    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, nullptr, (hipStream_t)stream));
+    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_planes_per_wave, grad_coords, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
         return mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, nullptr,
@@ -237,8 +237,9 @@ int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T, const float 
     if (rc != MG_OK) return rc;
     const mg::Batch bt = make_batch(B, N, T, coords, nullptr, weights, radii, natoms, centers,
                                     quats, translations);
-    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, grad_weights, (hipStream_t)stream));
+    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_planes_per_wave, grad_coords, grad_weights,
+                                    (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
         return mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, grad_weights,
@@ -273,9 +274,14 @@ int mg_time_next_kernel(void *start_event, void *stop_event)
 int mg_set_option(const char *key, int value)
 {
     if (!key) return MG_ENULL;
-    if (std::strcmp(key, "xcd_map") == 0) {
-        if (value < 0) return MG_EPARAM;
-        g_xcd_map = value;
+    if (std::strcmp(key, "planes_per_wave") == 0) {
+        if (value < 1 || value > 64) return MG_EPARAM;
+        g_planes_per_wave = value;
+        return MG_OK;
+    }
+    if (std::strcmp(key, "debug") == 0) {
+        if (value < 0 || value > 3) return MG_EPARAM;
+        g_debug = value;
         return MG_OK;
     }
     return MG_EPARAM;

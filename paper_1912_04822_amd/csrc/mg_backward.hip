@@ -25,7 +25,7 @@ struct BwdParams {
     GridSpec gs;
     const float4 *rec;
     const int *idx;
-    const int2 *meta;
+    const int4 *meta;
     const float *rot;
     const int32_t *types;
     const float *weights;
@@ -137,8 +137,8 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
     const GridSpec &gs = p.gs;
     const int b = blockIdx.y, slot = blockIdx.x;
     const int N = p.N, T = p.T, D = gs.D;
-    const int2 last = p.meta[(size_t)b * T + (VECTOR ? 0 : T - 1)];
-    if (slot >= last.x + last.y) return;            // uniform for the block
+    const int4 last = p.meta[(size_t)b * T + (VECTOR ? 0 : T - 1)];
+    if (slot >= last.x + last.z) return;            // past the last group's slots (uniform)
     const float4 a = p.rec[(size_t)b * N + slot];
     if (!(a.w > 0.0f)) return;                      // dead record: the prep kernel wrote its zeros
     const int ai = p.idx[(size_t)b * N + slot];

@@ -33,26 +33,37 @@ struct GridSpec {
 };
 
 // ---------------------------------------------------------------------------
-// Workspace layout (device, caller-provided, 16-byte aligned):
-//   rec   [B][N] float4   transformed atom records {x', y', z', r}; r = 0 marks
-//                         an atom that contributes nothing.  Index types: the
-//                         records of example b are grouped by type, group t
-//                         starting at meta[b][t].x with meta[b][t].y entries,
-//                         in atom order.  Vector types: one group per example
-//                         (meta[b][0]), r unused (1 = live, 0 = dead).
+// Workspace layout (device, caller-provided, 16-byte aligned).  A "group" is
+// the set of atoms one output channel reads: for index types the atoms of
+// example b with type t (group b*T+t), for vector types all atoms of example
+// b (group b*T+0).
+//   rec   [B][N] float4   transformed atom records {x', y', z', r} (vector
+//                         types: r = 1).  The live records of a group sit at
+//                         rec[b][first .. first+live), binned by x-plane (bin
+//                         k+1 holds floor((x'-origin_x)/res) == k, bins 0 and
+//                         D+1 the atoms left / right of the grid) and, inside
+//                         a bin, in atom order.  Slots first+live .. first+all
+//                         hold w = 0.
 //   idx   [B][N] int32    original atom index of each record
-//   meta  [B][T] int2     {first record, number of records}
+//   meta  [B][T] int4     {first, live, all, sorted}; sorted = 0 means the
+//                         group was too long to bin: its records are in atom
+//                         order, culled ones carry r = 0, and live == all
+//   range [B][T][PG] int2 for plane group pg (the planes_per_wave consecutive
+//                         x-planes one forward wavefront produces): the span
+//                         [r0, r1) of the group's records, relative to `first`,
+//                         that can reach those planes; PG = ceil(D/planes_per_wave)
 //   rot   [B][12] float   rotation matrix rows (9 used), for the backward pass
 // ---------------------------------------------------------------------------
 struct Workspace {
     float4 *rec;
     int    *idx;
-    int2   *meta;
+    int4   *meta;
+    int2   *range;
     float  *rot;
 };
 
-size_t workspace_bytes(int B, int N, int T);
-Workspace carve_workspace(void *base, int B, int N, int T);
+size_t workspace_bytes(int B, int N, int T, int D);
+Workspace carve_workspace(void *base, int B, int N, int T, int D);
 
 struct Batch {
     int B, N, T;
@@ -77,17 +88,18 @@ struct Tiling {
 Tiling make_tiling(int B, int T, int D);
 
 constexpr int kTileFloats = 2304;       // LDS floats per wavefront tile (9216 B)
-constexpr int kWavesPerGroup = 4;
+constexpr int kWavesPerGroup = 1;
+constexpr int kSortCap = 2048;          // longest group the prep kernel bins by x-plane
 
 // Launchers (each enqueues on `stream`, returns the hipError_t of the launch).
 hipError_t launch_transform(int B, int N, const float *coords, const float *centers,
                             const float *quats, const float *translations, float *out,
                             hipStream_t stream);
 hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
-                       float *grad_coords_to_clear, float *grad_weights_to_clear,
-                       hipStream_t stream);
+                       int planes_per_wave, float *grad_coords_to_clear,
+                       float *grad_weights_to_clear, hipStream_t stream);
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
-                          float *out, int xcd_map, hipStream_t stream);
+                          float *out, int planes_per_wave, int debug, hipStream_t stream);
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                            const float *grad_out, float *grad_coords, float *grad_weights,
                            hipStream_t stream);

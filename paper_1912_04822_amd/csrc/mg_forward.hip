@@ -3,18 +3,30 @@
 //
 // Design (gfx950, wave64).  The output [B][T][D][D][D] is cut into tiles: a
 // tile is `rows` consecutive z-rows of one x-plane of one channel, i.e. one
-// contiguous run of rows*D floats (9216 B at D = 48).  A wavefront owns a tile:
-//   1. it walks the channel's atom records (written by the prep kernel), 64 at
-//      a time, and each lane tests one atom against the tile (disc of the
-//      atom's cutoff sphere in this x-plane versus the tile's rows);
-//   2. for every atom that passes, the 64 lanes spread over the atom's
-//      footprint (rows x 4-voxel z-segments), evaluate the density and add it
-//      into the tile held in LDS -- one atom at a time, in record order, so the
-//      sum is deterministic and needs no atomics;
-//   3. the finished tile is streamed to HBM, each lane writing 32 contiguous
+// contiguous run of rows*D floats (9216 B at D = 48).  A wavefront produces
+// `planes_per_wave` consecutive x-planes of one channel, one tile at a time:
+//   1. once: it loads the records of the channel's atoms that can reach its
+//      planes (the span the prep kernel computed), one atom per lane;
+//   2. per plane, each lane tests its atom against the tile (disc of the
+//      atom's cutoff sphere in this x-plane versus the tile's rows); the
+//      (atom, row) pairs that survive are packed into a task list, so that all
+//      64 lanes work even though a single atom's footprint is small;
+//   3. each lane takes one task: the chord of the atom's sphere along that
+//      z-row.  It evaluates the density voxel by voxel and adds it into the
+//      tile held in LDS with LDS atomics (two atoms may hit one voxel in the
+//      same instruction).  The tile accumulates in signed fixed point (2^-24
+//      steps, integer LDS atomics): integer adds run ~40x faster in LDS than
+//      float adds on this chip, are exact and order-independent, and a
+//      contribution is rounded by at most 3e-8.  The sum of the magnitudes that
+//      can reach a voxel is tracked; if it could pass 120 (fixed-point range is
+//      +-128) the tile switches to float accumulation;
+//   4. the finished tile is streamed to HBM, each lane writing 32 contiguous
 //      bytes (two adjacent 16-byte stores), every output element exactly once,
 //      zeros included.  Tiles no atom touches skip LDS and store zeros.
-// No barrier is needed: a wavefront only touches its own LDS slice.
+// No barrier is needed: a wavefront only touches its own LDS slice.  The store
+// phase has a compile-time trip count and no loads from global memory happen
+// after the first plane, so stores of one plane are still in flight while the
+// next plane is computed.
 //
 // The density is rho(x) = exp(-2x^2) for x <= g, A(x-c)^2 for g < x < c, else 0
 // (x = d/r); evaluated from x^2 with the hardware exp2 and sqrt.
@@ -29,191 +41,329 @@ namespace mg {
 
 namespace {
 
+constexpr int kTaskCap = 512;                   // (atom, row) tasks staged per round
+constexpr int kTileLds = 2560;                  // LDS floats of a tile (rows are padded)
+constexpr int kWaveLdsFloats = kTileLds + 64 * 8 + kTaskCap / 2;
+constexpr float kFixedOne = 16777216.0f;        // 2^24
+constexpr float kFixedLimit = 120.0f;           // largest |sum| trusted to fixed point
+
 struct FwdParams {
     GridSpec gs;
     const float4 *rec;
     const int *idx;
-    const int2 *meta;
+    const int4 *meta;
+    const int2 *range;
     const float *weights;
     const float *radii;
     const float *centers;
     float *out;
     int B, N, T;
     int rows, strips, pitch;
-    long long units;
-    int groups;         // workgroups that own tiles
-    int xcd_map;
+    int planes_per_wave, pgroups;
     int debug;
     float kexp;         // -2 * log2(e)
 };
 
-__device__ inline float bcast(float v, int src)
-{
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src));
-}
+// what a wavefront keeps for the tile it is working on (all wave-uniform)
+struct TileCtx {
+    float *tile;
+    float4 *cand;
+    unsigned short *tasks;
+    int lane;
+    int D, pitch, j0, j1;
+    float res, inv_res, oy, oz;
+    float g2, c, A, kexp;
+    float inv_d4;       // 1 / (D/4)
+    int debug;
+};
+
+enum TileMode { kUntouched = 0, kFixed = 1, kFloat = 2 };
+
 __device__ inline int bcast(int v, int src) { return __builtin_amdgcn_readlane(v, src); }
 
+__device__ inline void lds_sync() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); }
+
 // rho as a function of x^2 = d^2 / r^2
-__device__ inline float density_from_x2(float x2, float kexp, float g2, float c, float c2, float A)
+__device__ inline float density_from_x2(float x2, const TileCtx &cx)
 {
-    const float e = __builtin_amdgcn_exp2f(x2 * kexp);
-    const float u = __builtin_amdgcn_sqrtf(x2) - c;
-    const float q = A * u * u;
-    const float v = x2 <= g2 ? e : q;
-    return x2 < c2 ? v : 0.0f;
+    const float e = __builtin_amdgcn_exp2f(x2 * cx.kexp);
+    const float u = fminf(__builtin_amdgcn_sqrtf(x2) - cx.c, 0.0f);    // 0 beyond the cutoff
+    const float q = cx.A * u * u;
+    return x2 <= cx.g2 ? e : q;
+}
+
+// Run the staged tasks [0, ntasks): one (atom, row) chord per lane.
+template <bool VECTOR, bool BINARY, bool FIXED>
+__device__ inline void run_tasks(const TileCtx &cx, int ntasks)
+{
+    for (int base = 0; base < ntasks; base += 64) {
+        const int tau = base + cx.lane;
+        bool act = tau < ntasks;
+        const int tk = cx.tasks[act ? tau : 0];
+        const int cnd = tk & 63, row = tk >> 6;
+        const float4 p0 = cx.cand[cnd * 2], p1 = cx.cand[cnd * 2 + 1];
+        const float ay = p0.x, az = p0.y, dx2 = p0.z, s = p0.w;
+        const float h2 = p1.x, w = p1.y;
+        const int j = __float_as_int(p1.z) + row;
+        const float gy = cx.oy + (float)j * cx.res;
+        const float dy = gy - ay;
+        const float dy2 = dy * dy;
+        const float rem = h2 - dy2;
+        act = act && rem > 0.0f;
+        const float hz = __builtin_amdgcn_sqrtf(fmaxf(rem, 0.0f)) * cx.inv_res + 1.0e-3f;
+        const float fz = (az - cx.oz) * cx.inv_res;
+        const int klo = max(0, (int)ceilf(fz - hz));
+        const int khi = min(cx.D - 1, (int)floorf(fz + hz));
+        const int nz = act ? khi - klo + 1 : 0;
+        float *rowp = cx.tile + (j - cx.j0) * cx.pitch + klo;
+        if (BINARY) {
+            const float base2 = dx2 + dy2;
+            for (int i = 0; i < nz; ++i) {
+                const float gz = cx.oz + (float)(klo + i) * cx.res;
+                const float dz = gz - az;
+                const float d2 = base2 + dz * dz;
+                if (d2 <= s) rowp[i] = 1.0f;
+            }
+        } else {
+            // coordinates in units of r: x^2 = b2s + zs^2
+            const float b2s = (dx2 + dy2) * s * s;
+            const float step = cx.res * s;
+            const float z0 = ((cx.oz - az) + (float)klo * cx.res) * s;
+            for (int i = 0; i < nz; ++i) {
+                const float zs = fmaf((float)i, step, z0);
+                const float rho = density_from_x2(fmaf(zs, zs, b2s), cx);
+                if (FIXED) {
+                    const int q = VECTOR ? (int)rintf(w * rho * kFixedOne)
+                                         : (int)fmaf(rho, kFixedOne, 0.5f);
+                    __hip_atomic_fetch_add(reinterpret_cast<int *>(rowp) + i, q, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_WAVEFRONT);
+                } else {
+                    __hip_atomic_fetch_add(rowp + i, VECTOR ? w * rho : rho, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_WAVEFRONT);
+                }
+            }
+        }
+    }
+    lds_sync();
+}
+
+// One batch of up to 64 atom records (one per lane) against one tile.
+//   a = {x', y', z', r};  valid: this lane holds a live record;  w: weight (vector types)
+template <bool VECTOR, bool BINARY>
+__device__ inline void plane_batch(const TileCtx &cx, float gx, float4 a, float r, float w,
+                                   bool valid, int &mode, float &bound)
+{
+    const float reach = BINARY ? r + 1.0e-3f * cx.res : r * cx.c;
+    const float dx = gx - a.x;
+    const float dx2 = dx * dx;
+    const float h2 = reach * reach - dx2;
+    bool ok = valid && (h2 > 0.0f);
+    // half-width of the footprint in this plane, in grid steps, padded
+    const float hv = __builtin_amdgcn_sqrtf(fmaxf(h2, 0.0f)) * cx.inv_res + 1.0e-3f;
+    const float fy = (a.y - cx.oy) * cx.inv_res;
+    const float fz = (a.z - cx.oz) * cx.inv_res;
+    const int jlo = max(cx.j0, (int)ceilf(fy - hv));
+    const int jhi = min(cx.j1 - 1, (int)floorf(fy + hv));
+    ok = ok && (jlo <= jhi) && (fz + hv >= 0.0f) && (fz - hv <= (float)(cx.D - 1));
+    unsigned long long mask = __ballot(ok);
+    if (cx.debug == 1) mask = 0ull;
+    if (mask == 0ull) return;
+
+    // upper bound on what this batch can add to one voxel (rho <= 1)
+    if (VECTOR) {
+        float s = ok ? fabsf(w) : 0.0f;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
+        bound += s;
+    } else {
+        bound += (float)__builtin_popcountll(mask);
+    }
+    const int n4 = ((cx.j1 - cx.j0) * cx.pitch) >> 2;
+    if (mode == kUntouched) {
+        mode = (BINARY || bound > kFixedLimit) ? kFloat : kFixed;
+        const float4 z4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);     // same bits as integer zeros
+        for (int o = cx.lane; o < n4; o += 64) reinterpret_cast<float4 *>(cx.tile)[o] = z4;
+    } else if (mode == kFixed && bound > kFixedLimit) {
+        mode = kFloat;                                               // leave fixed point
+        for (int o = cx.lane; o < n4 * 4; o += 64)
+            cx.tile[o] = (float)reinterpret_cast<int *>(cx.tile)[o] * (1.0f / kFixedOne);
+    }
+    lds_sync();
+    const int nrows = ok ? jhi - jlo + 1 : 0;
+    if (ok) {
+        cx.cand[cx.lane * 2] = make_float4(a.y, a.z, dx2, BINARY ? r * r : 1.0f / r);
+        cx.cand[cx.lane * 2 + 1] = make_float4(h2, w, __int_as_float(jlo), 0.0f);
+    }
+    // exclusive prefix of nrows over the lanes: where each atom's tasks start
+    int incl = nrows;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(incl, d, 64);
+        if (cx.lane >= d) incl += up;
+    }
+    const int total = bcast(incl, 63);
+    if (total <= kTaskCap) {
+        const int start = incl - nrows;
+        for (int rr = 0; rr < nrows; ++rr) cx.tasks[start + rr] = (unsigned short)(cx.lane | (rr << 6));
+        lds_sync();
+        if (mode == kFixed) run_tasks<VECTOR, BINARY, true>(cx, total);
+        else run_tasks<VECTOR, BINARY, false>(cx, total);
+    } else {
+        // rare: too many tasks for the staging list; take the atoms one at a time
+        while (mask != 0ull) {
+            const int src = (int)__builtin_ctzll(mask);
+            mask &= mask - 1ull;
+            const int n = bcast(nrows, src);
+            for (int rr = cx.lane; rr < n; rr += 64) cx.tasks[rr] = (unsigned short)(src | (rr << 6));
+            lds_sync();
+            if (mode == kFixed) run_tasks<VECTOR, BINARY, true>(cx, n);
+            else run_tasks<VECTOR, BINARY, false>(cx, n);
+        }
+    }
+}
+
+// Stream a finished tile to HBM (or zeros if no atom touched it).
+template <bool ALIGNED>
+__device__ inline void store_tile(const TileCtx &cx, float *dst, int mode)
+{
+    if (ALIGNED) {
+        const int n4 = ((cx.j1 - cx.j0) * cx.D) >> 2;
+        const int d4 = cx.D >> 2, p4 = cx.pitch >> 2;
+        float4 *dst4 = reinterpret_cast<float4 *>(dst);
+        const float4 *src4 = reinterpret_cast<const float4 *>(cx.tile);
+        const float4 z4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        // Constant trip count, fully unrolled, and separate paths (not a select between
+        // an LDS pointer and a zero): a generic-pointer load would make the compiler
+        // wait for all earlier stores before each new one.
+        constexpr int kIters = (kTileFloats / 4 + 127) / 128;
+        if (mode != kUntouched) {
+            float4 v[2 * kIters];
+#pragma unroll
+            for (int it = 0; it < 2 * kIters; ++it) {
+                const int o = min((it >> 1) * 128 + cx.lane * 2 + (it & 1), n4 - 1);
+                const int row = (int)(((float)o + 0.5f) * cx.inv_d4);
+                v[it] = src4[row * p4 + (o - row * d4)];            // rows are padded in LDS
+            }
+            if (mode == kFixed) {
+#pragma unroll
+                for (int it = 0; it < 2 * kIters; ++it) {
+                    const float sc = 1.0f / kFixedOne;
+                    v[it] = make_float4((float)__float_as_int(v[it].x) * sc,
+                                        (float)__float_as_int(v[it].y) * sc,
+                                        (float)__float_as_int(v[it].z) * sc,
+                                        (float)__float_as_int(v[it].w) * sc);
+                }
+            }
+#pragma unroll
+            for (int it = 0; it < 2 * kIters; ++it) {
+                const int o = (it >> 1) * 128 + cx.lane * 2 + (it & 1);
+                if (o < n4) dst4[o] = v[it];
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < 2 * kIters; ++it) {
+                const int o = (it >> 1) * 128 + cx.lane * 2 + (it & 1);
+                if (o < n4) dst4[o] = z4;
+            }
+        }
+    } else {
+        const int n = (cx.j1 - cx.j0) * cx.D;
+        for (int o = cx.lane; o < n; o += 64) {
+            const int row = o / cx.D;
+            const int col = o - row * cx.D;
+            float v = 0.0f;
+            if (mode == kFloat) v = cx.tile[row * cx.pitch + col];
+            if (mode == kFixed)
+                v = (float)reinterpret_cast<const int *>(cx.tile)[row * cx.pitch + col] *
+                    (1.0f / kFixedOne);
+            dst[o] = v;
+        }
+    }
 }
 
 template <bool VECTOR, bool BINARY, bool ALIGNED>
 __global__ __launch_bounds__(64 * kWavesPerGroup) void forward_kernel(FwdParams p)
 {
-    __shared__ __attribute__((aligned(16))) float lds[kWavesPerGroup * kTileFloats];
+    __shared__ __attribute__((aligned(16))) float lds[kWavesPerGroup * kWaveLdsFloats];
 
-    // grid: x = tile groups of one channel, y = channel, z = example
+    // grid: x = work items (strip, plane group) of one channel, y = channel, z = example
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const GridSpec &gs = p.gs;
     const int D = gs.D, T = p.T, N = p.N;
-    const int uc = (int)blockIdx.x * kWavesPerGroup + wave;     // tile within the channel
-    if (uc >= D * p.strips) return;
+    const int wi = (int)blockIdx.x * kWavesPerGroup + wave;
+    if (wi >= p.pgroups * p.strips) return;
     const int t = (int)blockIdx.y, b = (int)blockIdx.z;
-    const int plane = p.strips == 1 ? uc : uc / p.strips;
-    const int strip = p.strips == 1 ? 0 : uc - plane * p.strips;
-    float *tile = lds + wave * kTileFloats;
-    const int j0 = strip * p.rows;
-    const int j1 = min(D, j0 + p.rows);
-    const int pitch = p.pitch;
+    const int pg = p.strips == 1 ? wi : wi / p.strips;
+    const int strip = p.strips == 1 ? 0 : wi - pg * p.strips;
+    const int i0 = pg * p.planes_per_wave;
+    const int i1 = min(D, i0 + p.planes_per_wave);
 
-    const float res = gs.res, inv_res = gs.inv_res;
+    TileCtx cx;
+    cx.tile = lds + wave * kWaveLdsFloats;
+    cx.cand = reinterpret_cast<float4 *>(cx.tile + kTileLds);
+    cx.tasks = reinterpret_cast<unsigned short *>(cx.tile + kTileLds + 64 * 8);
+    cx.lane = lane;
+    cx.D = D;
+    cx.pitch = p.pitch;
+    cx.j0 = strip * p.rows;
+    cx.j1 = min(D, cx.j0 + p.rows);
+    cx.res = gs.res;
+    cx.inv_res = gs.inv_res;
+    cx.g2 = gs.g2; cx.c = gs.c; cx.A = gs.A; cx.kexp = p.kexp;
+    cx.inv_d4 = 1.0f / (float)max(1, D >> 2);
+    cx.debug = p.debug;
+
+    const size_t group = (size_t)b * T + (VECTOR ? 0 : t);
+    const int4 m = p.meta[group];
+    int2 span = p.range[group * p.pgroups + pg];
     const float ox = (p.centers ? p.centers[3 * b + 0] : 0.0f) - gs.half;
-    const float oy = (p.centers ? p.centers[3 * b + 1] : 0.0f) - gs.half;
-    const float oz = (p.centers ? p.centers[3 * b + 2] : 0.0f) - gs.half;
-    const float gx = ox + (float)plane * res;
-
-    const int2 m = p.meta[(size_t)b * T + (VECTOR ? 0 : t)];
-    const float4 *rec = p.rec + (size_t)b * N + m.x;
-    const int *idx = p.idx + (size_t)b * N + m.x;
-    const int count = m.y;
+    cx.oy = (p.centers ? p.centers[3 * b + 1] : 0.0f) - gs.half;
+    cx.oz = (p.centers ? p.centers[3 * b + 2] : 0.0f) - gs.half;
     const float r_chan = VECTOR ? gs.radius_scale * p.radii[t] : 0.0f;
+    if (p.debug == 2) span.y = span.x;
 
-    bool any = false;
-    for (int base = 0; base < (p.debug == 2 ? 0 : count); base += 64) {
-        const int e = base + lane;
+    const float4 *rec = p.rec + (size_t)b * N + m.x + span.x;
+    const int *idx = p.idx + (size_t)b * N + m.x + span.x;
+    const int count = span.y - span.x;
+    float *chan = p.out + ((size_t)b * T + t) * D * D * (size_t)D;
+
+    if (count <= 64) {
+        // the usual case: every atom that can reach these planes sits in one lane
         float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         float w = 1.0f;
-        if (e < count) {
-            a = rec[e];
-            if (VECTOR && a.w > 0.0f) w = p.weights[((size_t)b * N + idx[e]) * T + t];
+        if (lane < count) {
+            a = rec[lane];
+            if (VECTOR && a.w > 0.0f) w = p.weights[((size_t)b * N + idx[lane]) * T + t];
         }
-        float r = VECTOR ? (a.w > 0.0f ? r_chan : 0.0f) : a.w;
-        if (VECTOR) {
-            if (BINARY ? !(w > 0.0f) : (w == 0.0f)) r = 0.0f;
-        }
-        const float reach = BINARY ? r + 1.0e-3f * res : r * gs.c;
-        const float dx = gx - a.x;
-        const float dx2 = dx * dx;
-        const float h2 = reach * reach - dx2;
-        bool ok = (r > 0.0f) && (h2 > 0.0f);
-        // half-width of the footprint in this plane, in grid steps, padded
-        const float hv = __builtin_amdgcn_sqrtf(fmaxf(h2, 0.0f)) * inv_res + 1.0e-3f;
-        const float fy = (a.y - oy) * inv_res;
-        const float fz = (a.z - oz) * inv_res;
-        const int jlo = max(j0, (int)ceilf(fy - hv));
-        const int jhi = min(j1 - 1, (int)floorf(fy + hv));
-        const int klo = max(0, (int)ceilf(fz - hv));
-        const int khi = min(D - 1, (int)floorf(fz + hv));
-        ok = ok && (jlo <= jhi) && (klo <= khi);
-        const float rr = r * r;
-        const float scale = BINARY ? rr : (ok ? 1.0f / rr : 0.0f);   // r^2 or 1/r^2
-        const int nrows = jhi - jlo + 1;
-        const int seg0 = klo >> 2;
-        const int nsegs = (khi >> 2) - seg0 + 1;
-
-        unsigned long long mask = __ballot(ok);
-        if (p.debug == 1) mask = 0ull;
-        if (mask != 0ull && !any) {
-            any = true;
-            const float4 z4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            const int n4 = ((j1 - j0) * pitch) >> 2;
-            for (int o = lane; o < n4; o += 64) reinterpret_cast<float4 *>(tile)[o] = z4;
-            __builtin_amdgcn_wave_barrier();
-        }
-        while (mask != 0ull) {
-            const int src = (int)__builtin_ctzll(mask);
-            mask &= mask - 1ull;
-            const float ay = bcast(a.y, src), az = bcast(a.z, src);
-            const float sdx2 = bcast(dx2, src), sscale = bcast(scale, src);
-            const float sw = VECTOR ? bcast(w, src) : 1.0f;
-            const int sjlo = bcast(jlo, src), snrows = bcast(nrows, src);
-            const int sseg0 = bcast(seg0, src), snsegs = bcast(nsegs, src);
-            const int slots = snrows * snsegs;
-            const float inv_nsegs = 1.0f / (float)snsegs;
-            for (int s = lane; s < slots; s += 64) {
-                const int row = (int)(((float)s + 0.5f) * inv_nsegs);
-                const int seg = s - row * snsegs;
-                const int j = sjlo + row;
-                const int k4 = (sseg0 + seg) << 2;
-                const float gy = oy + (float)j * res;
-                const float dy = gy - ay;
-                const float base2 = sdx2 + dy * dy;
-                float4 *cell = reinterpret_cast<float4 *>(tile + (j - j0) * pitch + k4);
-                float4 v = *cell;
-                float vv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const float gz = oz + (float)(k4 + u) * res;
-                    const float dz = gz - az;
-                    const float d2 = base2 + dz * dz;
-                    if (BINARY) {
-                        if (d2 <= sscale) vv[u] = 1.0f;
-                    } else {
-                        const float rho = density_from_x2(d2 * sscale, p.kexp, gs.g2, gs.c, gs.c2, gs.A);
-                        vv[u] = VECTOR ? fmaf(sw, rho, vv[u]) : vv[u] + rho;
-                    }
-                }
-                *cell = make_float4(vv[0], vv[1], vv[2], vv[3]);
-            }
-            __builtin_amdgcn_wave_barrier();
-        }
-    }
-
-    // stream the tile out: every element written exactly once
-    float *dst = p.out + ((((size_t)b * T + t) * D + plane) * D + j0) * (size_t)D;
-    if (ALIGNED) {
-        const int n4 = ((j1 - j0) * D) >> 2;
-        float4 *dst4 = reinterpret_cast<float4 *>(dst);
-        const float4 *src4 = reinterpret_cast<const float4 *>(tile);
-        const float4 z4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        // Constant trip count, fully unrolled, and two separate paths (not a select
-        // between an LDS pointer and a zero): a run-time loop bound or a generic-pointer
-        // load makes the compiler wait for all earlier stores before each new one.
-        constexpr int kIters = (kTileFloats / 4 + 127) / 128;
-        if (any) {
-            float4 v0[kIters], v1[kIters];
-#pragma unroll
-            for (int it = 0; it < kIters; ++it) {
-                const int o = min(it * 128 + lane * 2, kTileFloats / 4 - 2);
-                v0[it] = src4[o];
-                v1[it] = src4[o + 1];
-            }
-#pragma unroll
-            for (int it = 0; it < kIters; ++it) {
-                const int o = it * 128 + lane * 2;
-                if (o < n4) dst4[o] = v0[it];
-                if (o + 1 < n4) dst4[o + 1] = v1[it];
-            }
-        } else {
-#pragma unroll
-            for (int it = 0; it < kIters; ++it) {
-                const int o = it * 128 + lane * 2;
-                if (o < n4) dst4[o] = z4;
-                if (o + 1 < n4) dst4[o + 1] = z4;
-            }
+        float r = VECTOR ? r_chan : a.w;
+        bool valid = (lane < count) && (a.w > 0.0f) && (r > 0.0f);
+        if (VECTOR) valid = valid && (BINARY ? (w > 0.0f) : (w != 0.0f));
+        for (int i = i0; i < i1; ++i) {
+            int mode = kUntouched;
+            float bound = 0.0f;
+            const float gx = ox + (float)i * gs.res;
+            plane_batch<VECTOR, BINARY>(cx, gx, a, r, w, valid, mode, bound);
+            store_tile<ALIGNED>(cx, chan + ((size_t)i * D + cx.j0) * D, mode);
         }
     } else {
-        const int n = (j1 - j0) * D;
-        for (int o = lane; o < n; o += 64) {
-            const int row = o / D;
-            const int col = o - row * D;
-            dst[o] = any ? tile[row * pitch + col] : 0.0f;
+        for (int i = i0; i < i1; ++i) {
+            int mode = kUntouched;
+            float bound = 0.0f;
+            const float gx = ox + (float)i * gs.res;
+            for (int base = 0; base < count; base += 64) {
+                const int e = base + lane;
+                float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                float w = 1.0f;
+                if (e < count) {
+                    a = rec[e];
+                    if (VECTOR && a.w > 0.0f) w = p.weights[((size_t)b * N + idx[e]) * T + t];
+                }
+                const float r = VECTOR ? r_chan : a.w;
+                bool valid = (e < count) && (a.w > 0.0f) && (r > 0.0f);
+                if (VECTOR) valid = valid && (BINARY ? (w > 0.0f) : (w != 0.0f));
+                plane_batch<VECTOR, BINARY>(cx, gx, a, r, w, valid, mode, bound);
+            }
+            store_tile<ALIGNED>(cx, chan + ((size_t)i * D + cx.j0) * D, mode);
         }
     }
 }
@@ -223,8 +373,11 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void forward_kernel(FwdParams 
 Tiling make_tiling(int B, int T, int D)
 {
     Tiling tl;
-    tl.pitch = (D + 3) & ~3;
-    int rows_max = kTileFloats / tl.pitch;
+    // LDS rows are padded by 4 floats: with a pitch of D (a multiple of 16 for the usual
+    // grids) the rows of one atom would fall on a few LDS banks only
+    const int d4 = (D + 3) & ~3;
+    tl.pitch = d4 + 4;
+    int rows_max = min(kTileFloats / d4, kTileLds / tl.pitch);
     if (rows_max < 1) rows_max = 1;
     if (rows_max > D) rows_max = D;
     tl.strips = (D + rows_max - 1) / rows_max;
@@ -234,7 +387,7 @@ Tiling make_tiling(int B, int T, int D)
 }
 
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws, float *out,
-                          int xcd_map, hipStream_t stream)
+                          int planes_per_wave, int debug, hipStream_t stream)
 {
     const Tiling tl = make_tiling(bt.B, bt.T, gs.D);
     FwdParams p;
@@ -242,18 +395,19 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     p.rec = ws.rec;
     p.idx = ws.idx;
     p.meta = ws.meta;
+    p.range = ws.range;
     p.weights = bt.weights;
     p.radii = bt.radii;
     p.centers = bt.centers;
     p.out = out;
     p.B = bt.B; p.N = bt.N; p.T = bt.T;
     p.rows = tl.rows; p.strips = tl.strips; p.pitch = tl.pitch;
-    p.units = tl.units;
-    p.groups = 0;
-    p.xcd_map = xcd_map & 1;
-    p.debug = xcd_map >> 4;
+    p.planes_per_wave = planes_per_wave;
+    p.pgroups = (gs.D + planes_per_wave - 1) / planes_per_wave;
+    p.debug = debug;
     p.kexp = -2.8853900817779268f;      // -2 / ln 2
-    const int per_channel = (gs.D * tl.strips + kWavesPerGroup - 1) / kWavesPerGroup;
+    const int items = p.pgroups * tl.strips;
+    const int per_channel = (items + kWavesPerGroup - 1) / kWavesPerGroup;
     const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)out & 15u) == 0);
     const bool vec = bt.weights != nullptr;
     const dim3 blk(64 * kWavesPerGroup), grd(per_channel, bt.T, bt.B);

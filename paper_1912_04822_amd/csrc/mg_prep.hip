@@ -1,5 +1,5 @@
-// Step 1 and 2 of the path: per-example coordinate transform, radius lookup,
-// bounding-box culling and channel binning.
+// Steps 1 and 2 of the path: per-example coordinate transform, radius lookup,
+// bounding-box culling, channel binning and x-plane binning.
 //
 // Transform (Transformations section of the paper): x' = R(q)(x - c) + c + t,
 // q = (w,x,y,z) with (1,0,0,0) the identity.  The arithmetic is double in one
@@ -15,6 +15,15 @@
 //
 // Culling is exact: the density is identically zero beyond c(grm)*r, so an
 // atom whose cutoff cube misses the grid box contributes nothing.
+//
+// One workgroup per group (example b, type t; vector types: example b):
+//   1. stable compaction of the group's atoms (every thread owns a run of
+//      consecutive atoms; a block scan gives each match its rank);
+//   2. transform + cull, bin the survivors by the x-plane they fall in;
+//   3. records are written bin by bin and, inside a bin, in atom order, so the
+//      forward kernel's summation order is fixed;
+//   4. for every plane range one forward wavefront produces, the span of
+//      records that can reach it.
 #include "mg_common.h"
 
 namespace mg {
@@ -22,7 +31,7 @@ namespace mg {
 namespace {
 
 constexpr int kPrepThreads = 256;
-constexpr int kListCap = 1024;      // matches staged in LDS per round
+constexpr int kMaxBins = 1028;      // MG_MAX_POINTS + 2, rounded up
 
 struct Xform {
     double R[9];
@@ -111,17 +120,61 @@ __device__ inline int block_exclusive_scan(int v, int *s_wave, int *total)
     return base + incl - v;
 }
 
-// One workgroup per (type t, example b) for index types; per example for
-// vector types (every atom belongs to the single group).
+struct Culler {
+    float org[3];       // grid origin (center - half)
+    float span;         // (D-1)*res
+    float pad;
+};
+
+// Transformed position, radius and liveness of atom a of example b.
+template <bool VECTOR>
+__device__ inline bool place_atom(const GridSpec &gs, const Batch &bt, const Xform &X,
+                                  const Culler &cu, int b, int t, int a, float vec_reach,
+                                  float *p, float *r_out)
+{
+    apply_xform(X, bt.coords + ((size_t)b * bt.N + a) * 3, p);
+    float r, reach;
+    if (VECTOR) {
+        r = 1.0f;
+        reach = vec_reach;
+    } else {
+        const float rad = gs.radius_type_indexed ? bt.radii[t] : bt.radii[(size_t)b * bt.N + a];
+        r = gs.radius_scale * rad;
+        reach = gs.binary ? r : r * gs.c;
+    }
+    bool live = (r > 0.0f) && (reach < 1.0e30f);
+    for (int k = 0; k < 3; ++k)     // also false for NaN / infinite coordinates
+        live = live && (p[k] >= cu.org[k] - reach - cu.pad) &&
+               (p[k] <= cu.org[k] + cu.span + reach + cu.pad);
+    *r_out = r;
+    return live;
+}
+
+__device__ inline void clear_grads(float *gclear, float *wclear, size_t atom, int T)
+{
+    if (gclear) {
+        float *g = gclear + atom * 3;
+        g[0] = 0.0f; g[1] = 0.0f; g[2] = 0.0f;
+    }
+    if (wclear)
+        for (int k = 0; k < T; ++k) wclear[atom * T + k] = 0.0f;
+}
+
 template <bool VECTOR>
 __global__ __launch_bounds__(256) void prep_kernel(GridSpec gs, Batch bt, Workspace ws,
-                                                   float *gclear, float *wclear)
+                                                   int planes_per_wave, float *gclear,
+                                                   float *wclear)
 {
-    __shared__ int s_list[kListCap];
+    __shared__ int s_list[kSortCap];                // atom index of match m
+    __shared__ unsigned short s_bin[kSortCap];      // x-bin of match m, 0xFFFF = culled
+    __shared__ unsigned short s_order[kSortCap];    // match id at sorted position
+    __shared__ int s_cnt[kMaxBins];                 // records per bin
+    __shared__ int s_pos[kMaxBins];                 // start of bin, then fill cursor
     __shared__ int s_wave[8];
+    __shared__ int s_rmax;
 
     const int b = blockIdx.y, t = blockIdx.x, tid = threadIdx.x;
-    const int N = bt.N, T = bt.T;
+    const int N = bt.N, T = bt.T, D = gs.D;
     int n = N;
     if (bt.natoms) {
         n = bt.natoms[b];
@@ -129,31 +182,34 @@ __global__ __launch_bounds__(256) void prep_kernel(GridSpec gs, Batch bt, Worksp
     }
     const int32_t *ty = VECTOR ? nullptr : bt.types + (size_t)b * N;
 
-    // every thread owns a run of consecutive atoms: keeps the binning stable
+    // ---- 1. stable compaction: thread tid owns atoms [a0, a1) ----
     const int per = (n + kPrepThreads - 1) / kPrepThreads;
     const int a0 = min(n, tid * per), a1 = min(n, a0 + per);
     int less = 0, eq = 0;
     if (VECTOR) {
         eq = a1 - a0;
     } else {
-        for (int a = a0; a < a1; ++a) {
-            const int v = ty[a];
-            less += (v >= 0 && v < t) ? 1 : 0;
-            eq += (v == t) ? 1 : 0;
+        for (int c0 = a0; c0 < a1; c0 += 8) {
+            int v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = (c0 + u < a1) ? ty[c0 + u] : -1;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                less += (v[u] >= 0 && v[u] < t) ? 1 : 0;
+                eq += (v[u] == t) ? 1 : 0;
+            }
         }
     }
     int M, first;
     const int my_first = block_exclusive_scan(eq, s_wave, &M);
     (void)block_exclusive_scan(less, s_wave, &first);
     if (VECTOR) first = 0;
-    if (tid == 0) ws.meta[(size_t)b * T + t] = make_int2(first, M);
 
     Xform X;
     load_xform(X, b, bt.centers, bt.quats, bt.translations);
     if (t == 0 && tid < 9) ws.rot[b * 12 + tid] = (float)X.R[tid];
 
-    // reach of the widest atom of this group, for vector types (radius per channel)
-    float vec_reach = 0.0f;
+    float vec_reach = 0.0f;         // reach of the widest channel, for vector types
     if (VECTOR) {
         for (int k = 0; k < T; ++k) {
             const float r = gs.radius_scale * bt.radii[k];
@@ -161,56 +217,123 @@ __global__ __launch_bounds__(256) void prep_kernel(GridSpec gs, Batch bt, Worksp
         }
         if (!gs.binary) vec_reach *= gs.c;
     }
-    const float pad = 1.0e-3f * gs.res;
-    const float span = (float)(gs.D - 1) * gs.res;
-    float org[3];
-    for (int m = 0; m < 3; ++m)
-        org[m] = (bt.centers ? bt.centers[3 * b + m] : 0.0f) - gs.half;
+    Culler cu;
+    cu.pad = 1.0e-3f * gs.res;
+    cu.span = (float)(D - 1) * gs.res;
+    for (int m = 0; m < 3; ++m) cu.org[m] = (bt.centers ? bt.centers[3 * b + m] : 0.0f) - gs.half;
 
     float4 *rec = ws.rec + (size_t)b * N + first;
     int *idx = ws.idx + (size_t)b * N + first;
+    const size_t group = (size_t)b * T + t;
+    const int nbins = D + 2;
+    const int pgroups = (D + planes_per_wave - 1) / planes_per_wave;
+    int2 *range = ws.range + group * pgroups;
 
-    for (int r0 = 0; r0 < M; r0 += kListCap) {
+    if (M <= kSortCap) {
+        // ---- 2. match list, transform, cull, count per x-bin ----
+        for (int k = tid; k < nbins; k += kPrepThreads) s_cnt[k] = 0;
+        if (tid == 0) s_rmax = 0;
         int rank = my_first;
-        for (int a = a0; a < a1; ++a) {
-            const bool match = VECTOR ? true : (ty[a] == t);
-            if (match) {
-                if (rank >= r0 && rank < r0 + kListCap) s_list[rank - r0] = a;
-                ++rank;
-            }
-        }
+        for (int a = a0; a < a1; ++a)
+            if (VECTOR || ty[a] == t) s_list[rank++] = a;
         __syncthreads();
-        const int cnt = min(kListCap, M - r0);
-        for (int m = tid; m < cnt; m += kPrepThreads) {
+        for (int m = tid; m < M; m += kPrepThreads) {
             const int a = s_list[m];
-            float p[3];
-            apply_xform(X, bt.coords + ((size_t)b * N + a) * 3, p);
-            float r, reach;
-            if (VECTOR) {
-                r = 1.0f;
-                reach = vec_reach;
+            float p[3], r;
+            const bool live = place_atom<VECTOR>(gs, bt, X, cu, b, t, a, vec_reach, p, &r);
+            int bin = 0xFFFF;
+            if (live) {
+                const float f = floorf((p[0] - cu.org[0]) * gs.inv_res);
+                bin = f < 0.0f ? 0 : (f >= (float)D ? D + 1 : (int)f + 1);
+                atomicAdd(&s_cnt[bin], 1);
+                atomicMax(&s_rmax, __float_as_int(r));      // r > 0: ordered like ints
             } else {
-                const float rad = gs.radius_type_indexed ? bt.radii[t] : bt.radii[(size_t)b * N + a];
-                r = gs.radius_scale * rad;
-                reach = gs.binary ? r : r * gs.c;
+                clear_grads(gclear, wclear, (size_t)b * N + a, T);
             }
-            bool live = (r > 0.0f) && (reach < 1.0e30f);
-            for (int k = 0; k < 3; ++k) {
-                // also false for NaN / infinite coordinates
-                live = live && (p[k] >= org[k] - reach - pad) && (p[k] <= org[k] + span + reach + pad);
-            }
-            rec[r0 + m] = make_float4(p[0], p[1], p[2], live ? r : 0.0f);
-            idx[r0 + m] = a;
-            if (!live) {
-                if (gclear) {
-                    float *g = gclear + ((size_t)b * N + a) * 3;
-                    g[0] = 0.0f; g[1] = 0.0f; g[2] = 0.0f;
+            s_bin[m] = (unsigned short)bin;
+        }
+        __syncthreads();
+        // ---- 3. bin starts (exclusive scan over the bins) ----
+        const int bper = (nbins + kPrepThreads - 1) / kPrepThreads;
+        const int k0 = min(nbins, tid * bper), k1 = min(nbins, k0 + bper);
+        int mine = 0;
+        for (int k = k0; k < k1; ++k) mine += s_cnt[k];
+        int L;
+        int run = block_exclusive_scan(mine, s_wave, &L);
+        for (int k = k0; k < k1; ++k) {
+            s_pos[k] = run;
+            run += s_cnt[k];
+        }
+        __syncthreads();
+        // ---- 4. span of records each forward wavefront needs ----
+        // a wavefront producing planes [i0, i1] needs bins [i0 - Rv, i1 + Rv + 1]
+        const float rmax = VECTOR ? vec_reach : __int_as_float(s_rmax) * (gs.binary ? 1.0f : gs.c);
+        const int Rv = (int)ceilf(rmax * gs.inv_res + cu.pad) + 1;
+        for (int pg = tid; pg < pgroups; pg += kPrepThreads) {
+            const int i0 = pg * planes_per_wave, i1 = min(D - 1, i0 + planes_per_wave - 1);
+            const int lo = max(0, i0 - Rv), hi = min(D + 1, i1 + Rv + 1);
+            const int r0 = s_pos[lo];
+            const int r1 = hi + 1 < nbins ? s_pos[hi + 1] : L;
+            range[pg] = make_int2(r0, r1);
+        }
+        __syncthreads();
+        // ---- 5. placement: any order inside a bin, then sort each bin by atom order ----
+        for (int m = tid; m < M; m += kPrepThreads) {
+            const int bin = s_bin[m];
+            if (bin != 0xFFFF) s_order[atomicAdd(&s_pos[bin], 1)] = (unsigned short)m;
+        }
+        __syncthreads();
+        for (int k = tid; k < nbins; k += kPrepThreads) {
+            const int hi = s_pos[k], lo = hi - s_cnt[k];
+            for (int i = lo + 1; i < hi; ++i) {
+                const unsigned short v = s_order[i];
+                int j = i - 1;
+                while (j >= lo && s_order[j] > v) {
+                    s_order[j + 1] = s_order[j];
+                    --j;
                 }
-                if (wclear)
-                    for (int k = 0; k < T; ++k) wclear[((size_t)b * N + a) * T + k] = 0.0f;
+                s_order[j + 1] = v;
             }
         }
         __syncthreads();
+        // ---- 6. records in sorted order ----
+        for (int pos = tid; pos < M; pos += kPrepThreads) {
+            if (pos < L) {
+                const int a = s_list[s_order[pos]];
+                float p[3], r;
+                (void)place_atom<VECTOR>(gs, bt, X, cu, b, t, a, vec_reach, p, &r);
+                rec[pos] = make_float4(p[0], p[1], p[2], r);
+                idx[pos] = a;
+            } else {
+                rec[pos] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                idx[pos] = -1;
+            }
+        }
+        if (tid == 0) ws.meta[group] = make_int4(first, L, M, 1);
+    } else {
+        // ---- group too long to bin: records in atom order, culled ones flagged r = 0 ----
+        for (int r0 = 0; r0 < M; r0 += kSortCap) {
+            int rank = my_first;
+            for (int a = a0; a < a1; ++a) {
+                if (VECTOR || ty[a] == t) {
+                    if (rank >= r0 && rank < r0 + kSortCap) s_list[rank - r0] = a;
+                    ++rank;
+                }
+            }
+            __syncthreads();
+            const int cnt = min(kSortCap, M - r0);
+            for (int m = tid; m < cnt; m += kPrepThreads) {
+                const int a = s_list[m];
+                float p[3], r;
+                const bool live = place_atom<VECTOR>(gs, bt, X, cu, b, t, a, vec_reach, p, &r);
+                rec[r0 + m] = make_float4(p[0], p[1], p[2], live ? r : 0.0f);
+                idx[r0 + m] = a;
+                if (!live) clear_grads(gclear, wclear, (size_t)b * N + a, T);
+            }
+            __syncthreads();
+        }
+        for (int pg = tid; pg < pgroups; pg += kPrepThreads) range[pg] = make_int2(0, M);
+        if (tid == 0) ws.meta[group] = make_int4(first, M, M, 0);
     }
 
     // atoms no group owns (past natoms, type outside [0,T)): zero gradients
@@ -221,40 +344,39 @@ __global__ __launch_bounds__(256) void prep_kernel(GridSpec gs, Batch bt, Worksp
                 const int v = ty[a];
                 orphan = v < 0 || v >= T;
             }
-            if (!orphan) continue;
-            if (gclear) {
-                float *g = gclear + ((size_t)b * N + a) * 3;
-                g[0] = 0.0f; g[1] = 0.0f; g[2] = 0.0f;
-            }
-            if (wclear)
-                for (int k = 0; k < T; ++k) wclear[((size_t)b * N + a) * T + k] = 0.0f;
+            if (orphan) clear_grads(gclear, wclear, (size_t)b * N + a, T);
         }
     }
 }
 
+size_t align16(size_t v) { return (v + 15) / 16 * 16; }
+
 }  // namespace
 
-size_t workspace_bytes(int B, int N, int T)
+size_t workspace_bytes(int B, int N, int T, int D)
 {
-    const size_t bn = (size_t)B * (size_t)N;
-    size_t bytes = bn * sizeof(float4);                         // rec
-    bytes += ((bn * sizeof(int) + 15) / 16) * 16;               // idx
-    bytes += (((size_t)B * T * sizeof(int2) + 15) / 16) * 16;   // meta
-    bytes += (size_t)B * 12 * sizeof(float);                    // rot
+    const size_t bn = (size_t)B * (size_t)N, bt = (size_t)B * (size_t)T;
+    size_t bytes = bn * sizeof(float4);                     // rec
+    bytes += align16(bn * sizeof(int));                     // idx
+    bytes += bt * sizeof(int4);                             // meta
+    bytes += align16(bt * (size_t)D * sizeof(int2));        // range (at most D plane groups)
+    bytes += (size_t)B * 12 * sizeof(float);                // rot
     return bytes;
 }
 
-Workspace carve_workspace(void *base, int B, int N, int T)
+Workspace carve_workspace(void *base, int B, int N, int T, int D)
 {
-    const size_t bn = (size_t)B * (size_t)N;
+    const size_t bn = (size_t)B * (size_t)N, bt = (size_t)B * (size_t)T;
     char *p = (char *)base;
     Workspace ws;
     ws.rec = (float4 *)p;
     p += bn * sizeof(float4);
     ws.idx = (int *)p;
-    p += ((bn * sizeof(int) + 15) / 16) * 16;
-    ws.meta = (int2 *)p;
-    p += (((size_t)B * T * sizeof(int2) + 15) / 16) * 16;
+    p += align16(bn * sizeof(int));
+    ws.meta = (int4 *)p;
+    p += bt * sizeof(int4);
+    ws.range = (int2 *)p;
+    p += align16(bt * (size_t)D * sizeof(int2));
     ws.rot = (float *)p;
     return ws;
 }
@@ -270,14 +392,14 @@ hipError_t launch_transform(int B, int N, const float *coords, const float *cent
 }
 
 hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
-                       float *gclear, float *wclear, hipStream_t stream)
+                       int planes_per_wave, float *gclear, float *wclear, hipStream_t stream)
 {
     if (bt.weights) {
         hipLaunchKernelGGL(prep_kernel<true>, dim3(1, bt.B), dim3(kPrepThreads), 0, stream, gs, bt,
-                           ws, gclear, wclear);
+                           ws, planes_per_wave, gclear, wclear);
     } else {
         hipLaunchKernelGGL(prep_kernel<false>, dim3(bt.T, bt.B), dim3(kPrepThreads), 0, stream, gs,
-                           bt, ws, gclear, wclear);
+                           bt, ws, planes_per_wave, gclear, wclear);
     }
     return hipGetLastError();
 }

@@ -80,7 +80,7 @@ def test_calls_reject_bad_arguments_before_any_launch(L):
     assert rc == 0
     n = sz()
     assert L.mg_workspace_bytes(h, 50, 2040, 28, ctypes.byref(n)) == 0
-    assert 50 * 2040 * 20 <= n.value <= 50 * 2040 * 20 + 50 * 28 * 8 + 50 * 48 + 64
+    assert 50 * 2040 * 20 <= n.value <= 50 * 2040 * 20 + 50 * 28 * (16 + 48 * 8) + 50 * 48 + 64
     assert L.mg_workspace_bytes(h, 0, 2040, 28, ctypes.byref(n)) == -2
     assert L.mg_workspace_bytes(h, 50, 2040, 28, None) == -1
     assert L.mg_workspace_bytes(None, 50, 2040, 28, ctypes.byref(n)) == -1
@@ -119,8 +119,8 @@ def test_calls_reject_bad_arguments_before_any_launch(L):
         assert len(L.mg_strerror(code)) > 1
     assert b"unknown" in L.mg_strerror(-99)
     L.mg_set_option.argtypes = [ctypes.c_char_p, ci]
-    assert L.mg_set_option(b"xcd_map", 1) == 0
-    assert L.mg_set_option(b"xcd_map", 5) == -3
+    assert L.mg_set_option(b"planes_per_wave", 4) == 0
+    assert L.mg_set_option(b"planes_per_wave", 0) == -3
     assert L.mg_set_option(b"nope", 0) == -3
     for hh in (h, hb, hp):
         L.mg_gridmaker_destroy(hh)

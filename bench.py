@@ -92,6 +92,7 @@ def time_call(torch, molgrid, fn, steps, warmup):
     t1 = time.perf_counter()
     kern = ev.elapsed_ms()
     ev.close()
+    time_call.last = kern
     return (t1 - t0) * 1e3 / steps, float(np.mean(kern)), float(np.min(kern))
 
 
@@ -104,6 +105,9 @@ def main():
     ap.add_argument("--rows", action="store_true", help="also time vector/binary/backward rows")
     ap.add_argument("--planes-per-wave", type=int, default=None, help="forward kernel tuning knob")
     ap.add_argument("--debug", type=int, default=None, help="forward kernel timing mode (wrong output)")
+    ap.add_argument("--prep-stop", type=int, default=None, help="timing aid (wrong output)")
+    ap.add_argument("--tile-rows", type=int, default=None, help="forward kernel tuning knob")
+    ap.add_argument("--lds-pad", type=int, default=None, help="forward kernel tuning knob")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size (for scaling rocprofv3 counters)")
     args = ap.parse_args()
@@ -134,6 +138,12 @@ def main():
         molgrid.set_option("planes_per_wave", args.planes_per_wave)
     if args.debug is not None:
         molgrid.set_option("debug", args.debug)
+    if args.tile_rows is not None:
+        molgrid.set_option("tile_rows", args.tile_rows)
+    if args.lds_pad is not None:
+        molgrid.set_option("lds_pad", args.lds_pad)
+    if args.prep_stop is not None:
+        molgrid.set_option("prep_stop", args.prep_stop)
 
     w = workloads.protein_ligand(B=50, with_weights=args.rows, with_grad=args.rows)
     dev = lambda a, dt=None: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
@@ -170,6 +180,7 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "kernel_ms_avg": ms_kernel, "kernel_ms_min": ms_kernel_min,
+                     "kernel_ms_pct": [float(x) for x in np.percentile(time_call.last, [10, 50, 90])],
                      "whole_call_GBs": w.out_bytes / (ms_step * 1e-3) / 1e9,
                      "traffic": stored_traffic("forward_index_protein_ligand")},
     }

@@ -18,7 +18,9 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
-int g_planes_per_wave = 4;
+int g_planes_per_wave = 2;
+int g_tile_rows = 0;
+int g_lds_pad = 0;
 int g_debug = 0;
 
 // Runs `launch` (the main kernel of a call) between the caller's timing events, if set.
@@ -161,7 +163,8 @@ int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T, const float *c
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_planes_per_wave, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
-        return mg::launch_forward(gm->gs, bt, ws, out, g_planes_per_wave, g_debug, (hipStream_t)stream);
+        return mg::launch_forward(gm->gs, bt, ws, out, g_planes_per_wave, g_tile_rows, g_lds_pad,
+                                  g_debug, (hipStream_t)stream);
     }));
 }
 
@@ -186,7 +189,8 @@ int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_planes_per_wave, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
-        return mg::launch_forward(gm->gs, bt, ws, out, g_planes_per_wave, g_debug, (hipStream_t)stream);
+        return mg::launch_forward(gm->gs, bt, ws, out, g_planes_per_wave, g_tile_rows, g_lds_pad,
+                                  g_debug, (hipStream_t)stream);
     }));
 }
 
@@ -277,6 +281,20 @@ int mg_set_option(const char *key, int value)
     if (std::strcmp(key, "planes_per_wave") == 0) {
         if (value < 1 || value > 64) return MG_EPARAM;
         g_planes_per_wave = value;
+        return MG_OK;
+    }
+    if (std::strcmp(key, "tile_rows") == 0) {
+        if (value < 0) return MG_EPARAM;
+        g_tile_rows = value;
+        return MG_OK;
+    }
+    if (std::strcmp(key, "lds_pad") == 0) {
+        if (value < 0 || value > 40000) return MG_EPARAM;
+        g_lds_pad = value;
+        return MG_OK;
+    }
+    if (std::strcmp(key, "prep_stop") == 0) {
+        mg::g_prep_stop = value;
         return MG_OK;
     }
     if (std::strcmp(key, "debug") == 0) {

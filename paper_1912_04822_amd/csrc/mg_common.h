@@ -85,11 +85,12 @@ struct Tiling {
     int pitch;          // floats per row in LDS (D rounded up to 4)
     long long units;    // B*T*D*strips tiles in total
 };
-Tiling make_tiling(int B, int T, int D);
+Tiling make_tiling(int B, int T, int D, int rows_wanted);
 
 constexpr int kTileFloats = 2304;       // LDS floats per wavefront tile (9216 B)
-constexpr int kWavesPerGroup = 1;
 constexpr int kSortCap = 2048;          // longest group the prep kernel bins by x-plane
+
+extern int g_prep_stop;                 // timing aid: stop the prep kernel after a stage
 
 // Launchers (each enqueues on `stream`, returns the hipError_t of the launch).
 hipError_t launch_transform(int B, int N, const float *coords, const float *centers,
@@ -99,7 +100,8 @@ hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                        int planes_per_wave, float *grad_coords_to_clear,
                        float *grad_weights_to_clear, hipStream_t stream);
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
-                          float *out, int planes_per_wave, int debug, hipStream_t stream);
+                          float *out, int planes_per_wave, int tile_rows, int lds_pad, int debug,
+                          hipStream_t stream);
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                            const float *grad_out, float *grad_coords, float *grad_weights,
                            hipStream_t stream);

@@ -42,8 +42,7 @@ namespace mg {
 namespace {
 
 constexpr int kTaskCap = 512;                   // (atom, row) tasks staged per round
-constexpr int kTileLds = 2560;                  // LDS floats of a tile (rows are padded)
-constexpr int kWaveLdsFloats = kTileLds + 64 * 8 + kTaskCap / 2;
+constexpr int kTileLds = 2560;                  // most LDS floats a tile may take (rows are padded)
 constexpr float kFixedOne = 16777216.0f;        // 2^24
 constexpr float kFixedLimit = 120.0f;           // largest |sum| trusted to fixed point
 
@@ -59,6 +58,7 @@ struct FwdParams {
     float *out;
     int B, N, T;
     int rows, strips, pitch;
+    int tile_lds;       // LDS floats reserved for the tile
     int planes_per_wave, pgroups;
     int debug;
     float kexp;         // -2 * log2(e)
@@ -80,6 +80,19 @@ struct TileCtx {
 enum TileMode { kUntouched = 0, kFixed = 1, kFloat = 2 };
 
 __device__ inline int bcast(int v, int src) { return __builtin_amdgcn_readlane(v, src); }
+
+// Inclusive prefix sum over the 64 lanes with DPP row shifts and row broadcasts
+// (no LDS traffic, six adds).
+__device__ inline int wave_inclusive_scan(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);    // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);    // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);    // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);    // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);    // row_bcast:15 -> rows 1,3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);    // row_bcast:31 -> rows 2,3
+    return v;
+}
 
 __device__ inline void lds_sync() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); }
 
@@ -195,12 +208,7 @@ __device__ inline void plane_batch(const TileCtx &cx, float gx, float4 a, float 
         cx.cand[cx.lane * 2 + 1] = make_float4(h2, w, __int_as_float(jlo), 0.0f);
     }
     // exclusive prefix of nrows over the lanes: where each atom's tasks start
-    int incl = nrows;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int up = __shfl_up(incl, d, 64);
-        if (cx.lane >= d) incl += up;
-    }
+    const int incl = wave_inclusive_scan(nrows);
     const int total = bcast(incl, 63);
     if (total <= kTaskCap) {
         const int start = incl - nrows;
@@ -254,16 +262,28 @@ __device__ inline void store_tile(const TileCtx &cx, float *dst, int mode)
                                         (float)__float_as_int(v[it].w) * sc);
                 }
             }
+            // the two 16-byte halves of a lane's 32 bytes go out back to back, under one
+            // predicate: separated by other instructions they are markedly slower
 #pragma unroll
-            for (int it = 0; it < 2 * kIters; ++it) {
-                const int o = (it >> 1) * 128 + cx.lane * 2 + (it & 1);
-                if (o < n4) dst4[o] = v[it];
+            for (int it = 0; it < kIters; ++it) {
+                const int o = it * 128 + cx.lane * 2;
+                if (o + 1 < n4) {
+                    dst4[o] = v[2 * it];
+                    dst4[o + 1] = v[2 * it + 1];
+                } else if (o < n4) {
+                    dst4[o] = v[2 * it];
+                }
             }
         } else {
 #pragma unroll
-            for (int it = 0; it < 2 * kIters; ++it) {
-                const int o = (it >> 1) * 128 + cx.lane * 2 + (it & 1);
-                if (o < n4) dst4[o] = z4;
+            for (int it = 0; it < kIters; ++it) {
+                const int o = it * 128 + cx.lane * 2;
+                if (o + 1 < n4) {
+                    dst4[o] = z4;
+                    dst4[o + 1] = z4;
+                } else if (o < n4) {
+                    dst4[o] = z4;
+                }
             }
         }
     } else {
@@ -282,37 +302,44 @@ __device__ inline void store_tile(const TileCtx &cx, float *dst, int mode)
 }
 
 template <bool VECTOR, bool BINARY, bool ALIGNED>
-__global__ __launch_bounds__(64 * kWavesPerGroup) void forward_kernel(FwdParams p)
+__global__ __launch_bounds__(64) void forward_kernel(FwdParams p)
 {
-    __shared__ __attribute__((aligned(16))) float lds[kWavesPerGroup * kWaveLdsFloats];
+    extern __shared__ __attribute__((aligned(16))) float lds[];   // tile | candidates | tasks
 
-    // grid: x = work items (strip, plane group) of one channel, y = channel, z = example
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // grid: x = plane group of one channel, y = channel, z = example; one wavefront each
+    const int lane = threadIdx.x;
     const GridSpec &gs = p.gs;
     const int D = gs.D, T = p.T, N = p.N;
-    const int wi = (int)blockIdx.x * kWavesPerGroup + wave;
-    if (wi >= p.pgroups * p.strips) return;
+    const int pg = (int)blockIdx.x;
     const int t = (int)blockIdx.y, b = (int)blockIdx.z;
-    const int pg = p.strips == 1 ? wi : wi / p.strips;
-    const int strip = p.strips == 1 ? 0 : wi - pg * p.strips;
     const int i0 = pg * p.planes_per_wave;
     const int i1 = min(D, i0 + p.planes_per_wave);
 
     TileCtx cx;
-    cx.tile = lds + wave * kWaveLdsFloats;
-    cx.cand = reinterpret_cast<float4 *>(cx.tile + kTileLds);
-    cx.tasks = reinterpret_cast<unsigned short *>(cx.tile + kTileLds + 64 * 8);
+    cx.tile = lds;
+    cx.cand = reinterpret_cast<float4 *>(cx.tile + p.tile_lds);
+    cx.tasks = reinterpret_cast<unsigned short *>(cx.tile + p.tile_lds + 64 * 8);
     cx.lane = lane;
     cx.D = D;
     cx.pitch = p.pitch;
-    cx.j0 = strip * p.rows;
-    cx.j1 = min(D, cx.j0 + p.rows);
+    cx.j0 = 0;
+    cx.j1 = 0;
     cx.res = gs.res;
     cx.inv_res = gs.inv_res;
     cx.g2 = gs.g2; cx.c = gs.c; cx.A = gs.A; cx.kexp = p.kexp;
     cx.inv_d4 = 1.0f / (float)max(1, D >> 2);
     cx.debug = p.debug;
 
+    float *chan0 = p.out + ((size_t)b * T + t) * D * D * (size_t)D;
+    if (p.debug == 3) {         // timing aid: nothing but the zero stores
+        for (int i = i0; i < i1; ++i)
+            for (int strip = 0; strip < p.strips; ++strip) {
+                cx.j0 = strip * p.rows;
+                cx.j1 = min(D, cx.j0 + p.rows);
+                store_tile<ALIGNED>(cx, chan0 + ((size_t)i * D + cx.j0) * D, kUntouched);
+            }
+        return;
+    }
     const size_t group = (size_t)b * T + (VECTOR ? 0 : t);
     const int4 m = p.meta[group];
     int2 span = p.range[group * p.pgroups + pg];
@@ -339,14 +366,21 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void forward_kernel(FwdParams 
         bool valid = (lane < count) && (a.w > 0.0f) && (r > 0.0f);
         if (VECTOR) valid = valid && (BINARY ? (w > 0.0f) : (w != 0.0f));
         for (int i = i0; i < i1; ++i) {
-            int mode = kUntouched;
-            float bound = 0.0f;
             const float gx = ox + (float)i * gs.res;
-            plane_batch<VECTOR, BINARY>(cx, gx, a, r, w, valid, mode, bound);
-            store_tile<ALIGNED>(cx, chan + ((size_t)i * D + cx.j0) * D, mode);
+            for (int strip = 0; strip < p.strips; ++strip) {
+                cx.j0 = strip * p.rows;
+                cx.j1 = min(D, cx.j0 + p.rows);
+                int mode = kUntouched;
+                float bound = 0.0f;
+                if (count > 0) plane_batch<VECTOR, BINARY>(cx, gx, a, r, w, valid, mode, bound);
+                store_tile<ALIGNED>(cx, chan + ((size_t)i * D + cx.j0) * D, mode);
+            }
         }
     } else {
-        for (int i = i0; i < i1; ++i) {
+        for (int i = i0; i < i1; ++i)
+        for (int strip = 0; strip < p.strips; ++strip) {
+            cx.j0 = strip * p.rows;
+            cx.j1 = min(D, cx.j0 + p.rows);
             int mode = kUntouched;
             float bound = 0.0f;
             const float gx = ox + (float)i * gs.res;
@@ -370,7 +404,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void forward_kernel(FwdParams 
 
 }  // namespace
 
-Tiling make_tiling(int B, int T, int D)
+Tiling make_tiling(int B, int T, int D, int rows_wanted)
 {
     Tiling tl;
     // LDS rows are padded by 4 floats: with a pitch of D (a multiple of 16 for the usual
@@ -378,6 +412,7 @@ Tiling make_tiling(int B, int T, int D)
     const int d4 = (D + 3) & ~3;
     tl.pitch = d4 + 4;
     int rows_max = min(kTileFloats / d4, kTileLds / tl.pitch);
+    if (rows_wanted > 0 && rows_wanted < rows_max) rows_max = rows_wanted;
     if (rows_max < 1) rows_max = 1;
     if (rows_max > D) rows_max = D;
     tl.strips = (D + rows_max - 1) / rows_max;
@@ -387,9 +422,10 @@ Tiling make_tiling(int B, int T, int D)
 }
 
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws, float *out,
-                          int planes_per_wave, int debug, hipStream_t stream)
+                          int planes_per_wave, int tile_rows, int lds_pad, int debug,
+                          hipStream_t stream)
 {
-    const Tiling tl = make_tiling(bt.B, bt.T, gs.D);
+    const Tiling tl = make_tiling(bt.B, bt.T, gs.D, tile_rows);
     FwdParams p;
     p.gs = gs;
     p.rec = ws.rec;
@@ -402,17 +438,17 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     p.out = out;
     p.B = bt.B; p.N = bt.N; p.T = bt.T;
     p.rows = tl.rows; p.strips = tl.strips; p.pitch = tl.pitch;
+    p.tile_lds = (tl.rows * tl.pitch + 3) & ~3;
     p.planes_per_wave = planes_per_wave;
     p.pgroups = (gs.D + planes_per_wave - 1) / planes_per_wave;
     p.debug = debug;
     p.kexp = -2.8853900817779268f;      // -2 / ln 2
-    const int items = p.pgroups * tl.strips;
-    const int per_channel = (items + kWavesPerGroup - 1) / kWavesPerGroup;
+    const size_t lds_bytes = ((size_t)p.tile_lds + 64 * 8 + kTaskCap / 2) * sizeof(float) + lds_pad;
     const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)out & 15u) == 0);
     const bool vec = bt.weights != nullptr;
-    const dim3 blk(64 * kWavesPerGroup), grd(per_channel, bt.T, bt.B);
+    const dim3 blk(64), grd(p.pgroups, bt.T, bt.B);
 #define MG_LAUNCH(V, Bn, Al) \
-    hipLaunchKernelGGL((forward_kernel<V, Bn, Al>), grd, blk, 0, stream, p)
+    hipLaunchKernelGGL((forward_kernel<V, Bn, Al>), grd, blk, lds_bytes, stream, p)
     if (vec) {
         if (gs.binary) { if (aligned) MG_LAUNCH(true, true, true); else MG_LAUNCH(true, true, false); }
         else           { if (aligned) MG_LAUNCH(true, false, true); else MG_LAUNCH(true, false, false); }

@@ -16,9 +16,9 @@
 // Culling is exact: the density is identically zero beyond c(grm)*r, so an
 // atom whose cutoff cube misses the grid box contributes nothing.
 //
-// One workgroup per group (example b, type t; vector types: example b):
-//   1. stable compaction of the group's atoms (every thread owns a run of
-//      consecutive atoms; a block scan gives each match its rank);
+// One wavefront per group (example b, type t; vector types: example b):
+//   1. stable compaction of the group's atoms (every lane owns a run of
+//      consecutive atoms; a wavefront scan gives each match its rank);
 //   2. transform + cull, bin the survivors by the x-plane they fall in;
 //   3. records are written bin by bin and, inside a bin, in atom order, so the
 //      forward kernel's summation order is fixed;
@@ -30,7 +30,7 @@ namespace mg {
 
 namespace {
 
-constexpr int kPrepThreads = 256;
+constexpr int kPrepThreads = 64;
 constexpr int kMaxBins = 1028;      // MG_MAX_POINTS + 2, rounded up
 
 struct Xform {
@@ -97,28 +97,21 @@ __global__ __launch_bounds__(256) void transform_kernel(int B, int N, const floa
     out[k + 2] = o[2];
 }
 
-// Exclusive prefix sum of `v` over the 256 threads of the block; *total gets the sum.
-__device__ inline int block_exclusive_scan(int v, int *s_wave, int *total)
+// Exclusive prefix sum of `v` over the 64 lanes of the wavefront; *total gets the sum.
+__device__ inline int wave_exclusive_scan(int v, int *total)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
     int incl = v;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
         const int up = __shfl_up(incl, d, 64);
         if (lane >= d) incl += up;
     }
-    if (lane == 63) s_wave[wave] = incl;
-    __syncthreads();
-    int base = 0, sum = 0;
-    for (int w = 0; w < kPrepThreads / 64; ++w) {
-        const int c = s_wave[w];
-        if (w < wave) base += c;
-        sum += c;
-    }
-    __syncthreads();
-    *total = sum;
-    return base + incl - v;
+    *total = __builtin_amdgcn_readlane(incl, 63);
+    return incl - v;
 }
+
+__device__ inline void lds_sync() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); }
 
 struct Culler {
     float org[3];       // grid origin (center - half)
@@ -160,21 +153,22 @@ __device__ inline void clear_grads(float *gclear, float *wclear, size_t atom, in
         for (int k = 0; k < T; ++k) wclear[atom * T + k] = 0.0f;
 }
 
+// One wavefront per group: no barriers, the scans are wavefront shuffles.
 template <bool VECTOR>
-__global__ __launch_bounds__(256) void prep_kernel(GridSpec gs, Batch bt, Workspace ws,
-                                                   int planes_per_wave, float *gclear,
-                                                   float *wclear)
+__global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspace ws,
+                                                  int planes_per_wave, float *gclear,
+                                                  float *wclear, int stop)
 {
     __shared__ int s_list[kSortCap];                // atom index of match m
     __shared__ unsigned short s_bin[kSortCap];      // x-bin of match m, 0xFFFF = culled
     __shared__ unsigned short s_order[kSortCap];    // match id at sorted position
     __shared__ int s_cnt[kMaxBins];                 // records per bin
     __shared__ int s_pos[kMaxBins];                 // start of bin, then fill cursor
-    __shared__ int s_wave[8];
     __shared__ int s_rmax;
 
-    const int b = blockIdx.y, t = blockIdx.x, tid = threadIdx.x;
+    const int b = blockIdx.y, t = blockIdx.x, lane = threadIdx.x;
     const int N = bt.N, T = bt.T, D = gs.D;
+    if (stop == 1) return;
     int n = N;
     if (bt.natoms) {
         n = bt.natoms[b];
@@ -182,32 +176,38 @@ __global__ __launch_bounds__(256) void prep_kernel(GridSpec gs, Batch bt, Worksp
     }
     const int32_t *ty = VECTOR ? nullptr : bt.types + (size_t)b * N;
 
-    // ---- 1. stable compaction: thread tid owns atoms [a0, a1) ----
-    const int per = (n + kPrepThreads - 1) / kPrepThreads;
-    const int a0 = min(n, tid * per), a1 = min(n, a0 + per);
+    Xform X;
+    load_xform(X, b, bt.centers, bt.quats, bt.translations);
+
+    // ---- 1. stable compaction: lane owns atoms [a0, a1) ----
+    const int per = (n + 63) / 64;
+    const int a0 = min(n, lane * per), a1 = min(n, a0 + per);
     int less = 0, eq = 0;
+    unsigned long long eqmask = 0ull;       // matches among the first 64 atoms of the run
     if (VECTOR) {
         eq = a1 - a0;
     } else {
-        for (int c0 = a0; c0 < a1; c0 += 8) {
-            int v[8];
+        for (int c0 = a0; c0 < a1; c0 += 16) {
+            int v[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = (c0 + u < a1) ? ty[c0 + u] : -1;
+            for (int u = 0; u < 16; ++u) v[u] = (c0 + u < a1) ? ty[c0 + u] : -1;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < 16; ++u) {
                 less += (v[u] >= 0 && v[u] < t) ? 1 : 0;
-                eq += (v[u] == t) ? 1 : 0;
+                if (v[u] == t) {
+                    ++eq;
+                    if (c0 - a0 + u < 64) eqmask |= 1ull << (c0 - a0 + u);
+                }
             }
         }
     }
+    if (stop == 2) { if (less + eq == 12345) ws.rot[0] = 1.0f; return; }
     int M, first;
-    const int my_first = block_exclusive_scan(eq, s_wave, &M);
-    (void)block_exclusive_scan(less, s_wave, &first);
+    const int my_first = wave_exclusive_scan(eq, &M);
+    (void)wave_exclusive_scan(less, &first);
     if (VECTOR) first = 0;
-
-    Xform X;
-    load_xform(X, b, bt.centers, bt.quats, bt.translations);
-    if (t == 0 && tid < 9) ws.rot[b * 12 + tid] = (float)X.R[tid];
+    if (t == 0 && lane < 9) ws.rot[b * 12 + lane] = (float)X.R[lane];
+    if (stop == 3) { if (M + first == 12345) ws.rot[0] = 1.0f; return; }
 
     float vec_reach = 0.0f;         // reach of the widest channel, for vector types
     if (VECTOR) {
@@ -231,13 +231,22 @@ __global__ __launch_bounds__(256) void prep_kernel(GridSpec gs, Batch bt, Worksp
 
     if (M <= kSortCap) {
         // ---- 2. match list, transform, cull, count per x-bin ----
-        for (int k = tid; k < nbins; k += kPrepThreads) s_cnt[k] = 0;
-        if (tid == 0) s_rmax = 0;
+        for (int k = lane; k < nbins; k += 64) s_cnt[k] = 0;
+        if (lane == 0) s_rmax = 0;
         int rank = my_first;
-        for (int a = a0; a < a1; ++a)
-            if (VECTOR || ty[a] == t) s_list[rank++] = a;
-        __syncthreads();
-        for (int m = tid; m < M; m += kPrepThreads) {
+        if (VECTOR) {
+            for (int a = a0; a < a1; ++a) s_list[rank++] = a;
+        } else {
+            unsigned long long mk = eqmask;
+            while (mk != 0ull) {
+                s_list[rank++] = a0 + (int)__builtin_ctzll(mk);
+                mk &= mk - 1ull;
+            }
+            for (int a = a0 + 64; a < a1; ++a)
+                if (ty[a] == t) s_list[rank++] = a;
+        }
+        lds_sync();
+        for (int m = lane; m < M; m += 64) {
             const int a = s_list[m];
             float p[3], r;
             const bool live = place_atom<VECTOR>(gs, bt, X, cu, b, t, a, vec_reach, p, &r);
@@ -252,38 +261,40 @@ __global__ __launch_bounds__(256) void prep_kernel(GridSpec gs, Batch bt, Worksp
             }
             s_bin[m] = (unsigned short)bin;
         }
-        __syncthreads();
+        lds_sync();
+        if (stop == 4) return;
         // ---- 3. bin starts (exclusive scan over the bins) ----
-        const int bper = (nbins + kPrepThreads - 1) / kPrepThreads;
-        const int k0 = min(nbins, tid * bper), k1 = min(nbins, k0 + bper);
+        const int bper = (nbins + 63) / 64;
+        const int k0 = min(nbins, lane * bper), k1 = min(nbins, k0 + bper);
         int mine = 0;
         for (int k = k0; k < k1; ++k) mine += s_cnt[k];
         int L;
-        int run = block_exclusive_scan(mine, s_wave, &L);
+        int run = wave_exclusive_scan(mine, &L);
         for (int k = k0; k < k1; ++k) {
             s_pos[k] = run;
             run += s_cnt[k];
         }
-        __syncthreads();
+        lds_sync();
         // ---- 4. span of records each forward wavefront needs ----
         // a wavefront producing planes [i0, i1] needs bins [i0 - Rv, i1 + Rv + 1]
         const float rmax = VECTOR ? vec_reach : __int_as_float(s_rmax) * (gs.binary ? 1.0f : gs.c);
         const int Rv = (int)ceilf(rmax * gs.inv_res + cu.pad) + 1;
-        for (int pg = tid; pg < pgroups; pg += kPrepThreads) {
+        for (int pg = lane; pg < pgroups; pg += 64) {
             const int i0 = pg * planes_per_wave, i1 = min(D - 1, i0 + planes_per_wave - 1);
             const int lo = max(0, i0 - Rv), hi = min(D + 1, i1 + Rv + 1);
             const int r0 = s_pos[lo];
             const int r1 = hi + 1 < nbins ? s_pos[hi + 1] : L;
             range[pg] = make_int2(r0, r1);
         }
-        __syncthreads();
+        lds_sync();
+        if (stop == 5) return;
         // ---- 5. placement: any order inside a bin, then sort each bin by atom order ----
-        for (int m = tid; m < M; m += kPrepThreads) {
+        for (int m = lane; m < M; m += 64) {
             const int bin = s_bin[m];
             if (bin != 0xFFFF) s_order[atomicAdd(&s_pos[bin], 1)] = (unsigned short)m;
         }
-        __syncthreads();
-        for (int k = tid; k < nbins; k += kPrepThreads) {
+        lds_sync();
+        for (int k = lane; k < nbins; k += 64) {
             const int hi = s_pos[k], lo = hi - s_cnt[k];
             for (int i = lo + 1; i < hi; ++i) {
                 const unsigned short v = s_order[i];
@@ -295,9 +306,10 @@ __global__ __launch_bounds__(256) void prep_kernel(GridSpec gs, Batch bt, Worksp
                 s_order[j + 1] = v;
             }
         }
-        __syncthreads();
-        // ---- 6. records in sorted order ----
-        for (int pos = tid; pos < M; pos += kPrepThreads) {
+        lds_sync();
+        if (stop == 6) return;
+        // ---- 6. records in sorted order (the transform is cheap: done again) ----
+        for (int pos = lane; pos < M; pos += 64) {
             if (pos < L) {
                 const int a = s_list[s_order[pos]];
                 float p[3], r;
@@ -309,7 +321,7 @@ __global__ __launch_bounds__(256) void prep_kernel(GridSpec gs, Batch bt, Worksp
                 idx[pos] = -1;
             }
         }
-        if (tid == 0) ws.meta[group] = make_int4(first, L, M, 1);
+        if (lane == 0) ws.meta[group] = make_int4(first, L, M, 1);
     } else {
         // ---- group too long to bin: records in atom order, culled ones flagged r = 0 ----
         for (int r0 = 0; r0 < M; r0 += kSortCap) {
@@ -320,9 +332,9 @@ __global__ __launch_bounds__(256) void prep_kernel(GridSpec gs, Batch bt, Worksp
                     ++rank;
                 }
             }
-            __syncthreads();
+            lds_sync();
             const int cnt = min(kSortCap, M - r0);
-            for (int m = tid; m < cnt; m += kPrepThreads) {
+            for (int m = lane; m < cnt; m += 64) {
                 const int a = s_list[m];
                 float p[3], r;
                 const bool live = place_atom<VECTOR>(gs, bt, X, cu, b, t, a, vec_reach, p, &r);
@@ -330,15 +342,15 @@ __global__ __launch_bounds__(256) void prep_kernel(GridSpec gs, Batch bt, Worksp
                 idx[r0 + m] = a;
                 if (!live) clear_grads(gclear, wclear, (size_t)b * N + a, T);
             }
-            __syncthreads();
+            lds_sync();
         }
-        for (int pg = tid; pg < pgroups; pg += kPrepThreads) range[pg] = make_int2(0, M);
-        if (tid == 0) ws.meta[group] = make_int4(first, M, M, 0);
+        for (int pg = lane; pg < pgroups; pg += 64) range[pg] = make_int2(0, M);
+        if (lane == 0) ws.meta[group] = make_int4(first, M, M, 0);
     }
 
     // atoms no group owns (past natoms, type outside [0,T)): zero gradients
     if (t == 0 && (gclear || wclear)) {
-        for (int a = tid; a < N; a += kPrepThreads) {
+        for (int a = lane; a < N; a += 64) {
             bool orphan = a >= n;
             if (!VECTOR && !orphan) {
                 const int v = ty[a];
@@ -391,15 +403,17 @@ hipError_t launch_transform(int B, int N, const float *coords, const float *cent
     return hipGetLastError();
 }
 
+int g_prep_stop = 0;
 hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                        int planes_per_wave, float *gclear, float *wclear, hipStream_t stream)
 {
+    const int stop = g_prep_stop;
     if (bt.weights) {
         hipLaunchKernelGGL(prep_kernel<true>, dim3(1, bt.B), dim3(kPrepThreads), 0, stream, gs, bt,
-                           ws, planes_per_wave, gclear, wclear);
+                           ws, planes_per_wave, gclear, wclear, stop);
     } else {
         hipLaunchKernelGGL(prep_kernel<false>, dim3(bt.T, bt.B), dim3(kPrepThreads), 0, stream, gs,
-                           bt, ws, planes_per_wave, gclear, wclear);
+                           bt, ws, planes_per_wave, gclear, wclear, stop);
     }
     return hipGetLastError();
 }

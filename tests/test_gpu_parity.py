@@ -135,7 +135,7 @@ def test_forward_protein_ligand_subset_and_determinism(mg):
         try:
             other = run_forward_index(mg, w)
         finally:
-            mg.set_option("planes_per_wave", 4)
+            mg.set_option("planes_per_wave", 2)
         # the knob changes the order in which overlapping atoms are summed: equal to rounding
         assert np.abs(got - other).max() <= 2e-6
         assert np.abs(other - ref).max() <= GRID_TOL

@@ -103,10 +103,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--rows", action="store_true", help="also time vector/binary/backward rows")
-    ap.add_argument("--planes-per-wave", type=int, default=None, help="forward kernel tuning knob")
+    ap.add_argument("--tile-floats", type=int, default=None, help="forward kernel tuning knob")
     ap.add_argument("--debug", type=int, default=None, help="forward kernel timing mode (wrong output)")
     ap.add_argument("--prep-stop", type=int, default=None, help="timing aid (wrong output)")
-    ap.add_argument("--tile-rows", type=int, default=None, help="forward kernel tuning knob")
     ap.add_argument("--lds-pad", type=int, default=None, help="forward kernel tuning knob")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size (for scaling rocprofv3 counters)")
@@ -134,12 +133,10 @@ def main():
 
     from paper_1912_04822_amd import molgrid, workloads
     molgrid.lib()                       # raises if the HIP library is missing: no fallback
-    if args.planes_per_wave is not None:
-        molgrid.set_option("planes_per_wave", args.planes_per_wave)
+    if args.tile_floats is not None:
+        molgrid.set_option("tile_floats", args.tile_floats)
     if args.debug is not None:
         molgrid.set_option("debug", args.debug)
-    if args.tile_rows is not None:
-        molgrid.set_option("tile_rows", args.tile_rows)
     if args.lds_pad is not None:
         molgrid.set_option("lds_pad", args.lds_pad)
     if args.prep_stop is not None:

@@ -156,9 +156,12 @@ int mg_last_hip_error(void);
 
 /*
  * Tuning knobs of the forward kernel, for measurement only (results do not
- * depend on them).  key "planes_per_wave" (1..64, default 4): consecutive
- * x-planes one wavefront produces; key "debug" (0..3): 0 = normal, other
- * values skip parts of the kernel to time the rest (output then wrong).
+ * depend on them beyond rounding).  key "tile_floats" (512, 1024, 2048 or 4096,
+ * default 2048): consecutive output floats one wavefront produces; key "debug"
+ * (0..3): 0 = normal, 1 = no density evaluation, 2 = no atoms, 3 = stores only
+ * (the output is then wrong: for timing the parts of the kernel); key
+ * "lds_pad" (0..40000): extra LDS bytes per workgroup, lowers residency; key
+ * "prep_stop" (0..6): end the prep kernel after that stage (wrong output).
  * Returns MG_EPARAM for an unknown key or value.
  */
 int mg_set_option(const char *key, int value);

@@ -18,8 +18,7 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
-int g_planes_per_wave = 2;
-int g_tile_rows = 0;
+int g_tile_floats = 2048;
 int g_lds_pad = 0;
 int g_debug = 0;
 
@@ -160,11 +159,11 @@ int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T, const float *c
     const mg::Batch bt = make_batch(B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
                                     translations);
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_planes_per_wave, nullptr, nullptr, (hipStream_t)stream));
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
-        return mg::launch_forward(gm->gs, bt, ws, out, g_planes_per_wave, g_tile_rows, g_lds_pad,
-                                  g_debug, (hipStream_t)stream);
+        return mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_lds_pad, g_debug,
+                                  (hipStream_t)stream);
     }));
 }
 
@@ -186,11 +185,11 @@ int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *
     const mg::Batch bt = make_batch(B, N, T, coords, nullptr, weights, radii, natoms, centers,
                                     quats, translations);
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_planes_per_wave, nullptr, nullptr, (hipStream_t)stream));
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
-        return mg::launch_forward(gm->gs, bt, ws, out, g_planes_per_wave, g_tile_rows, g_lds_pad,
-                                  g_debug, (hipStream_t)stream);
+        return mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_lds_pad, g_debug,
+                                  (hipStream_t)stream);
     }));
 }
 
@@ -213,7 +212,7 @@ int mg_backward_index(const mg_gridmaker *gm, int B, int N, int T, const float *
     const mg::Batch bt = make_batch(B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
                                     translations);
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_planes_per_wave, grad_coords, nullptr, (hipStream_t)stream));
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
         return mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, nullptr,
@@ -242,7 +241,7 @@ int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T, const float 
     const mg::Batch bt = make_batch(B, N, T, coords, nullptr, weights, radii, natoms, centers,
                                     quats, translations);
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_planes_per_wave, grad_coords, grad_weights,
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, grad_weights,
                                     (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
@@ -278,14 +277,9 @@ int mg_time_next_kernel(void *start_event, void *stop_event)
 int mg_set_option(const char *key, int value)
 {
     if (!key) return MG_ENULL;
-    if (std::strcmp(key, "planes_per_wave") == 0) {
-        if (value < 1 || value > 64) return MG_EPARAM;
-        g_planes_per_wave = value;
-        return MG_OK;
-    }
-    if (std::strcmp(key, "tile_rows") == 0) {
-        if (value < 0) return MG_EPARAM;
-        g_tile_rows = value;
+    if (std::strcmp(key, "tile_floats") == 0) {
+        if (value != 512 && value != 1024 && value != 2048 && value != 4096) return MG_EPARAM;
+        g_tile_floats = value;
         return MG_OK;
     }
     if (std::strcmp(key, "lds_pad") == 0) {

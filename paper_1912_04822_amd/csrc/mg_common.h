@@ -48,10 +48,10 @@ struct GridSpec {
 //   meta  [B][T] int4     {first, live, all, sorted}; sorted = 0 means the
 //                         group was too long to bin: its records are in atom
 //                         order, culled ones carry r = 0, and live == all
-//   range [B][T][PG] int2 for plane group pg (the planes_per_wave consecutive
-//                         x-planes one forward wavefront produces): the span
-//                         [r0, r1) of the group's records, relative to `first`,
-//                         that can reach those planes; PG = ceil(D/planes_per_wave)
+//   range [B][T][D] int2  for x-plane i: the span [r0, r1) of records, counted
+//                         from the example's first record rec[b][0], that can
+//                         reach the plane.  r0 and r1 do not decrease with i, so
+//                         planes i..k are reached by [range[i].x, range[k].y)
 //   rot   [B][12] float   rotation matrix rows (9 used), for the backward pass
 // ---------------------------------------------------------------------------
 struct Workspace {
@@ -77,17 +77,17 @@ struct Batch {
     const float   *translations;  // [B][3] or null
 };
 
-// Tile geometry of the forward kernel: every wavefront owns `rows` consecutive
-// z-rows of one x-plane of one channel (a contiguous run of rows*D floats).
-struct Tiling {
-    int rows;           // rows per tile
-    int strips;         // tiles per x-plane = ceil(D / rows)
-    int pitch;          // floats per row in LDS (D rounded up to 4)
-    long long units;    // B*T*D*strips tiles in total
+// Geometry of the forward kernel: every wavefront owns one flat tile of
+// `tile_floats` consecutive floats of one channel (the last tile of a channel
+// may be shorter).
+struct ForwardGeometry {
+    int tile_floats;    // 512, 1024, 2048 or 4096
+    int tiles;          // tiles per channel = ceil(D^3 / tile_floats)
+    int pitch;          // floats per row in LDS (D rounded up to 4, plus 4)
+    int tile_lds;       // LDS floats for the rows a tile can touch
 };
-Tiling make_tiling(int B, int T, int D, int rows_wanted);
+ForwardGeometry forward_geometry(int D, int tile_floats);
 
-constexpr int kTileFloats = 2304;       // LDS floats per wavefront tile (9216 B)
 constexpr int kSortCap = 2048;          // longest group the prep kernel bins by x-plane
 
 extern int g_prep_stop;                 // timing aid: stop the prep kernel after a stage
@@ -97,10 +97,10 @@ hipError_t launch_transform(int B, int N, const float *coords, const float *cent
                             const float *quats, const float *translations, float *out,
                             hipStream_t stream);
 hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
-                       int planes_per_wave, float *grad_coords_to_clear,
-                       float *grad_weights_to_clear, hipStream_t stream);
+                       float *grad_coords_to_clear, float *grad_weights_to_clear,
+                       hipStream_t stream);
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
-                          float *out, int planes_per_wave, int tile_rows, int lds_pad, int debug,
+                          float *out, int tile_floats, int lds_pad, int debug,
                           hipStream_t stream);
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                            const float *grad_out, float *grad_coords, float *grad_weights,

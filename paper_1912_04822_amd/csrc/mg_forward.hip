@@ -1,32 +1,38 @@
 // Steps 3-5 of the path: the forward atom-to-grid kernel (index types, vector
 // types, binary occupancy), GridMaker section of the paper.
 //
-// Design (gfx950, wave64).  The output [B][T][D][D][D] is cut into tiles: a
-// tile is `rows` consecutive z-rows of one x-plane of one channel, i.e. one
-// contiguous run of rows*D floats (9216 B at D = 48).  A wavefront produces
-// `planes_per_wave` consecutive x-planes of one channel, one tile at a time:
-//   1. once: it loads the records of the channel's atoms that can reach its
-//      planes (the span the prep kernel computed), one atom per lane;
-//   2. per plane, each lane tests its atom against the tile (disc of the
-//      atom's cutoff sphere in this x-plane versus the tile's rows); the
-//      (atom, row) pairs that survive are packed into a task list, so that all
-//      64 lanes work even though a single atom's footprint is small;
+// Design (gfx950, wave64).  Each channel of the output (D*D*D floats, z fastest)
+// is cut into flat tiles of `tile_floats` consecutive floats (2048 = 8192 B by
+// default), whatever rows and x-planes that run happens to cover; with the
+// usual grids (D = 48, 96) every tile starts on a 4 KB boundary of the output.
+// One wavefront produces one tile:
+//   1. it loads the records of the channel's atoms that can reach the x-planes
+//      the tile touches (spans the prep kernel computed), one atom per lane;
+//   2. per x-plane of the tile, each lane tests its atom against the tile's
+//      rows in that plane (disc of the atom's cutoff sphere in the plane versus
+//      the row range); the (atom, row) pairs that survive are packed into a
+//      task list, so that all 64 lanes work even though one atom's footprint is
+//      small;
 //   3. each lane takes one task: the chord of the atom's sphere along that
-//      z-row.  It evaluates the density voxel by voxel and adds it into the
-//      tile held in LDS with LDS atomics (two atoms may hit one voxel in the
-//      same instruction).  The tile accumulates in signed fixed point (2^-24
-//      steps, integer LDS atomics): integer adds run ~40x faster in LDS than
-//      float adds on this chip, are exact and order-independent, and a
-//      contribution is rounded by at most 3e-8.  The sum of the magnitudes that
-//      can reach a voxel is tracked; if it could pass 120 (fixed-point range is
-//      +-128) the tile switches to float accumulation;
+//      z-row, clipped to the tile in its first and last row.  It evaluates the
+//      density voxel by voxel and adds it into the tile held in LDS with LDS
+//      atomics (two atoms may hit one voxel in the same instruction).  The tile
+//      accumulates in signed fixed point (2^-24 steps, integer LDS atomics):
+//      integer adds run ~40x faster in LDS than float adds on this chip, are
+//      exact and order-independent, and a contribution is rounded by at most
+//      3e-8.  The sum of the magnitudes that can reach a voxel is tracked; if it
+//      could pass 120 (fixed-point range is +-128) the tile switches to float
+//      accumulation;
 //   4. the finished tile is streamed to HBM, each lane writing 32 contiguous
 //      bytes (two adjacent 16-byte stores), every output element exactly once,
 //      zeros included.  Tiles no atom touches skip LDS and store zeros.
-// No barrier is needed: a wavefront only touches its own LDS slice.  The store
-// phase has a compile-time trip count and no loads from global memory happen
-// after the first plane, so stores of one plane are still in flight while the
-// next plane is computed.
+// No barrier is needed: a wavefront only touches its own LDS slice.
+//
+// Why 8 KB tiles on 4 KB boundaries: measured on this chip, one-wavefront
+// workgroups that each write one aligned 4 KB or 8 KB run sustain 6.3-6.6 TB/s
+// at any residency, with or without work between the stores, while runs of
+// 6, 9, 18 or 36 KB per wavefront (whole x-planes of a 48^3 grid are 9 KB) fall
+// to 5.2-5.4 TB/s.
 //
 // The density is rho(x) = exp(-2x^2) for x <= g, A(x-c)^2 for g < x < c, else 0
 // (x = d/r); evaluated from x^2 with the hardware exp2 and sqrt.
@@ -42,7 +48,6 @@ namespace mg {
 namespace {
 
 constexpr int kTaskCap = 512;                   // (atom, row) tasks staged per round
-constexpr int kTileLds = 2560;                  // most LDS floats a tile may take (rows are padded)
 constexpr float kFixedOne = 16777216.0f;        // 2^24
 constexpr float kFixedLimit = 120.0f;           // largest |sum| trusted to fixed point
 
@@ -50,27 +55,30 @@ struct FwdParams {
     GridSpec gs;
     const float4 *rec;
     const int *idx;
-    const int4 *meta;
     const int2 *range;
     const float *weights;
     const float *radii;
     const float *centers;
     float *out;
     int B, N, T;
-    int rows, strips, pitch;
+    int tile_floats;    // floats per tile (a multiple of 512)
+    int pitch;          // floats per row in LDS
     int tile_lds;       // LDS floats reserved for the tile
-    int planes_per_wave, pgroups;
     int debug;
     float kexp;         // -2 * log2(e)
 };
 
 // what a wavefront keeps for the tile it is working on (all wave-uniform)
 struct TileCtx {
-    float *tile;
+    float *tile0;       // LDS: first row of the tile
+    int tile_n4;        // float4s of LDS the tile's rows take
+    float *tile;        // LDS: row j0 of the current x-plane
     float4 *cand;
     unsigned short *tasks;
     int lane;
-    int D, pitch, j0, j1;
+    int D, pitch, j0, j1;       // rows [j0, j1) of the current plane belong to the tile
+    int jfirst, cfirst;         // row of this plane that is the tile's first row (-1: none) and
+    int jlast, clast;           // its first column; same for the last row / last column
     float res, inv_res, oy, oz;
     float g2, c, A, kexp;
     float inv_d4;       // 1 / (D/4)
@@ -125,8 +133,9 @@ __device__ inline void run_tasks(const TileCtx &cx, int ntasks)
         act = act && rem > 0.0f;
         const float hz = __builtin_amdgcn_sqrtf(fmaxf(rem, 0.0f)) * cx.inv_res + 1.0e-3f;
         const float fz = (az - cx.oz) * cx.inv_res;
-        const int klo = max(0, (int)ceilf(fz - hz));
-        const int khi = min(cx.D - 1, (int)floorf(fz + hz));
+        // the chord, clipped to the grid and (first / last row of the tile) to the tile
+        const int klo = max(j == cx.jfirst ? cx.cfirst : 0, (int)ceilf(fz - hz));
+        const int khi = min(j == cx.jlast ? cx.clast : cx.D - 1, (int)floorf(fz + hz));
         const int nz = act ? khi - klo + 1 : 0;
         float *rowp = cx.tile + (j - cx.j0) * cx.pitch + klo;
         if (BINARY) {
@@ -160,8 +169,10 @@ __device__ inline void run_tasks(const TileCtx &cx, int ntasks)
     lds_sync();
 }
 
-// One batch of up to 64 atom records (one per lane) against one tile.
+// One batch of up to 64 atom records (one per lane) against the rows [j0, j1) of one
+// x-plane of the tile.
 //   a = {x', y', z', r};  valid: this lane holds a live record;  w: weight (vector types)
+//   mode: state of the whole tile;  bound: running bound for this plane
 template <bool VECTOR, bool BINARY>
 __device__ inline void plane_batch(const TileCtx &cx, float gx, float4 a, float r, float w,
                                    bool valid, int &mode, float &bound)
@@ -191,15 +202,14 @@ __device__ inline void plane_batch(const TileCtx &cx, float gx, float4 a, float 
     } else {
         bound += (float)__builtin_popcountll(mask);
     }
-    const int n4 = ((cx.j1 - cx.j0) * cx.pitch) >> 2;
     if (mode == kUntouched) {
         mode = (BINARY || bound > kFixedLimit) ? kFloat : kFixed;
         const float4 z4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);     // same bits as integer zeros
-        for (int o = cx.lane; o < n4; o += 64) reinterpret_cast<float4 *>(cx.tile)[o] = z4;
+        for (int o = cx.lane; o < cx.tile_n4; o += 64) reinterpret_cast<float4 *>(cx.tile0)[o] = z4;
     } else if (mode == kFixed && bound > kFixedLimit) {
         mode = kFloat;                                               // leave fixed point
-        for (int o = cx.lane; o < n4 * 4; o += 64)
-            cx.tile[o] = (float)reinterpret_cast<int *>(cx.tile)[o] * (1.0f / kFixedOne);
+        for (int o = cx.lane; o < cx.tile_n4 * 4; o += 64)
+            cx.tile0[o] = (float)reinterpret_cast<int *>(cx.tile0)[o] * (1.0f / kFixedOne);
     }
     lds_sync();
     const int nrows = ok ? jhi - jlo + 1 : 0;
@@ -230,31 +240,32 @@ __device__ inline void plane_batch(const TileCtx &cx, float gx, float4 a, float 
     }
 }
 
-// Stream a finished tile to HBM (or zeros if no atom touched it).
-template <bool ALIGNED>
-__device__ inline void store_tile(const TileCtx &cx, float *dst, int mode)
+// Stream a finished tile to HBM (or zeros if no atom touched it): n floats to dst; the
+// first of them sits in column c0 of the tile's first LDS row.
+// ITERS = tile_floats / 512: each pass of the wavefront covers 2 KB.
+template <bool ALIGNED, int ITERS>
+__device__ inline void store_tile(const TileCtx &cx, float *dst, int c0, int n, int mode)
 {
     if (ALIGNED) {
-        const int n4 = ((cx.j1 - cx.j0) * cx.D) >> 2;
-        const int d4 = cx.D >> 2, p4 = cx.pitch >> 2;
+        const int n4 = n >> 2;                      // even: D^3 and the tile size are multiples of 8
+        const int d4 = cx.D >> 2, p4 = cx.pitch >> 2, q0 = c0 >> 2;
         float4 *dst4 = reinterpret_cast<float4 *>(dst);
-        const float4 *src4 = reinterpret_cast<const float4 *>(cx.tile);
+        const float4 *src4 = reinterpret_cast<const float4 *>(cx.tile0);
         const float4 z4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        // Constant trip count, fully unrolled, and separate paths (not a select between
-        // an LDS pointer and a zero): a generic-pointer load would make the compiler
-        // wait for all earlier stores before each new one.
-        constexpr int kIters = (kTileFloats / 4 + 127) / 128;
+        // Constant trip count, fully unrolled; the tile comes from LDS into registers
+        // under a wave-uniform branch (zeros otherwise), so that the stores below are one
+        // straight sequence with no load between them.
+        float4 v[2 * ITERS];
         if (mode != kUntouched) {
-            float4 v[2 * kIters];
 #pragma unroll
-            for (int it = 0; it < 2 * kIters; ++it) {
-                const int o = min((it >> 1) * 128 + cx.lane * 2 + (it & 1), n4 - 1);
+            for (int it = 0; it < 2 * ITERS; ++it) {
+                const int o = min((it >> 1) * 128 + cx.lane * 2 + (it & 1), n4 - 1) + q0;
                 const int row = (int)(((float)o + 0.5f) * cx.inv_d4);
                 v[it] = src4[row * p4 + (o - row * d4)];            // rows are padded in LDS
             }
             if (mode == kFixed) {
 #pragma unroll
-                for (int it = 0; it < 2 * kIters; ++it) {
+                for (int it = 0; it < 2 * ITERS; ++it) {
                     const float sc = 1.0f / kFixedOne;
                     v[it] = make_float4((float)__float_as_int(v[it].x) * sc,
                                         (float)__float_as_int(v[it].y) * sc,
@@ -262,201 +273,196 @@ __device__ inline void store_tile(const TileCtx &cx, float *dst, int mode)
                                         (float)__float_as_int(v[it].w) * sc);
                 }
             }
-            // the two 16-byte halves of a lane's 32 bytes go out back to back, under one
-            // predicate: separated by other instructions they are markedly slower
-#pragma unroll
-            for (int it = 0; it < kIters; ++it) {
-                const int o = it * 128 + cx.lane * 2;
-                if (o + 1 < n4) {
-                    dst4[o] = v[2 * it];
-                    dst4[o + 1] = v[2 * it + 1];
-                } else if (o < n4) {
-                    dst4[o] = v[2 * it];
-                }
-            }
         } else {
 #pragma unroll
-            for (int it = 0; it < kIters; ++it) {
-                const int o = it * 128 + cx.lane * 2;
-                if (o + 1 < n4) {
-                    dst4[o] = z4;
-                    dst4[o + 1] = z4;
-                } else if (o < n4) {
-                    dst4[o] = z4;
-                }
+            for (int it = 0; it < 2 * ITERS; ++it) v[it] = z4;
+        }
+        // the two 16-byte halves of a lane's 32 bytes go out back to back, under one
+        // predicate: separated by other instructions they are markedly slower
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int o = it * 128 + cx.lane * 2;
+            if (o < n4) {
+                dst4[o] = v[2 * it];
+                dst4[o + 1] = v[2 * it + 1];
             }
         }
     } else {
-        const int n = (cx.j1 - cx.j0) * cx.D;
         for (int o = cx.lane; o < n; o += 64) {
-            const int row = o / cx.D;
-            const int col = o - row * cx.D;
+            const int f = o + c0;
+            const int row = f / cx.D;
+            const int col = f - row * cx.D;
             float v = 0.0f;
-            if (mode == kFloat) v = cx.tile[row * cx.pitch + col];
+            if (mode == kFloat) v = cx.tile0[row * cx.pitch + col];
             if (mode == kFixed)
-                v = (float)reinterpret_cast<const int *>(cx.tile)[row * cx.pitch + col] *
+                v = (float)reinterpret_cast<const int *>(cx.tile0)[row * cx.pitch + col] *
                     (1.0f / kFixedOne);
             dst[o] = v;
         }
     }
 }
 
-template <bool VECTOR, bool BINARY, bool ALIGNED>
+template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS>
 __global__ __launch_bounds__(64) void forward_kernel(FwdParams p)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];   // tile | candidates | tasks
 
-    // grid: x = plane group of one channel, y = channel, z = example; one wavefront each
+    // grid: x = tile of one channel, y = channel, z = example; one wavefront each
     const int lane = threadIdx.x;
     const GridSpec &gs = p.gs;
     const int D = gs.D, T = p.T, N = p.N;
-    const int pg = (int)blockIdx.x;
     const int t = (int)blockIdx.y, b = (int)blockIdx.z;
-    const int i0 = pg * p.planes_per_wave;
-    const int i1 = min(D, i0 + p.planes_per_wave);
+
+    // the tile: floats [f0, f1) of the channel = rows [R0, R1) of its D*D rows, the first
+    // from column c0 on, the last up to column c1
+    const int total = D * D * D;
+    const int f0 = (int)blockIdx.x * p.tile_floats;
+    const int f1 = min(total, f0 + p.tile_floats);
+    const int R0 = f0 / D, R1 = (f1 - 1) / D + 1;
+    const int c0 = f0 - R0 * D, c1 = f1 - 1 - (R1 - 1) * D;
+    const int i_lo = R0 / D, i_hi = (R1 - 1) / D;
 
     TileCtx cx;
+    cx.tile0 = lds;
+    cx.tile_n4 = ((R1 - R0) * p.pitch) >> 2;
     cx.tile = lds;
-    cx.cand = reinterpret_cast<float4 *>(cx.tile + p.tile_lds);
-    cx.tasks = reinterpret_cast<unsigned short *>(cx.tile + p.tile_lds + 64 * 8);
+    cx.cand = reinterpret_cast<float4 *>(lds + p.tile_lds);
+    cx.tasks = reinterpret_cast<unsigned short *>(lds + p.tile_lds + 64 * 8);
     cx.lane = lane;
     cx.D = D;
     cx.pitch = p.pitch;
     cx.j0 = 0;
     cx.j1 = 0;
+    cx.jfirst = -1; cx.cfirst = c0;
+    cx.jlast = -1; cx.clast = c1;
     cx.res = gs.res;
     cx.inv_res = gs.inv_res;
     cx.g2 = gs.g2; cx.c = gs.c; cx.A = gs.A; cx.kexp = p.kexp;
     cx.inv_d4 = 1.0f / (float)max(1, D >> 2);
     cx.debug = p.debug;
 
-    float *chan0 = p.out + ((size_t)b * T + t) * D * D * (size_t)D;
+    float *dst = p.out + ((size_t)b * T + t) * (size_t)total + f0;
     if (p.debug == 3) {         // timing aid: nothing but the zero stores
-        for (int i = i0; i < i1; ++i)
-            for (int strip = 0; strip < p.strips; ++strip) {
-                cx.j0 = strip * p.rows;
-                cx.j1 = min(D, cx.j0 + p.rows);
-                store_tile<ALIGNED>(cx, chan0 + ((size_t)i * D + cx.j0) * D, kUntouched);
-            }
+        store_tile<ALIGNED, ITERS>(cx, dst, c0, f1 - f0, kUntouched);
         return;
     }
     const size_t group = (size_t)b * T + (VECTOR ? 0 : t);
-    const int4 m = p.meta[group];
-    int2 span = p.range[group * p.pgroups + pg];
+    // records (relative to the example's first) that can reach planes i_lo .. i_hi
+    const int r0 = p.range[group * D + i_lo].x;
+    const int r1 = p.debug == 2 ? r0 : p.range[group * D + i_hi].y;
     const float ox = (p.centers ? p.centers[3 * b + 0] : 0.0f) - gs.half;
     cx.oy = (p.centers ? p.centers[3 * b + 1] : 0.0f) - gs.half;
     cx.oz = (p.centers ? p.centers[3 * b + 2] : 0.0f) - gs.half;
     const float r_chan = VECTOR ? gs.radius_scale * p.radii[t] : 0.0f;
-    if (p.debug == 2) span.y = span.x;
 
-    const float4 *rec = p.rec + (size_t)b * N + m.x + span.x;
-    const int *idx = p.idx + (size_t)b * N + m.x + span.x;
-    const int count = span.y - span.x;
-    float *chan = p.out + ((size_t)b * T + t) * D * D * (size_t)D;
+    const float4 *rec = p.rec + (size_t)b * N + r0;
+    const int *idx = p.idx + (size_t)b * N + r0;
+    const int count = r1 - r0;
 
-    if (count <= 64) {
-        // the usual case: every atom that can reach these planes sits in one lane
-        float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        float w = 1.0f;
-        if (lane < count) {
-            a = rec[lane];
-            if (VECTOR && a.w > 0.0f) w = p.weights[((size_t)b * N + idx[lane]) * T + t];
-        }
-        float r = VECTOR ? r_chan : a.w;
-        bool valid = (lane < count) && (a.w > 0.0f) && (r > 0.0f);
-        if (VECTOR) valid = valid && (BINARY ? (w > 0.0f) : (w != 0.0f));
-        for (int i = i0; i < i1; ++i) {
-            const float gx = ox + (float)i * gs.res;
-            for (int strip = 0; strip < p.strips; ++strip) {
-                cx.j0 = strip * p.rows;
-                cx.j1 = min(D, cx.j0 + p.rows);
-                int mode = kUntouched;
-                float bound = 0.0f;
-                if (count > 0) plane_batch<VECTOR, BINARY>(cx, gx, a, r, w, valid, mode, bound);
-                store_tile<ALIGNED>(cx, chan + ((size_t)i * D + cx.j0) * D, mode);
-            }
-        }
-    } else {
-        for (int i = i0; i < i1; ++i)
-        for (int strip = 0; strip < p.strips; ++strip) {
-            cx.j0 = strip * p.rows;
-            cx.j1 = min(D, cx.j0 + p.rows);
-            int mode = kUntouched;
-            float bound = 0.0f;
-            const float gx = ox + (float)i * gs.res;
+    // the usual case: every atom that can reach the tile sits in one lane, loaded once
+    const bool once = count <= 64;
+    float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    float w = 1.0f;
+    if (once && lane < count) {
+        a = rec[lane];
+        if (VECTOR && a.w > 0.0f) w = p.weights[((size_t)b * N + idx[lane]) * T + t];
+    }
+    float r = VECTOR ? r_chan : a.w;
+    bool valid = (lane < count) && (a.w > 0.0f) && (r > 0.0f);
+    if (VECTOR) valid = valid && (BINARY ? (w > 0.0f) : (w != 0.0f));
+
+    int mode = kUntouched;
+    for (int i = i_lo; i <= i_hi && count > 0; ++i) {
+        // rows of plane i inside the tile
+        const int ja = max(R0 - i * D, 0), jb = min(R1 - i * D, D);
+        cx.j0 = ja;
+        cx.j1 = jb;
+        cx.tile = cx.tile0 + (i * D + ja - R0) * p.pitch;
+        cx.jfirst = (i == i_lo) ? ja : -1;
+        cx.jlast = (i == i_hi) ? jb - 1 : -1;
+        const float gx = ox + (float)i * gs.res;
+        float bound = 0.0f;         // planes do not share voxels: one bound per plane
+        if (once) {
+            plane_batch<VECTOR, BINARY>(cx, gx, a, r, w, valid, mode, bound);
+        } else {
             for (int base = 0; base < count; base += 64) {
                 const int e = base + lane;
-                float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                float w = 1.0f;
+                a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                w = 1.0f;
                 if (e < count) {
                     a = rec[e];
                     if (VECTOR && a.w > 0.0f) w = p.weights[((size_t)b * N + idx[e]) * T + t];
                 }
-                const float r = VECTOR ? r_chan : a.w;
-                bool valid = (e < count) && (a.w > 0.0f) && (r > 0.0f);
+                r = VECTOR ? r_chan : a.w;
+                valid = (e < count) && (a.w > 0.0f) && (r > 0.0f);
                 if (VECTOR) valid = valid && (BINARY ? (w > 0.0f) : (w != 0.0f));
                 plane_batch<VECTOR, BINARY>(cx, gx, a, r, w, valid, mode, bound);
             }
-            store_tile<ALIGNED>(cx, chan + ((size_t)i * D + cx.j0) * D, mode);
         }
     }
+    store_tile<ALIGNED, ITERS>(cx, dst, c0, f1 - f0, mode);
 }
 
 }  // namespace
 
-Tiling make_tiling(int B, int T, int D, int rows_wanted)
+ForwardGeometry forward_geometry(int D, int tile_floats)
 {
-    Tiling tl;
+    ForwardGeometry fg;
+    fg.tile_floats = tile_floats;
+    const long long total = (long long)D * D * D;
+    fg.tiles = (int)((total + tile_floats - 1) / tile_floats);
     // LDS rows are padded by 4 floats: with a pitch of D (a multiple of 16 for the usual
     // grids) the rows of one atom would fall on a few LDS banks only
-    const int d4 = (D + 3) & ~3;
-    tl.pitch = d4 + 4;
-    int rows_max = min(kTileFloats / d4, kTileLds / tl.pitch);
-    if (rows_wanted > 0 && rows_wanted < rows_max) rows_max = rows_wanted;
-    if (rows_max < 1) rows_max = 1;
-    if (rows_max > D) rows_max = D;
-    tl.strips = (D + rows_max - 1) / rows_max;
-    tl.rows = (D + tl.strips - 1) / tl.strips;
-    tl.units = (long long)B * T * D * tl.strips;
-    return tl;
+    fg.pitch = ((D + 3) & ~3) + 4;
+    // a run of tile_floats floats touches at most tile_floats/D + 2 rows
+    long long rows = (long long)tile_floats / D + 2;
+    if (rows > (long long)D * D) rows = (long long)D * D;
+    fg.tile_lds = (int)((rows * fg.pitch + 3) & ~3LL);
+    return fg;
 }
 
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws, float *out,
-                          int planes_per_wave, int tile_rows, int lds_pad, int debug,
-                          hipStream_t stream)
+                          int tile_floats, int lds_pad, int debug, hipStream_t stream)
 {
-    const Tiling tl = make_tiling(bt.B, bt.T, gs.D, tile_rows);
+    const ForwardGeometry fg = forward_geometry(gs.D, tile_floats);
     FwdParams p;
     p.gs = gs;
     p.rec = ws.rec;
     p.idx = ws.idx;
-    p.meta = ws.meta;
     p.range = ws.range;
     p.weights = bt.weights;
     p.radii = bt.radii;
     p.centers = bt.centers;
     p.out = out;
     p.B = bt.B; p.N = bt.N; p.T = bt.T;
-    p.rows = tl.rows; p.strips = tl.strips; p.pitch = tl.pitch;
-    p.tile_lds = (tl.rows * tl.pitch + 3) & ~3;
-    p.planes_per_wave = planes_per_wave;
-    p.pgroups = (gs.D + planes_per_wave - 1) / planes_per_wave;
+    p.tile_floats = fg.tile_floats;
+    p.pitch = fg.pitch;
+    p.tile_lds = fg.tile_lds;
     p.debug = debug;
     p.kexp = -2.8853900817779268f;      // -2 / ln 2
     const size_t lds_bytes = ((size_t)p.tile_lds + 64 * 8 + kTaskCap / 2) * sizeof(float) + lds_pad;
     const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)out & 15u) == 0);
     const bool vec = bt.weights != nullptr;
-    const dim3 blk(64), grd(p.pgroups, bt.T, bt.B);
-#define MG_LAUNCH(V, Bn, Al) \
-    hipLaunchKernelGGL((forward_kernel<V, Bn, Al>), grd, blk, lds_bytes, stream, p)
+    const dim3 blk(64), grd(fg.tiles, bt.T, bt.B);
+#define MG_LAUNCH4(V, Bn, Al, It) \
+    hipLaunchKernelGGL((forward_kernel<V, Bn, Al, It>), grd, blk, lds_bytes, stream, p)
+#define MG_LAUNCH(V, Bn, Al)                            \
+    switch (tile_floats) {                              \
+    case 512: MG_LAUNCH4(V, Bn, Al, 1); break;          \
+    case 1024: MG_LAUNCH4(V, Bn, Al, 2); break;         \
+    case 2048: MG_LAUNCH4(V, Bn, Al, 4); break;         \
+    case 4096: MG_LAUNCH4(V, Bn, Al, 8); break;         \
+    default: return hipErrorInvalidValue;               \
+    }
     if (vec) {
-        if (gs.binary) { if (aligned) MG_LAUNCH(true, true, true); else MG_LAUNCH(true, true, false); }
-        else           { if (aligned) MG_LAUNCH(true, false, true); else MG_LAUNCH(true, false, false); }
+        if (gs.binary) { if (aligned) MG_LAUNCH(true, true, true) else MG_LAUNCH(true, true, false) }
+        else           { if (aligned) MG_LAUNCH(true, false, true) else MG_LAUNCH(true, false, false) }
     } else {
-        if (gs.binary) { if (aligned) MG_LAUNCH(false, true, true); else MG_LAUNCH(false, true, false); }
-        else           { if (aligned) MG_LAUNCH(false, false, true); else MG_LAUNCH(false, false, false); }
+        if (gs.binary) { if (aligned) MG_LAUNCH(false, true, true) else MG_LAUNCH(false, true, false) }
+        else           { if (aligned) MG_LAUNCH(false, false, true) else MG_LAUNCH(false, false, false) }
     }
 #undef MG_LAUNCH
+#undef MG_LAUNCH4
     return hipGetLastError();
 }
 

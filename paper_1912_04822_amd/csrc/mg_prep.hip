@@ -22,8 +22,7 @@
 //   2. transform + cull, bin the survivors by the x-plane they fall in;
 //   3. records are written bin by bin and, inside a bin, in atom order, so the
 //      forward kernel's summation order is fixed;
-//   4. for every plane range one forward wavefront produces, the span of
-//      records that can reach it.
+//   4. for every x-plane, the span of records that can reach it.
 #include "mg_common.h"
 
 namespace mg {
@@ -156,8 +155,7 @@ __device__ inline void clear_grads(float *gclear, float *wclear, size_t atom, in
 // One wavefront per group: no barriers, the scans are wavefront shuffles.
 template <bool VECTOR>
 __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspace ws,
-                                                  int planes_per_wave, float *gclear,
-                                                  float *wclear, int stop)
+                                                  float *gclear, float *wclear, int stop)
 {
     __shared__ int s_list[kSortCap];                // atom index of match m
     __shared__ unsigned short s_bin[kSortCap];      // x-bin of match m, 0xFFFF = culled
@@ -226,8 +224,7 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
     int *idx = ws.idx + (size_t)b * N + first;
     const size_t group = (size_t)b * T + t;
     const int nbins = D + 2;
-    const int pgroups = (D + planes_per_wave - 1) / planes_per_wave;
-    int2 *range = ws.range + group * pgroups;
+    int2 *range = ws.range + group * D;
 
     if (M <= kSortCap) {
         // ---- 2. match list, transform, cull, count per x-bin ----
@@ -275,16 +272,15 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
             run += s_cnt[k];
         }
         lds_sync();
-        // ---- 4. span of records each forward wavefront needs ----
-        // a wavefront producing planes [i0, i1] needs bins [i0 - Rv, i1 + Rv + 1]
+        // ---- 4. span of records that can reach each plane ----
+        // plane i is reached from bins [i - Rv, i + Rv + 1]
         const float rmax = VECTOR ? vec_reach : __int_as_float(s_rmax) * (gs.binary ? 1.0f : gs.c);
         const int Rv = (int)ceilf(rmax * gs.inv_res + cu.pad) + 1;
-        for (int pg = lane; pg < pgroups; pg += 64) {
-            const int i0 = pg * planes_per_wave, i1 = min(D - 1, i0 + planes_per_wave - 1);
-            const int lo = max(0, i0 - Rv), hi = min(D + 1, i1 + Rv + 1);
+        for (int i = lane; i < D; i += 64) {
+            const int lo = max(0, i - Rv), hi = min(D + 1, i + Rv + 1);
             const int r0 = s_pos[lo];
             const int r1 = hi + 1 < nbins ? s_pos[hi + 1] : L;
-            range[pg] = make_int2(r0, r1);
+            range[i] = make_int2(first + r0, first + r1);
         }
         lds_sync();
         if (stop == 5) return;
@@ -344,7 +340,7 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
             }
             lds_sync();
         }
-        for (int pg = lane; pg < pgroups; pg += 64) range[pg] = make_int2(0, M);
+        for (int i = lane; i < D; i += 64) range[i] = make_int2(first, first + M);
         if (lane == 0) ws.meta[group] = make_int4(first, M, M, 0);
     }
 
@@ -371,7 +367,7 @@ size_t workspace_bytes(int B, int N, int T, int D)
     size_t bytes = bn * sizeof(float4);                     // rec
     bytes += align16(bn * sizeof(int));                     // idx
     bytes += bt * sizeof(int4);                             // meta
-    bytes += align16(bt * (size_t)D * sizeof(int2));        // range (at most D plane groups)
+    bytes += align16(bt * (size_t)D * sizeof(int2));        // range (one entry per x-plane)
     bytes += (size_t)B * 12 * sizeof(float);                // rot
     return bytes;
 }
@@ -404,16 +400,16 @@ hipError_t launch_transform(int B, int N, const float *coords, const float *cent
 }
 
 int g_prep_stop = 0;
-hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
-                       int planes_per_wave, float *gclear, float *wclear, hipStream_t stream)
+hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws, float *gclear,
+                       float *wclear, hipStream_t stream)
 {
     const int stop = g_prep_stop;
     if (bt.weights) {
         hipLaunchKernelGGL(prep_kernel<true>, dim3(1, bt.B), dim3(kPrepThreads), 0, stream, gs, bt,
-                           ws, planes_per_wave, gclear, wclear, stop);
+                           ws, gclear, wclear, stop);
     } else {
         hipLaunchKernelGGL(prep_kernel<false>, dim3(bt.T, bt.B), dim3(kPrepThreads), 0, stream, gs,
-                           bt, ws, planes_per_wave, gclear, wclear, stop);
+                           bt, ws, gclear, wclear, stop);
     }
     return hipGetLastError();
 }

@@ -119,8 +119,8 @@ def test_calls_reject_bad_arguments_before_any_launch(L):
         assert len(L.mg_strerror(code)) > 1
     assert b"unknown" in L.mg_strerror(-99)
     L.mg_set_option.argtypes = [ctypes.c_char_p, ci]
-    assert L.mg_set_option(b"planes_per_wave", 4) == 0
-    assert L.mg_set_option(b"planes_per_wave", 0) == -3
+    assert L.mg_set_option(b"tile_floats", 2048) == 0
+    assert L.mg_set_option(b"tile_floats", 1000) == -3
     assert L.mg_set_option(b"nope", 0) == -3
     for hh in (h, hb, hp):
         L.mg_gridmaker_destroy(hh)

@@ -130,12 +130,12 @@ def test_forward_protein_ligand_subset_and_determinism(mg):
     assert got.max() > 1.0
     again = run_forward_index(mg, w)
     assert np.array_equal(got.view(np.uint32), again.view(np.uint32))
-    for ppw in (1, 3, 48):
-        mg.set_option("planes_per_wave", ppw)
+    for tile_floats in (512, 1024, 4096):
+        mg.set_option("tile_floats", tile_floats)
         try:
             other = run_forward_index(mg, w)
         finally:
-            mg.set_option("planes_per_wave", 2)
+            mg.set_option("tile_floats", 2048)
         # the knob changes the order in which overlapping atoms are summed: equal to rounding
         assert np.abs(got - other).max() <= 2e-6
         assert np.abs(other - ref).max() <= GRID_TOL

@@ -107,6 +107,7 @@ def main():
     ap.add_argument("--debug", type=int, default=None, help="forward kernel timing mode (wrong output)")
     ap.add_argument("--prep-stop", type=int, default=None, help="timing aid (wrong output)")
     ap.add_argument("--lds-pad", type=int, default=None, help="forward kernel tuning knob")
+    ap.add_argument("--xcd-run", type=int, default=None, help="forward kernel tuning knob")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size (for scaling rocprofv3 counters)")
     args = ap.parse_args()
@@ -137,6 +138,8 @@ def main():
         molgrid.set_option("tile_floats", args.tile_floats)
     if args.debug is not None:
         molgrid.set_option("debug", args.debug)
+    if args.xcd_run is not None:
+        molgrid.set_option("xcd_run", args.xcd_run)
     if args.lds_pad is not None:
         molgrid.set_option("lds_pad", args.lds_pad)
     if args.prep_stop is not None:

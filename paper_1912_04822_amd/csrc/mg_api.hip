@@ -19,6 +19,7 @@ namespace {
 thread_local int g_last_hip_error = 0;
 thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 int g_tile_floats = 2048;
+int g_xcd_run = 0;
 int g_lds_pad = 0;
 int g_debug = 0;
 
@@ -43,8 +44,9 @@ int check_shape(const mg_gridmaker *gm, int B, int N, int T)
     if (B < 1 || N < 1 || T < 1) return MG_ESHAPE;
     if (B > 65535 || T > 65535) return MG_ESHAPE;         // grid.y, grid.z of the launches
     const long long D = gm->gs.D;
-    const long long tiles = (long long)B * T * D * D;     // upper bound on forward tiles
+    const long long tiles = (long long)B * T * ((D * D * D + 511) / 512);   // forward workgroups
     if (tiles > 0x7fffffffLL) return MG_ESHAPE;
+    if ((long long)B * T * D * D > 0x7fffffffLL) return MG_ESHAPE;
     if ((long long)B * N > 0x7fffffffLL / 32) return MG_ESHAPE;
     return MG_OK;
 }
@@ -162,7 +164,7 @@ int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T, const float *c
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
-        return mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_lds_pad, g_debug,
+        return mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_xcd_run, g_lds_pad, g_debug,
                                   (hipStream_t)stream);
     }));
 }
@@ -188,7 +190,7 @@ int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
-        return mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_lds_pad, g_debug,
+        return mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_xcd_run, g_lds_pad, g_debug,
                                   (hipStream_t)stream);
     }));
 }
@@ -280,6 +282,11 @@ int mg_set_option(const char *key, int value)
     if (std::strcmp(key, "tile_floats") == 0) {
         if (value != 512 && value != 1024 && value != 2048 && value != 4096) return MG_EPARAM;
         g_tile_floats = value;
+        return MG_OK;
+    }
+    if (std::strcmp(key, "xcd_run") == 0) {
+        if (value < 0 || value > 32768 || (value & (value - 1)) != 0) return MG_EPARAM;
+        g_xcd_run = value;
         return MG_OK;
     }
     if (std::strcmp(key, "lds_pad") == 0) {

@@ -83,8 +83,6 @@ struct Batch {
 struct ForwardGeometry {
     int tile_floats;    // 512, 1024, 2048 or 4096
     int tiles;          // tiles per channel = ceil(D^3 / tile_floats)
-    int pitch;          // floats per row in LDS (D rounded up to 4, plus 4)
-    int tile_lds;       // LDS floats for the rows a tile can touch
 };
 ForwardGeometry forward_geometry(int D, int tile_floats);
 
@@ -100,7 +98,7 @@ hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                        float *grad_coords_to_clear, float *grad_weights_to_clear,
                        hipStream_t stream);
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
-                          float *out, int tile_floats, int lds_pad, int debug,
+                          float *out, int tile_floats, int xcd_run, int lds_pad, int debug,
                           hipStream_t stream);
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                            const float *grad_out, float *grad_coords, float *grad_weights,

@@ -8,11 +8,13 @@
 // One wavefront produces one tile:
 //   1. it loads the records of the channel's atoms that can reach the x-planes
 //      the tile touches (spans the prep kernel computed), one atom per lane;
-//   2. per x-plane of the tile, each lane tests its atom against the tile's
-//      rows in that plane (disc of the atom's cutoff sphere in the plane versus
-//      the row range); the (atom, row) pairs that survive are packed into a
-//      task list, so that all 64 lanes work even though one atom's footprint is
-//      small;
+//   2. each lane tests its atom against the tile's rows in two x-planes at a
+//      time (disc of the atom's cutoff sphere in the plane versus the row
+//      range).  Every surviving (atom, row) pair is a task; a wavefront scan
+//      gives each atom the index of its first task, which the lane marks in a
+//      byte array, so that a later max-scan over the marks tells every lane
+//      which atom its task belongs to: all 64 lanes work even though one
+//      atom's footprint is small, and no lane loops over its rows to list them;
 //   3. each lane takes one task: the chord of the atom's sphere along that
 //      z-row, clipped to the tile in its first and last row.  It evaluates the
 //      density voxel by voxel and adds it into the tile held in LDS with LDS
@@ -26,7 +28,8 @@
 //   4. the finished tile is streamed to HBM, each lane writing 32 contiguous
 //      bytes (two adjacent 16-byte stores), every output element exactly once,
 //      zeros included.  Tiles no atom touches skip LDS and store zeros.
-// No barrier is needed: a wavefront only touches its own LDS slice.
+// No barrier is needed: a wavefront only touches its own LDS slice, which holds
+// the tile in output order (LDS index = output index - first index of the tile).
 //
 // Why 8 KB tiles on 4 KB boundaries: measured on this chip, one-wavefront
 // workgroups that each write one aligned 4 KB or 8 KB run sustain 6.3-6.6 TB/s
@@ -35,12 +38,16 @@
 // to 5.2-5.4 TB/s.
 //
 // The density is rho(x) = exp(-2x^2) for x <= g, A(x-c)^2 for g < x < c, else 0
-// (x = d/r); evaluated from x^2 with the hardware exp2 and sqrt.
+// (x = d/r).  Distances are carried in units of r/sqrt(k), k = 2*log2(e), so
+// that the Gaussian is exp2(-x'^2) with the hardware exp2 and the tail is
+// (sqrt(x'^2)*sA - cA)^2 with sA = sqrt(A/k), cA = c*sqrt(A).
 //
 // Binary mode decides d^2 <= r^2 in float with this fixed order (the file is
 // compiled with -ffp-contract=off, nothing fuses):
 //   gx = o_x + (float)i*res   (o = center - half)      dx = gx - ax
 //   d2 = (dx*dx + dy*dy) + dz*dz                        r2 = r*r
+#include <cmath>
+
 #include "mg_common.h"
 
 namespace mg {
@@ -61,27 +68,31 @@ struct FwdParams {
     const float *centers;
     float *out;
     int B, N, T;
-    int tile_floats;    // floats per tile (a multiple of 512)
-    int pitch;          // floats per row in LDS
-    int tile_lds;       // LDS floats reserved for the tile
+    int tile_floats;                // floats per tile (a multiple of 512)
+    unsigned tiles;                 // tiles per channel
+    unsigned long long div_magic;   // ceil(2^40 / D): x / D = (x * div_magic) >> 40 for x < D^3
+    unsigned long long tiles_magic; // ceil(2^64 / tiles), see div_u32
+    unsigned long long t_magic;     // ceil(2^64 / T)
+    int xcd_shift;                  // >= 0: runs of 2^xcd_shift consecutive tiles go to one XCD
+    unsigned n_remap;               // workgroups covered by that mapping (the rest map 1:1)
     int debug;
-    float kexp;         // -2 * log2(e)
+    float sk;           // sqrt(k), k = 2 log2(e)
+    float inv_sk;
+    float g2k, c2k;     // g^2 k, c^2 k
+    float sA, cA;       // tail coefficients
 };
 
 // what a wavefront keeps for the tile it is working on (all wave-uniform)
 struct TileCtx {
-    float *tile0;       // LDS: first row of the tile
-    int tile_n4;        // float4s of LDS the tile's rows take
-    float *tile;        // LDS: row j0 of the current x-plane
-    float4 *cand;
-    unsigned short *tasks;
+    float *tile;                // LDS: tile_floats floats, in output order
+    unsigned char *marks;       // LDS: marks[first task of atom in lane l] = l + 1, else 0
     int lane;
-    int D, pitch, j0, j1;       // rows [j0, j1) of the current plane belong to the tile
-    int jfirst, cfirst;         // row of this plane that is the tile's first row (-1: none) and
-    int jlast, clast;           // its first column; same for the last row / last column
+    int D, n;                   // points per side; floats in this tile
+    int nrows;                  // grid rows the tile touches
+    int c0, c1;                 // first column of its first row, last column of its last row
+    int rowA, rowB;             // tile row of row 0 of plane A / plane B (may be negative)
     float res, inv_res, oy, oz;
-    float g2, c, A, kexp;
-    float inv_d4;       // 1 / (D/4)
+    float g2k, c2k, sA, cA;
     int debug;
 };
 
@@ -102,65 +113,124 @@ __device__ inline int wave_inclusive_scan(int v)
     return v;
 }
 
+// Inclusive running maximum over the 64 lanes (values >= 0).
+__device__ inline int wave_inclusive_max(int v)
+{
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false));
+    return v;
+}
+
 __device__ inline void lds_sync() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); }
 
-// rho as a function of x^2 = d^2 / r^2
-__device__ inline float density_from_x2(float x2, const TileCtx &cx)
+__device__ inline int div_by_d(int x, unsigned long long magic)
 {
-    const float e = __builtin_amdgcn_exp2f(x2 * cx.kexp);
-    const float u = fminf(__builtin_amdgcn_sqrtf(x2) - cx.c, 0.0f);    // 0 beyond the cutoff
-    const float q = cx.A * u * u;
-    return x2 <= cx.g2 ? e : q;
+    return (int)(((unsigned long long)(unsigned)x * magic) >> 40);
+}
+
+// x / d for any 32-bit x, with magic = ceil(2^64 / d) (d >= 2; d == 1 is passed as magic 0).
+__device__ inline unsigned div_u32(unsigned x, unsigned long long magic)
+{
+    return magic == 0ull ? x : (unsigned)__umul64hi((unsigned long long)x, magic);
+}
+
+// One atom of the current batch as its lane holds it.
+struct Atom {
+    float4 a;           // x', y', z', r
+    float w;            // weight (vector types), else 1
+    bool valid;
+};
+
+// What a task needs of its atom; it stays in the registers of the atom's lane and the
+// task's lane fetches it with ds_bpermute (register exchange, no LDS storage).
+struct Cand {
+    float c0, c1, c2, c3;       // fy, fz, stepk, inv_stepk | w     (binary: y', z', r^2, reach^2)
+    float pxA, pxB;             // plane term of d^2 for plane A, plane B
+    int start;                  // index of the atom's first task
+    int pack;                   // jloA | nA << 10 | jloB << 20
+};
+
+__device__ inline float fetch(int byte_addr, float v)
+{
+    return __int_as_float(__builtin_amdgcn_ds_bpermute(byte_addr, __float_as_int(v)));
 }
 
 // Run the staged tasks [0, ntasks): one (atom, row) chord per lane.
 template <bool VECTOR, bool BINARY, bool FIXED>
-__device__ inline void run_tasks(const TileCtx &cx, int ntasks)
+__device__ inline void run_tasks(const TileCtx &cx, const Cand &cd, int ntasks)
 {
+    int carry = 0;
     for (int base = 0; base < ntasks; base += 64) {
         const int tau = base + cx.lane;
         bool act = tau < ntasks;
-        const int tk = cx.tasks[act ? tau : 0];
-        const int cnd = tk & 63, row = tk >> 6;
-        const float4 p0 = cx.cand[cnd * 2], p1 = cx.cand[cnd * 2 + 1];
-        const float ay = p0.x, az = p0.y, dx2 = p0.z, s = p0.w;
-        const float h2 = p1.x, w = p1.y;
-        const int j = __float_as_int(p1.z) + row;
-        const float gy = cx.oy + (float)j * cx.res;
-        const float dy = gy - ay;
-        const float dy2 = dy * dy;
-        const float rem = h2 - dy2;
-        act = act && rem > 0.0f;
-        const float hz = __builtin_amdgcn_sqrtf(fmaxf(rem, 0.0f)) * cx.inv_res + 1.0e-3f;
-        const float fz = (az - cx.oz) * cx.inv_res;
-        // the chord, clipped to the grid and (first / last row of the tile) to the tile
-        const int klo = max(j == cx.jfirst ? cx.cfirst : 0, (int)ceilf(fz - hz));
-        const int khi = min(j == cx.jlast ? cx.clast : cx.D - 1, (int)floorf(fz + hz));
-        const int nz = act ? khi - klo + 1 : 0;
-        float *rowp = cx.tile + (j - cx.j0) * cx.pitch + klo;
+        // which atom: the last mark at or before this task
+        const int owner = max(carry, wave_inclusive_max((int)cx.marks[tau]));
+        carry = bcast(owner, 63);
+        const int src = (act ? owner - 1 : 0) << 2;
+        const float4 p0 = make_float4(fetch(src, cd.c0), fetch(src, cd.c1), fetch(src, cd.c2),
+                                      fetch(src, cd.c3));
+        const float2 p1 = make_float2(fetch(src, cd.pxA), fetch(src, cd.pxB));
+        const int pack = __builtin_amdgcn_ds_bpermute(src, cd.pack);
+        const int k = tau - __builtin_amdgcn_ds_bpermute(src, cd.start);   // row number within the atom
+        const int nA = (pack >> 10) & 1023;
+        const bool inB = k >= nA;
+        const int j = inB ? (pack >> 20) + (k - nA) : (pack & 1023) + k;   // row in its plane
+        const int trow = (inB ? cx.rowB : cx.rowA) + j;                    // row in the tile
+        const float px2 = inB ? p1.y : p1.x;                               // plane term of d^2
+        const int clip_lo = trow == 0 ? cx.c0 : 0;
+        const int clip_hi = trow == cx.nrows - 1 ? cx.c1 : cx.D - 1;
+        float *rowp = cx.tile + (trow * cx.D - cx.c0);
         if (BINARY) {
-            const float base2 = dx2 + dy2;
+            const float ay = p0.x, az = p0.y, r2 = p0.z, reach2 = p0.w;
+            const float gy = cx.oy + (float)j * cx.res;
+            const float dy = gy - ay;
+            const float dy2 = dy * dy;
+            const float rem = (reach2 - px2) - dy2;
+            act = act && rem > 0.0f;
+            const float hz = __builtin_amdgcn_sqrtf(fmaxf(rem, 0.0f)) * cx.inv_res + 1.0e-3f;
+            const float fz = (az - cx.oz) * cx.inv_res;
+            const int klo = max(clip_lo, (int)ceilf(fz - hz));
+            const int khi = min(clip_hi, (int)floorf(fz + hz));
+            const int nz = act ? khi - klo + 1 : 0;
+            const float base2 = px2 + dy2;
             for (int i = 0; i < nz; ++i) {
                 const float gz = cx.oz + (float)(klo + i) * cx.res;
                 const float dz = gz - az;
                 const float d2 = base2 + dz * dz;
-                if (d2 <= s) rowp[i] = 1.0f;
+                if (d2 <= r2) rowp[klo + i] = 1.0f;
             }
         } else {
-            // coordinates in units of r: x^2 = b2s + zs^2
-            const float b2s = (dx2 + dy2) * s * s;
-            const float step = cx.res * s;
-            const float z0 = ((cx.oz - az) + (float)klo * cx.res) * s;
+            const float fy = p0.x, fz = p0.y, stepk = p0.z;
+            const float w = p0.w;                                           // vector types
+            const float inv_stepk = VECTOR ? __builtin_amdgcn_rcpf(stepk) : p0.w;
+            const float dyk = ((float)j - fy) * stepk;
+            const float x2b = fmaf(dyk, dyk, px2);
+            const float rem = cx.c2k - x2b;
+            act = act && rem > 0.0f;
+            const float hz = __builtin_amdgcn_sqrtf(fmaxf(rem, 0.0f)) * inv_stepk + 1.0e-3f;
+            const int klo = max(clip_lo, (int)ceilf(fz - hz));
+            const int khi = min(clip_hi, (int)floorf(fz + hz));
+            const int nz = act ? khi - klo + 1 : 0;
+            const float z0 = ((float)klo - fz) * stepk;
+            float fi = 0.0f;
             for (int i = 0; i < nz; ++i) {
-                const float zs = fmaf((float)i, step, z0);
-                const float rho = density_from_x2(fmaf(zs, zs, b2s), cx);
+                const float zs = fmaf(fi, stepk, z0);
+                fi += 1.0f;
+                const float x2 = fmaf(zs, zs, x2b);
+                const float e = __builtin_amdgcn_exp2f(-x2);
+                const float u = fminf(fmaf(__builtin_amdgcn_sqrtf(x2), cx.sA, -cx.cA), 0.0f);
+                const float rho = x2 <= cx.g2k ? e : u * u;                 // 0 beyond the cutoff
                 if (FIXED) {
                     const int q = VECTOR ? (int)rintf(w * rho * kFixedOne)
                                          : (int)fmaf(rho, kFixedOne, 0.5f);
-                    __hip_atomic_fetch_add(reinterpret_cast<int *>(rowp) + i, q, __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_WAVEFRONT);
+                    __hip_atomic_fetch_add(reinterpret_cast<int *>(rowp) + klo + i, q,
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
                 } else {
-                    __hip_atomic_fetch_add(rowp + i, VECTOR ? w * rho : rho, __ATOMIC_RELAXED,
+                    __hip_atomic_fetch_add(rowp + klo + i, VECTOR ? w * rho : rho, __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_WAVEFRONT);
                 }
             }
@@ -169,100 +239,132 @@ __device__ inline void run_tasks(const TileCtx &cx, int ntasks)
     lds_sync();
 }
 
-// One batch of up to 64 atom records (one per lane) against the rows [j0, j1) of one
-// x-plane of the tile.
-//   a = {x', y', z', r};  valid: this lane holds a live record;  w: weight (vector types)
-//   mode: state of the whole tile;  bound: running bound for this plane
-template <bool VECTOR, bool BINARY>
-__device__ inline void plane_batch(const TileCtx &cx, float gx, float4 a, float r, float w,
-                                   bool valid, int &mode, float &bound)
+// Rows of one x-plane (rows [ja, jb) of it belong to the tile) that the lane's atom reaches.
+//   out: px2 = plane term of the squared distance (scaled units; binary: dx^2), rows [jlo, jlo+n)
+template <bool BINARY>
+__device__ inline int plane_rows(const TileCtx &cx, const FwdParams &p, const Atom &at, float gx,
+                                 int ja, int jb, float sks, float inv_stepk, float fy, float fz,
+                                 float &px2, int &jlo)
 {
-    const float reach = BINARY ? r + 1.0e-3f * cx.res : r * cx.c;
-    const float dx = gx - a.x;
-    const float dx2 = dx * dx;
-    const float h2 = reach * reach - dx2;
-    bool ok = valid && (h2 > 0.0f);
-    // half-width of the footprint in this plane, in grid steps, padded
-    const float hv = __builtin_amdgcn_sqrtf(fmaxf(h2, 0.0f)) * cx.inv_res + 1.0e-3f;
-    const float fy = (a.y - cx.oy) * cx.inv_res;
-    const float fz = (a.z - cx.oz) * cx.inv_res;
-    const int jlo = max(cx.j0, (int)ceilf(fy - hv));
-    const int jhi = min(cx.j1 - 1, (int)floorf(fy + hv));
-    ok = ok && (jlo <= jhi) && (fz + hv >= 0.0f) && (fz - hv <= (float)(cx.D - 1));
-    unsigned long long mask = __ballot(ok);
-    if (cx.debug == 1) mask = 0ull;
-    if (mask == 0ull) return;
-
-    // upper bound on what this batch can add to one voxel (rho <= 1)
-    if (VECTOR) {
-        float s = ok ? fabsf(w) : 0.0f;
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
-        bound += s;
+    float hv;
+    bool ok = at.valid && ja < jb;
+    const float dx = gx - at.a.x;
+    if (BINARY) {
+        const float reach = at.a.w + 1.0e-3f * cx.res;
+        px2 = dx * dx;
+        const float h2 = reach * reach - px2;
+        ok = ok && h2 > 0.0f;
+        hv = __builtin_amdgcn_sqrtf(fmaxf(h2, 0.0f)) * cx.inv_res + 1.0e-3f;
     } else {
-        bound += (float)__builtin_popcountll(mask);
+        const float dxk = dx * sks;
+        px2 = dxk * dxk;
+        const float h2 = cx.c2k - px2;
+        ok = ok && h2 > 0.0f;
+        hv = __builtin_amdgcn_sqrtf(fmaxf(h2, 0.0f)) * inv_stepk + 1.0e-3f;
+    }
+    // half-width of the footprint in this plane, in grid steps, padded
+    jlo = max(ja, (int)ceilf(fy - hv));
+    const int jhi = min(jb - 1, (int)floorf(fy + hv));
+    ok = ok && (jlo <= jhi) && (fz + hv >= 0.0f) && (fz - hv <= (float)(cx.D - 1));
+    return ok ? jhi - jlo + 1 : 0;
+}
+
+// One batch of up to 64 atoms (one per lane) against the rows of planes iA and iA + 1 that
+// belong to the tile.  mode: state of the whole tile;  bound: running bound on |sum|
+template <bool VECTOR, bool BINARY, int ITERS>
+__device__ inline void pair_batch(const TileCtx &cx, const FwdParams &p, const Atom &at, float gxA,
+                                  float gxB, int jaA, int jbA, int jaB, int jbB, int &mode,
+                                  float &bound)
+{
+    const float r = at.a.w;
+    // per atom: position in grid steps, scale of its distances
+    const float fy = (at.a.y - cx.oy) * cx.inv_res;
+    const float fz = (at.a.z - cx.oz) * cx.inv_res;
+    const float sks = at.valid ? p.sk * __builtin_amdgcn_rcpf(r) : 0.0f;
+    const float stepk = cx.res * sks;
+    const float inv_stepk = r * cx.inv_res * p.inv_sk;
+    float pxA, pxB;
+    int jloA, jloB;
+    int nA = plane_rows<BINARY>(cx, p, at, gxA, jaA, jbA, sks, inv_stepk, fy, fz, pxA, jloA);
+    int nB = plane_rows<BINARY>(cx, p, at, gxB, jaB, jbB, sks, inv_stepk, fy, fz, pxB, jloB);
+    if (cx.debug == 1) { nA = 0; nB = 0; }
+    if (nA == 0) jloA = 0;          // both are packed into bit fields below
+    if (nB == 0) jloB = 0;
+    const unsigned long long maskA = __ballot(nA > 0), maskB = __ballot(nB > 0);
+    if ((maskA | maskB) == 0ull) return;
+
+    // upper bound on what this batch can add to one voxel (rho <= 1); the two planes
+    // share no voxel
+    if (VECTOR) {
+        float sa = nA > 0 ? fabsf(at.w) : 0.0f, sb = nB > 0 ? fabsf(at.w) : 0.0f;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            sa += __shfl_xor(sa, d, 64);
+            sb += __shfl_xor(sb, d, 64);
+        }
+        bound += fmaxf(sa, sb);
+    } else {
+        bound += (float)max(__builtin_popcountll(maskA), __builtin_popcountll(maskB));
     }
     if (mode == kUntouched) {
         mode = (BINARY || bound > kFixedLimit) ? kFloat : kFixed;
         const float4 z4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);     // same bits as integer zeros
-        for (int o = cx.lane; o < cx.tile_n4; o += 64) reinterpret_cast<float4 *>(cx.tile0)[o] = z4;
+#pragma unroll
+        for (int it = 0; it < 2 * ITERS; ++it)
+            reinterpret_cast<float4 *>(cx.tile)[it * 64 + cx.lane] = z4;
     } else if (mode == kFixed && bound > kFixedLimit) {
         mode = kFloat;                                               // leave fixed point
-        for (int o = cx.lane; o < cx.tile_n4 * 4; o += 64)
-            cx.tile0[o] = (float)reinterpret_cast<int *>(cx.tile0)[o] * (1.0f / kFixedOne);
+        for (int o = cx.lane; o < ITERS * 512; o += 64)
+            cx.tile[o] = (float)reinterpret_cast<int *>(cx.tile)[o] * (1.0f / kFixedOne);
     }
-    lds_sync();
-    const int nrows = ok ? jhi - jlo + 1 : 0;
-    if (ok) {
-        cx.cand[cx.lane * 2] = make_float4(a.y, a.z, dx2, BINARY ? r * r : 1.0f / r);
-        cx.cand[cx.lane * 2 + 1] = make_float4(h2, w, __int_as_float(jlo), 0.0f);
-    }
-    // exclusive prefix of nrows over the lanes: where each atom's tasks start
-    const int incl = wave_inclusive_scan(nrows);
-    const int total = bcast(incl, 63);
-    if (total <= kTaskCap) {
-        const int start = incl - nrows;
-        for (int rr = 0; rr < nrows; ++rr) cx.tasks[start + rr] = (unsigned short)(cx.lane | (rr << 6));
-        lds_sync();
-        if (mode == kFixed) run_tasks<VECTOR, BINARY, true>(cx, total);
-        else run_tasks<VECTOR, BINARY, false>(cx, total);
+
+    // tasks of this lane's atom: rows of plane A, then rows of plane B
+    Cand cd;
+    if (BINARY) {
+        const float reach = r + 1.0e-3f * cx.res;
+        cd.c0 = at.a.y; cd.c1 = at.a.z; cd.c2 = r * r; cd.c3 = reach * reach;
     } else {
-        // rare: too many tasks for the staging list; take the atoms one at a time
-        while (mask != 0ull) {
-            const int src = (int)__builtin_ctzll(mask);
-            mask &= mask - 1ull;
-            const int n = bcast(nrows, src);
-            for (int rr = cx.lane; rr < n; rr += 64) cx.tasks[rr] = (unsigned short)(src | (rr << 6));
-            lds_sync();
-            if (mode == kFixed) run_tasks<VECTOR, BINARY, true>(cx, n);
-            else run_tasks<VECTOR, BINARY, false>(cx, n);
+        cd.c0 = fy; cd.c1 = fz; cd.c2 = stepk; cd.c3 = VECTOR ? at.w : inv_stepk;
+    }
+    cd.pxA = pxA; cd.pxB = pxB;
+    cd.start = 0;
+    cd.pack = jloA | (nA << 10) | (jloB << 20);
+    int todo = nA + nB;             // lanes still to be staged have todo > 0
+    while (true) {
+        const int incl = wave_inclusive_scan(todo);
+        const bool now = todo > 0 && incl <= kTaskCap;              // fits this round
+        const int total = bcast(wave_inclusive_scan(now ? todo : 0), 63);
+        if (total == 0) break;
+        if (cx.lane < kTaskCap / 16)
+            reinterpret_cast<float4 *>(cx.marks)[cx.lane] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (now) {
+            cd.start = incl - todo;
+            cx.marks[cd.start] = (unsigned char)(cx.lane + 1);
+            todo = 0;
         }
+        lds_sync();
+        if (mode == kFixed) run_tasks<VECTOR, BINARY, true>(cx, cd, total);
+        else run_tasks<VECTOR, BINARY, false>(cx, cd, total);
     }
 }
 
-// Stream a finished tile to HBM (or zeros if no atom touched it): n floats to dst; the
-// first of them sits in column c0 of the tile's first LDS row.
+// Stream a finished tile to HBM (or zeros if no atom touched it).
 // ITERS = tile_floats / 512: each pass of the wavefront covers 2 KB.
 template <bool ALIGNED, int ITERS>
-__device__ inline void store_tile(const TileCtx &cx, float *dst, int c0, int n, int mode)
+__device__ inline void store_tile(const TileCtx &cx, float *dst, int mode)
 {
     if (ALIGNED) {
-        const int n4 = n >> 2;                      // even: D^3 and the tile size are multiples of 8
-        const int d4 = cx.D >> 2, p4 = cx.pitch >> 2, q0 = c0 >> 2;
+        const int n4 = cx.n >> 2;                   // even: D^3 and the tile size are multiples of 8
         float4 *dst4 = reinterpret_cast<float4 *>(dst);
-        const float4 *src4 = reinterpret_cast<const float4 *>(cx.tile0);
-        const float4 z4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        const float4 *src4 = reinterpret_cast<const float4 *>(cx.tile);
         // Constant trip count, fully unrolled; the tile comes from LDS into registers
         // under a wave-uniform branch (zeros otherwise), so that the stores below are one
         // straight sequence with no load between them.
         float4 v[2 * ITERS];
         if (mode != kUntouched) {
 #pragma unroll
-            for (int it = 0; it < 2 * ITERS; ++it) {
-                const int o = min((it >> 1) * 128 + cx.lane * 2 + (it & 1), n4 - 1) + q0;
-                const int row = (int)(((float)o + 0.5f) * cx.inv_d4);
-                v[it] = src4[row * p4 + (o - row * d4)];            // rows are padded in LDS
-            }
+            for (int it = 0; it < 2 * ITERS; ++it)
+                v[it] = src4[(it >> 1) * 128 + cx.lane * 2 + (it & 1)];
             if (mode == kFixed) {
 #pragma unroll
                 for (int it = 0; it < 2 * ITERS; ++it) {
@@ -275,7 +377,7 @@ __device__ inline void store_tile(const TileCtx &cx, float *dst, int c0, int n, 
             }
         } else {
 #pragma unroll
-            for (int it = 0; it < 2 * ITERS; ++it) v[it] = z4;
+            for (int it = 0; it < 2 * ITERS; ++it) v[it] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         }
         // the two 16-byte halves of a lane's 32 bytes go out back to back, under one
         // predicate: separated by other instructions they are markedly slower
@@ -288,15 +390,11 @@ __device__ inline void store_tile(const TileCtx &cx, float *dst, int c0, int n, 
             }
         }
     } else {
-        for (int o = cx.lane; o < n; o += 64) {
-            const int f = o + c0;
-            const int row = f / cx.D;
-            const int col = f - row * cx.D;
+        for (int o = cx.lane; o < cx.n; o += 64) {
             float v = 0.0f;
-            if (mode == kFloat) v = cx.tile0[row * cx.pitch + col];
+            if (mode == kFloat) v = cx.tile[o];
             if (mode == kFixed)
-                v = (float)reinterpret_cast<const int *>(cx.tile0)[row * cx.pitch + col] *
-                    (1.0f / kFixedOne);
+                v = (float)reinterpret_cast<const int *>(cx.tile)[o] * (1.0f / kFixedOne);
             dst[o] = v;
         }
     }
@@ -305,102 +403,102 @@ __device__ inline void store_tile(const TileCtx &cx, float *dst, int c0, int n, 
 template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS>
 __global__ __launch_bounds__(64) void forward_kernel(FwdParams p)
 {
-    extern __shared__ __attribute__((aligned(16))) float lds[];   // tile | candidates | tasks
+    extern __shared__ __attribute__((aligned(16))) float lds[];   // tile | marks
 
-    // grid: x = tile of one channel, y = channel, z = example; one wavefront each
+    // One wavefront per tile.  Workgroup ids go round the 8 XCDs (id % 8), each with its
+    // own L2: runs of consecutive tiles, which read the same atom records, are given to
+    // one XCD.
     const int lane = threadIdx.x;
     const GridSpec &gs = p.gs;
     const int D = gs.D, T = p.T, N = p.N;
-    const int t = (int)blockIdx.y, b = (int)blockIdx.z;
+    unsigned u = blockIdx.x;
+    if (p.xcd_shift >= 0 && u < p.n_remap) {
+        const unsigned xcd = u & 7u, slot = u >> 3, sh = (unsigned)p.xcd_shift;
+        u = ((slot >> sh) << (sh + 3)) + (xcd << sh) + (slot & ((1u << sh) - 1u));
+    }
+    const unsigned chan = div_u32(u, p.tiles_magic);
+    const unsigned tile_in_chan = u - chan * p.tiles;
+    const int b = (int)div_u32(chan, p.t_magic);
+    const int t = (int)chan - b * T;
 
     // the tile: floats [f0, f1) of the channel = rows [R0, R1) of its D*D rows, the first
     // from column c0 on, the last up to column c1
     const int total = D * D * D;
-    const int f0 = (int)blockIdx.x * p.tile_floats;
-    const int f1 = min(total, f0 + p.tile_floats);
-    const int R0 = f0 / D, R1 = (f1 - 1) / D + 1;
-    const int c0 = f0 - R0 * D, c1 = f1 - 1 - (R1 - 1) * D;
-    const int i_lo = R0 / D, i_hi = (R1 - 1) / D;
+    const int f0 = (int)tile_in_chan * (ITERS * 512);
+    const int f1 = min(total, f0 + ITERS * 512);
+    const int R0 = div_by_d(f0, p.div_magic), R1 = div_by_d(f1 - 1, p.div_magic) + 1;
+    const int i_lo = div_by_d(R0, p.div_magic), i_hi = div_by_d(R1 - 1, p.div_magic);
 
     TileCtx cx;
-    cx.tile0 = lds;
-    cx.tile_n4 = ((R1 - R0) * p.pitch) >> 2;
     cx.tile = lds;
-    cx.cand = reinterpret_cast<float4 *>(lds + p.tile_lds);
-    cx.tasks = reinterpret_cast<unsigned short *>(lds + p.tile_lds + 64 * 8);
+    cx.marks = reinterpret_cast<unsigned char *>(lds + ITERS * 512);
     cx.lane = lane;
     cx.D = D;
-    cx.pitch = p.pitch;
-    cx.j0 = 0;
-    cx.j1 = 0;
-    cx.jfirst = -1; cx.cfirst = c0;
-    cx.jlast = -1; cx.clast = c1;
+    cx.n = f1 - f0;
+    cx.nrows = R1 - R0;
+    cx.c0 = f0 - R0 * D;
+    cx.c1 = f1 - 1 - (R1 - 1) * D;
+    cx.rowA = 0;
+    cx.rowB = 0;
     cx.res = gs.res;
     cx.inv_res = gs.inv_res;
-    cx.g2 = gs.g2; cx.c = gs.c; cx.A = gs.A; cx.kexp = p.kexp;
-    cx.inv_d4 = 1.0f / (float)max(1, D >> 2);
+    cx.g2k = p.g2k; cx.c2k = p.c2k; cx.sA = p.sA; cx.cA = p.cA;
     cx.debug = p.debug;
 
     float *dst = p.out + ((size_t)b * T + t) * (size_t)total + f0;
     if (p.debug == 3) {         // timing aid: nothing but the zero stores
-        store_tile<ALIGNED, ITERS>(cx, dst, c0, f1 - f0, kUntouched);
+        store_tile<ALIGNED, ITERS>(cx, dst, kUntouched);
         return;
     }
     const size_t group = (size_t)b * T + (VECTOR ? 0 : t);
-    // records (relative to the example's first) that can reach planes i_lo .. i_hi
-    const int r0 = p.range[group * D + i_lo].x;
-    const int r1 = p.debug == 2 ? r0 : p.range[group * D + i_hi].y;
-    const float ox = (p.centers ? p.centers[3 * b + 0] : 0.0f) - gs.half;
-    cx.oy = (p.centers ? p.centers[3 * b + 1] : 0.0f) - gs.half;
-    cx.oz = (p.centers ? p.centers[3 * b + 2] : 0.0f) - gs.half;
+    // All the scalar loads of the preamble are issued together (one trip to L2, which is
+    // slow while the chip streams stores): the span of records that can reach planes
+    // i_lo .. i_hi (counted from the example's first record) and the grid centre.
+    const int2 *span = p.range + group * D;
+    const float *cen = p.centers ? p.centers + 3 * b : reinterpret_cast<const float *>(span);
+    const int r0 = span[i_lo].x;
+    const int r1_loaded = span[i_hi].y;
+    const float cen_x = cen[0], cen_y = cen[1], cen_z = cen[2];
+    asm volatile("" ::"s"(r0), "s"(r1_loaded), "s"(cen_x), "s"(cen_y), "s"(cen_z));  // all in flight before the first wait
+    const int r1 = p.debug == 2 ? r0 : r1_loaded;
+    const float ox = (p.centers ? cen_x : 0.0f) - gs.half;
+    cx.oy = (p.centers ? cen_y : 0.0f) - gs.half;
+    cx.oz = (p.centers ? cen_z : 0.0f) - gs.half;
     const float r_chan = VECTOR ? gs.radius_scale * p.radii[t] : 0.0f;
 
     const float4 *rec = p.rec + (size_t)b * N + r0;
     const int *idx = p.idx + (size_t)b * N + r0;
     const int count = r1 - r0;
 
-    // the usual case: every atom that can reach the tile sits in one lane, loaded once
-    const bool once = count <= 64;
-    float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    float w = 1.0f;
-    if (once && lane < count) {
-        a = rec[lane];
-        if (VECTOR && a.w > 0.0f) w = p.weights[((size_t)b * N + idx[lane]) * T + t];
-    }
-    float r = VECTOR ? r_chan : a.w;
-    bool valid = (lane < count) && (a.w > 0.0f) && (r > 0.0f);
-    if (VECTOR) valid = valid && (BINARY ? (w > 0.0f) : (w != 0.0f));
-
     int mode = kUntouched;
-    for (int i = i_lo; i <= i_hi && count > 0; ++i) {
-        // rows of plane i inside the tile
-        const int ja = max(R0 - i * D, 0), jb = min(R1 - i * D, D);
-        cx.j0 = ja;
-        cx.j1 = jb;
-        cx.tile = cx.tile0 + (i * D + ja - R0) * p.pitch;
-        cx.jfirst = (i == i_lo) ? ja : -1;
-        cx.jlast = (i == i_hi) ? jb - 1 : -1;
-        const float gx = ox + (float)i * gs.res;
-        float bound = 0.0f;         // planes do not share voxels: one bound per plane
-        if (once) {
-            plane_batch<VECTOR, BINARY>(cx, gx, a, r, w, valid, mode, bound);
-        } else {
-            for (int base = 0; base < count; base += 64) {
-                const int e = base + lane;
-                a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                w = 1.0f;
-                if (e < count) {
-                    a = rec[e];
-                    if (VECTOR && a.w > 0.0f) w = p.weights[((size_t)b * N + idx[e]) * T + t];
-                }
-                r = VECTOR ? r_chan : a.w;
-                valid = (e < count) && (a.w > 0.0f) && (r > 0.0f);
-                if (VECTOR) valid = valid && (BINARY ? (w > 0.0f) : (w != 0.0f));
-                plane_batch<VECTOR, BINARY>(cx, gx, a, r, w, valid, mode, bound);
-            }
+    float bound = 0.0f;         // over all batches and planes: never too small
+    for (int base = 0; base < count; base += 64) {
+        // one atom per lane
+        const int e = base + lane;
+        Atom at;
+        at.a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        at.w = 1.0f;
+        if (e < count) {
+            at.a = rec[e];
+            if (VECTOR && at.a.w > 0.0f) at.w = p.weights[((size_t)b * N + idx[e]) * T + t];
+        }
+        at.valid = (e < count) && (at.a.w > 0.0f);
+        if (VECTOR) {
+            at.a.w = r_chan;
+            at.valid = at.valid && (r_chan > 0.0f) && (BINARY ? (at.w > 0.0f) : (at.w != 0.0f));
+        }
+        // the planes the tile touches, two at a time
+        for (int iA = i_lo; iA <= i_hi; iA += 2) {
+            cx.rowA = iA * D - R0;
+            cx.rowB = cx.rowA + D;
+            const int jaA = max(-cx.rowA, 0), jbA = min(R1 - R0 - cx.rowA, D);
+            const int jaB = max(-cx.rowB, 0), jbB = iA < i_hi ? min(R1 - R0 - cx.rowB, D) : 0;
+            pair_batch<VECTOR, BINARY, ITERS>(cx, p, at, ox + (float)iA * gs.res,
+                                              ox + (float)(iA + 1) * gs.res, jaA, jbA, jaB, jbB,
+                                              mode, bound);
         }
     }
-    store_tile<ALIGNED, ITERS>(cx, dst, c0, f1 - f0, mode);
+    store_tile<ALIGNED, ITERS>(cx, dst, mode);
 }
 
 }  // namespace
@@ -411,18 +509,22 @@ ForwardGeometry forward_geometry(int D, int tile_floats)
     fg.tile_floats = tile_floats;
     const long long total = (long long)D * D * D;
     fg.tiles = (int)((total + tile_floats - 1) / tile_floats);
-    // LDS rows are padded by 4 floats: with a pitch of D (a multiple of 16 for the usual
-    // grids) the rows of one atom would fall on a few LDS banks only
-    fg.pitch = ((D + 3) & ~3) + 4;
-    // a run of tile_floats floats touches at most tile_floats/D + 2 rows
-    long long rows = (long long)tile_floats / D + 2;
-    if (rows > (long long)D * D) rows = (long long)D * D;
-    fg.tile_lds = (int)((rows * fg.pitch + 3) & ~3LL);
     return fg;
 }
 
+namespace {
+unsigned long long magic64(unsigned d)      // ceil(2^64 / d); 0 stands for d == 1
+{
+    if (d <= 1) return 0ull;
+    const unsigned long long q = ~0ull / d;             // floor((2^64 - 1) / d)
+    return q + 1ull;        // = ceil(2^64 / d): d >= 2 never divides 2^64 - 1 and 2^64 both, and
+                            // when d divides 2^64, q = 2^64/d - 1
+}
+}  // namespace
+
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws, float *out,
-                          int tile_floats, int lds_pad, int debug, hipStream_t stream)
+                          int tile_floats, int xcd_run, int lds_pad, int debug,
+                          hipStream_t stream)
 {
     const ForwardGeometry fg = forward_geometry(gs.D, tile_floats);
     FwdParams p;
@@ -436,14 +538,31 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     p.out = out;
     p.B = bt.B; p.N = bt.N; p.T = bt.T;
     p.tile_floats = fg.tile_floats;
-    p.pitch = fg.pitch;
-    p.tile_lds = fg.tile_lds;
+    p.div_magic = ((1ULL << 40) + (unsigned long long)gs.D - 1ULL) / (unsigned long long)gs.D;
+    p.tiles = (unsigned)fg.tiles;
+    p.tiles_magic = magic64((unsigned)fg.tiles);
+    p.t_magic = magic64((unsigned)bt.T);
+    const unsigned long long groups = (unsigned long long)bt.B * bt.T * fg.tiles;
+    p.xcd_shift = -1;
+    p.n_remap = 0;
+    for (int sh = 0; sh < 16; ++sh)
+        if (xcd_run == (1 << sh)) p.xcd_shift = sh;
+    if (p.xcd_shift >= 0) {
+        const unsigned long long chunk = 8ull << p.xcd_shift;
+        p.n_remap = (unsigned)(groups / chunk * chunk);
+    }
     p.debug = debug;
-    p.kexp = -2.8853900817779268f;      // -2 / ln 2
-    const size_t lds_bytes = ((size_t)p.tile_lds + 64 * 8 + kTaskCap / 2) * sizeof(float) + lds_pad;
+    const double k = 2.8853900817779268;        // 2 / ln 2
+    p.sk = (float)std::sqrt(k);
+    p.inv_sk = (float)(1.0 / std::sqrt(k));
+    p.g2k = (float)((double)gs.g2 * k);
+    p.c2k = (float)((double)gs.c * (double)gs.c * k);
+    p.sA = (float)std::sqrt((double)gs.A / k);
+    p.cA = (float)((double)gs.c * std::sqrt((double)gs.A));
+    const size_t lds_bytes = (size_t)tile_floats * sizeof(float) + kTaskCap + lds_pad;
     const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)out & 15u) == 0);
     const bool vec = bt.weights != nullptr;
-    const dim3 blk(64), grd(fg.tiles, bt.T, bt.B);
+    const dim3 blk(64), grd((unsigned)groups);
 #define MG_LAUNCH4(V, Bn, Al, It) \
     hipLaunchKernelGGL((forward_kernel<V, Bn, Al, It>), grd, blk, lds_bytes, stream, p)
 #define MG_LAUNCH(V, Bn, Al)                            \

@@ -16,13 +16,17 @@
 // Culling is exact: the density is identically zero beyond c(grm)*r, so an
 // atom whose cutoff cube misses the grid box contributes nothing.
 //
-// One wavefront per group (example b, type t; vector types: example b):
-//   1. stable compaction of the group's atoms (every lane owns a run of
-//      consecutive atoms; a wavefront scan gives each match its rank);
-//   2. transform + cull, bin the survivors by the x-plane they fall in;
-//   3. records are written bin by bin and, inside a bin, in atom order, so the
-//      forward kernel's summation order is fixed;
-//   4. for every x-plane, the span of records that can reach it.
+// Usual sizes: one 1024-thread workgroup per example does a counting sort of
+// the example's atoms by (type, x-plane bin) in LDS:
+//   1. every atom: transform, cull, key = type * bins + bin (bins 0 and D+1 are
+//      the atoms left / right of the grid, bin D+2 the culled ones), count;
+//   2. exclusive scan of the counts = where each (type, bin) starts;
+//   3. atoms are placed, each bin is put in atom order (so the order in which
+//      the forward kernel sums is fixed), records are written bin by bin;
+//   4. for every type and x-plane, the span of records that can reach it.
+// Large N or very many (type, bin) pairs take the slower kernel below it: one
+// wavefront per group (example b, type t; vector types: example b) that scans
+// the example's types for its own atoms.
 #include "mg_common.h"
 
 namespace mg {
@@ -150,6 +154,174 @@ __device__ inline void clear_grads(float *gclear, float *wclear, size_t atom, in
     }
     if (wclear)
         for (int k = 0; k < T; ++k) wclear[atom * T + k] = 0.0f;
+}
+
+// ---------------------------------------------------------------------------
+// One workgroup per example: counting sort by (type, x-bin) in LDS.
+// ---------------------------------------------------------------------------
+constexpr int kExThreads = 1024;
+constexpr int kExMaxAtoms = 4096;
+constexpr int kExMaxKeys = 12288;
+
+struct ExLayout {       // LDS, in ints
+    int K, Tg, N;
+    __host__ __device__ int cnt() const { return 0; }
+    __host__ __device__ int pos() const { return K; }
+    __host__ __device__ int rmax() const { return 2 * K; }
+    __host__ __device__ int part() const { return 2 * K + Tg; }
+    __host__ __device__ int key() const { return 2 * K + Tg + 32; }             // ushort[N]
+    __host__ __device__ int slot() const { return key() + (N + 1) / 2; }        // ushort[N]
+    __host__ __device__ int order() const { return slot() + (N + 1) / 2; }      // ushort[N]
+    __host__ __device__ int ints() const { return order() + (N + 1) / 2; }
+};
+
+template <bool VECTOR>
+__global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, Batch bt,
+                                                                  Workspace ws, float *gclear,
+                                                                  float *wclear, int stop)
+{
+    extern __shared__ int s_mem[];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int N = bt.N, T = bt.T, D = gs.D;
+    if (stop == 1) return;
+    const int Tg = VECTOR ? 1 : T;      // groups per example
+    const int nb = D + 3;               // bins per group; bin D+2 holds the culled atoms
+    ExLayout L;
+    L.K = Tg * nb; L.Tg = Tg; L.N = N;
+    const int K = L.K;
+    int *s_cnt = s_mem + L.cnt();
+    int *s_pos = s_mem + L.pos();
+    int *s_rmax = s_mem + L.rmax();
+    int *s_part = s_mem + L.part();
+    unsigned short *s_key = reinterpret_cast<unsigned short *>(s_mem + L.key());
+    unsigned short *s_slot = reinterpret_cast<unsigned short *>(s_mem + L.slot());
+    unsigned short *s_order = reinterpret_cast<unsigned short *>(s_mem + L.order());
+
+    int n = N;
+    if (bt.natoms) {
+        n = bt.natoms[b];
+        n = n < 0 ? 0 : (n > N ? N : n);
+    }
+    const int32_t *ty = VECTOR ? nullptr : bt.types + (size_t)b * N;
+    Xform X;
+    load_xform(X, b, bt.centers, bt.quats, bt.translations);
+    if (tid < 9) ws.rot[b * 12 + tid] = (float)X.R[tid];
+    float vec_reach = 0.0f;         // reach of the widest channel, for vector types
+    if (VECTOR) {
+        for (int k = 0; k < T; ++k) {
+            const float r = gs.radius_scale * bt.radii[k];
+            if (r > vec_reach) vec_reach = r;
+        }
+        if (!gs.binary) vec_reach *= gs.c;
+    }
+    Culler cu;
+    cu.pad = 1.0e-3f * gs.res;
+    cu.span = (float)(D - 1) * gs.res;
+    for (int m = 0; m < 3; ++m) cu.org[m] = (bt.centers ? bt.centers[3 * b + m] : 0.0f) - gs.half;
+
+    for (int k = tid; k < K; k += kExThreads) s_cnt[k] = 0;
+    for (int k = tid; k < Tg; k += kExThreads) s_rmax[k] = 0;
+    __syncthreads();
+
+    // ---- 1. key and rank inside its bin for every atom ----
+    for (int a = tid; a < N; a += kExThreads) {
+        int tg = 0;
+        bool member = a < n;
+        if (!VECTOR && member) {
+            tg = ty[a];
+            member = tg >= 0 && tg < T;
+        }
+        int key = 0xFFFF;
+        if (member) {
+            float p[3], r;
+            const bool live = place_atom<VECTOR>(gs, bt, X, cu, b, tg, a, vec_reach, p, &r);
+            int bin = D + 2;
+            if (live) {
+                const float f = floorf((p[0] - cu.org[0]) * gs.inv_res);
+                bin = f < 0.0f ? 0 : (f >= (float)D ? D + 1 : (int)f + 1);
+                atomicMax(&s_rmax[tg], __float_as_int(r));      // r > 0: ordered like ints
+            }
+            key = tg * nb + bin;
+            s_slot[a] = (unsigned short)atomicAdd(&s_cnt[key], 1);
+            if (!live) clear_grads(gclear, wclear, (size_t)b * N + a, T);
+        } else {
+            clear_grads(gclear, wclear, (size_t)b * N + a, T);   // no group owns this atom
+        }
+        s_key[a] = (unsigned short)key;
+    }
+    __syncthreads();
+
+    // ---- 2. exclusive scan of the counts ----
+    const int chunk = (K + kExThreads - 1) / kExThreads;
+    const int k0 = min(K, tid * chunk), k1 = min(K, k0 + chunk);
+    int mine = 0;
+    for (int k = k0; k < k1; ++k) mine += s_cnt[k];
+    int wtotal;
+    int run = wave_exclusive_scan(mine, &wtotal);
+    if ((tid & 63) == 0) s_part[tid >> 6] = wtotal;
+    __syncthreads();
+    if (tid < 64) {
+        int t16;
+        const int v = tid < kExThreads / 64 ? s_part[tid] : 0;
+        const int ex = wave_exclusive_scan(v, &t16);
+        if (tid < kExThreads / 64) s_part[tid] = ex;
+        if (tid == 0) s_part[kExThreads / 64] = t16;
+    }
+    __syncthreads();
+    run += s_part[tid >> 6];
+    const int total = s_part[kExThreads / 64];      // atoms that belong to a group
+    for (int k = k0; k < k1; ++k) {
+        s_pos[k] = run;
+        run += s_cnt[k];
+    }
+    __syncthreads();
+
+    // ---- 3. placement, then every live bin in atom order ----
+    for (int a = tid; a < N; a += kExThreads) {
+        const int key = s_key[a];
+        if (key != 0xFFFF) s_order[s_pos[key] + s_slot[a]] = (unsigned short)a;
+    }
+    __syncthreads();
+    for (int k = tid; k < K; k += kExThreads) {
+        const int bin = k - (k / nb) * nb;
+        if (bin == D + 2) continue;         // the order of culled atoms does not matter
+        const int lo = s_pos[k], hi = lo + s_cnt[k];
+        for (int i = lo + 1; i < hi; ++i) {
+            const unsigned short v = s_order[i];
+            int j = i - 1;
+            while (j >= lo && s_order[j] > v) {
+                s_order[j + 1] = s_order[j];
+                --j;
+            }
+            s_order[j + 1] = v;
+        }
+    }
+    __syncthreads();
+
+    // ---- 4. records, group descriptors, spans per plane ----
+    for (int pos = tid; pos < total; pos += kExThreads) {
+        const int a = s_order[pos];
+        const int tg = VECTOR ? 0 : ty[a];
+        float p[3], r;
+        const bool live = place_atom<VECTOR>(gs, bt, X, cu, b, tg, a, vec_reach, p, &r);
+        ws.rec[(size_t)b * N + pos] = make_float4(p[0], p[1], p[2], live ? r : 0.0f);
+        ws.idx[(size_t)b * N + pos] = a;
+    }
+    for (int tg = tid; tg < Tg; tg += kExThreads) {
+        const int first = s_pos[tg * nb];
+        const int dead = s_pos[tg * nb + D + 2];
+        const int end = tg + 1 < Tg ? s_pos[(tg + 1) * nb] : total;
+        ws.meta[(size_t)b * T + tg] = make_int4(first, dead - first, end - first, 1);
+    }
+    for (int e = tid; e < Tg * D; e += kExThreads) {
+        const int tg = e / D, i = e - tg * D;
+        // plane i is reached from bins [i - Rv, i + Rv + 1]
+        const float rmax = VECTOR ? vec_reach
+                                  : __int_as_float(s_rmax[tg]) * (gs.binary ? 1.0f : gs.c);
+        const int Rv = (int)ceilf(rmax * gs.inv_res + cu.pad) + 1;
+        const int lo = max(0, i - Rv), hi = min(D + 1, i + Rv + 1);
+        ws.range[((size_t)b * T + tg) * D + i] = make_int2(s_pos[tg * nb + lo], s_pos[tg * nb + hi + 1]);
+    }
 }
 
 // One wavefront per group: no barriers, the scans are wavefront shuffles.
@@ -404,7 +576,23 @@ hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                        float *wclear, hipStream_t stream)
 {
     const int stop = g_prep_stop;
-    if (bt.weights) {
+    const bool vec = bt.weights != nullptr;
+    ExLayout L;
+    L.Tg = vec ? 1 : bt.T;
+    L.N = bt.N;
+    const long long K = (long long)L.Tg * (gs.D + 3);
+    L.K = (int)(K <= kExMaxKeys ? K : 0);
+    const size_t lds_bytes = (size_t)L.ints() * sizeof(int);
+    if (K <= kExMaxKeys && bt.N <= kExMaxAtoms && lds_bytes <= 64 * 1024 && stop <= 1) {
+        if (vec)
+            hipLaunchKernelGGL(prep_example_kernel<true>, dim3(bt.B), dim3(kExThreads), lds_bytes,
+                               stream, gs, bt, ws, gclear, wclear, stop);
+        else
+            hipLaunchKernelGGL(prep_example_kernel<false>, dim3(bt.B), dim3(kExThreads), lds_bytes,
+                               stream, gs, bt, ws, gclear, wclear, stop);
+        return hipGetLastError();
+    }
+    if (vec) {
         hipLaunchKernelGGL(prep_kernel<true>, dim3(1, bt.B), dim3(kPrepThreads), 0, stream, gs, bt,
                            ws, gclear, wclear, stop);
     } else {

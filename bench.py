@@ -106,7 +106,8 @@ def main():
     ap.add_argument("--tile-floats", type=int, default=None, help="forward kernel tuning knob")
     ap.add_argument("--debug", type=int, default=None, help="forward kernel timing mode (wrong output)")
     ap.add_argument("--prep-stop", type=int, default=None, help="timing aid (wrong output)")
-    ap.add_argument("--lds-pad", type=int, default=None, help="forward kernel tuning knob")
+    ap.add_argument("--lds-floor", type=int, default=None, help="forward kernel tuning knob")
+    ap.add_argument("--waves-per-tile", type=int, default=None, help="forward kernel tuning knob")
     ap.add_argument("--xcd-run", type=int, default=None, help="forward kernel tuning knob")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size (for scaling rocprofv3 counters)")
@@ -140,8 +141,10 @@ def main():
         molgrid.set_option("debug", args.debug)
     if args.xcd_run is not None:
         molgrid.set_option("xcd_run", args.xcd_run)
-    if args.lds_pad is not None:
-        molgrid.set_option("lds_pad", args.lds_pad)
+    if args.lds_floor is not None:
+        molgrid.set_option("lds_floor", args.lds_floor)
+    if args.waves_per_tile is not None:
+        molgrid.set_option("waves_per_tile", args.waves_per_tile)
     if args.prep_stop is not None:
         molgrid.set_option("prep_stop", args.prep_stop)
 

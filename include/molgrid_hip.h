@@ -48,7 +48,7 @@ enum {
     MG_EWORKSPACE = -4,  /* workspace NULL, misaligned or too small             */
     MG_EHIP = -5,        /* the HIP runtime refused a launch (see mg_last_hip_error) */
     MG_EMODE = -6,       /* call not defined for this GridMaker (e.g. backward in binary mode) */
-    MG_EALIGN = -7       /* a float array is not 4-byte / workspace not 16-byte aligned */
+    MG_EALIGN = -7       /* a float / int array is not 4-byte aligned            */
 };
 
 #define MG_MAX_POINTS 1024      /* largest supported D (points per side) */
@@ -76,7 +76,7 @@ int mg_gridmaker_points_per_side(const mg_gridmaker *gm, int *D);
 /*
  * Bytes of caller-provided device workspace a forward/backward call with this
  * (B, N, T) needs (transformed, culled, channel-binned atom records).  The
- * workspace must be 16-byte aligned; its contents are scratch.
+ * workspace must be 32-byte aligned; its contents are scratch.
  */
 int mg_workspace_bytes(const mg_gridmaker *gm, int B, int N, int T, size_t *bytes);
 

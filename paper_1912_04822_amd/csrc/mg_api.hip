@@ -19,8 +19,9 @@ namespace {
 thread_local int g_last_hip_error = 0;
 thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 int g_tile_floats = 2048;
+int g_waves_per_tile = 1;
 int g_xcd_run = 0;
-int g_lds_pad = 0;
+int g_lds_floor = -1;     // < 0: chosen by the launcher
 int g_debug = 0;
 
 // Runs `launch` (the main kernel of a call) between the caller's timing events, if set.
@@ -54,7 +55,7 @@ int check_shape(const mg_gridmaker *gm, int B, int N, int T)
 int check_workspace(const mg_gridmaker *gm, int B, int N, int T, void *ws, size_t ws_bytes)
 {
         if (!ws) return MG_EWORKSPACE;
-    if (((uintptr_t)ws & 15u) != 0) return MG_EWORKSPACE;
+    if (((uintptr_t)ws & 31u) != 0) return MG_EWORKSPACE;
     if (ws_bytes < mg::workspace_bytes(B, N, T, gm->gs.D)) return MG_EWORKSPACE;
     return MG_OK;
 }
@@ -161,10 +162,11 @@ int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T, const float *c
     const mg::Batch bt = make_batch(B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
                                     translations);
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_tile_floats, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
-        return mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_xcd_run, g_lds_pad, g_debug,
+        return mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_waves_per_tile, g_xcd_run,
+                                  g_lds_floor, g_debug,
                                   (hipStream_t)stream);
     }));
 }
@@ -187,10 +189,11 @@ int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *
     const mg::Batch bt = make_batch(B, N, T, coords, nullptr, weights, radii, natoms, centers,
                                     quats, translations);
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_tile_floats, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
-        return mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_xcd_run, g_lds_pad, g_debug,
+        return mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_waves_per_tile, g_xcd_run,
+                                  g_lds_floor, g_debug,
                                   (hipStream_t)stream);
     }));
 }
@@ -214,7 +217,7 @@ int mg_backward_index(const mg_gridmaker *gm, int B, int N, int T, const float *
     const mg::Batch bt = make_batch(B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
                                     translations);
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, nullptr, (hipStream_t)stream));
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_tile_floats, grad_coords, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
         return mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, nullptr,
@@ -243,7 +246,7 @@ int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T, const float 
     const mg::Batch bt = make_batch(B, N, T, coords, nullptr, weights, radii, natoms, centers,
                                     quats, translations);
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, grad_weights,
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_tile_floats, grad_coords, grad_weights,
                                     (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
@@ -259,7 +262,7 @@ const char *mg_strerror(int code)
     case MG_ENULL: return "a required pointer is NULL";
     case MG_ESHAPE: return "bad shape: B, N, T must be >= 1, B <= 65535, 1 <= D <= 1024, sizes must fit";
     case MG_EPARAM: return "bad parameter: resolution, radius_scale and gaussian_radius_multiple must be finite and positive";
-    case MG_EWORKSPACE: return "workspace is NULL, not 16-byte aligned, or smaller than mg_workspace_bytes";
+    case MG_EWORKSPACE: return "workspace is NULL, not 32-byte aligned, or smaller than mg_workspace_bytes";
     case MG_EHIP: return "the HIP runtime refused a launch (mg_last_hip_error has the hipError_t)";
     case MG_EMODE: return "call not defined for this GridMaker (binary backward, or vector types without radius_type_indexed)";
     case MG_EALIGN: return "an array argument is not 4-byte aligned";
@@ -280,8 +283,13 @@ int mg_set_option(const char *key, int value)
 {
     if (!key) return MG_ENULL;
     if (std::strcmp(key, "tile_floats") == 0) {
-        if (value != 512 && value != 1024 && value != 2048 && value != 4096) return MG_EPARAM;
+        if (value != 1024 && value != 2048) return MG_EPARAM;
         g_tile_floats = value;
+        return MG_OK;
+    }
+    if (std::strcmp(key, "waves_per_tile") == 0) {
+        if (value != 1 && value != 2 && value != 4) return MG_EPARAM;
+        g_waves_per_tile = value;
         return MG_OK;
     }
     if (std::strcmp(key, "xcd_run") == 0) {
@@ -289,9 +297,9 @@ int mg_set_option(const char *key, int value)
         g_xcd_run = value;
         return MG_OK;
     }
-    if (std::strcmp(key, "lds_pad") == 0) {
-        if (value < 0 || value > 40000) return MG_EPARAM;
-        g_lds_pad = value;
+    if (std::strcmp(key, "lds_floor") == 0) {
+        if (value < -1 || value > 65536) return MG_EPARAM;
+        g_lds_floor = value;
         return MG_OK;
     }
     if (std::strcmp(key, "prep_stop") == 0) {

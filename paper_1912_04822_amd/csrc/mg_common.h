@@ -33,7 +33,7 @@ struct GridSpec {
 };
 
 // ---------------------------------------------------------------------------
-// Workspace layout (device, caller-provided, 16-byte aligned).  A "group" is
+// Workspace layout (device, caller-provided, 32-byte aligned).  A "group" is
 // the set of atoms one output channel reads: for index types the atoms of
 // example b with type t (group b*T+t), for vector types all atoms of example
 // b (group b*T+0).
@@ -48,19 +48,28 @@ struct GridSpec {
 //   meta  [B][T] int4     {first, live, all, sorted}; sorted = 0 means the
 //                         group was too long to bin: its records are in atom
 //                         order, culled ones carry r = 0, and live == all
-//   range [B][T][D] int2  for x-plane i: the span [r0, r1) of records, counted
-//                         from the example's first record rec[b][0], that can
-//                         reach the plane.  r0 and r1 do not decrease with i, so
-//                         planes i..k are reached by [range[i].x, range[k].y)
+//   tinfo [B][T][tiles] TileInfo  what the forward workgroup of tile q of a
+//                         channel needs first, in one 32-byte entry: the span
+//                         [r0, r1) of records, counted from the example's first
+//                         record rec[b][0], that can reach the x-planes the tile
+//                         touches, and the grid origin (centre - half extent)
 //   rot   [B][12] float   rotation matrix rows (9 used), for the backward pass
 // ---------------------------------------------------------------------------
-struct Workspace {
-    float4 *rec;
-    int    *idx;
-    int4   *meta;
-    int2   *range;
-    float  *rot;
+struct alignas(32) TileInfo {
+    int r0, r1;
+    float ox, oy, oz;
+    int pad[3];
 };
+
+struct Workspace {
+    float4   *rec;
+    int      *idx;
+    int4     *meta;
+    TileInfo *tinfo;
+    float    *rot;
+};
+
+constexpr int kMinTileFloats = 1024;    // smallest forward tile: sizes the tinfo table
 
 size_t workspace_bytes(int B, int N, int T, int D);
 Workspace carve_workspace(void *base, int B, int N, int T, int D);
@@ -81,7 +90,7 @@ struct Batch {
 // `tile_floats` consecutive floats of one channel (the last tile of a channel
 // may be shorter).
 struct ForwardGeometry {
-    int tile_floats;    // 512, 1024, 2048 or 4096
+    int tile_floats;    // 1024 or 2048
     int tiles;          // tiles per channel = ceil(D^3 / tile_floats)
 };
 ForwardGeometry forward_geometry(int D, int tile_floats);
@@ -94,12 +103,12 @@ extern int g_prep_stop;                 // timing aid: stop the prep kernel afte
 hipError_t launch_transform(int B, int N, const float *coords, const float *centers,
                             const float *quats, const float *translations, float *out,
                             hipStream_t stream);
-hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
+hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws, int tile_floats,
                        float *grad_coords_to_clear, float *grad_weights_to_clear,
                        hipStream_t stream);
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
-                          float *out, int tile_floats, int xcd_run, int lds_pad, int debug,
-                          hipStream_t stream);
+                          float *out, int tile_floats, int waves_per_tile, int xcd_run,
+                          int lds_floor, int debug, hipStream_t stream);
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                            const float *grad_out, float *grad_coords, float *grad_weights,
                            hipStream_t stream);

@@ -5,9 +5,11 @@
 // is cut into flat tiles of `tile_floats` consecutive floats (2048 = 8192 B by
 // default), whatever rows and x-planes that run happens to cover; with the
 // usual grids (D = 48, 96) every tile starts on a 4 KB boundary of the output.
-// One wavefront produces one tile:
-//   1. it loads the records of the channel's atoms that can reach the x-planes
-//      the tile touches (spans the prep kernel computed), one atom per lane;
+// One workgroup of 1, 2 or 4 wavefronts produces one tile; its wavefronts split
+// the atoms and, at the end, the 2 KB chunks of the tile between them:
+//   1. the workgroup loads the records of the channel's atoms that can reach the
+//      x-planes the tile touches (spans the prep kernel computed), one atom per
+//      lane, atom e going to wavefront e mod (number of wavefronts);
 //   2. each lane tests its atom against the tile's rows in two x-planes at a
 //      time (disc of the atom's cutoff sphere in the plane versus the row
 //      range).  Every surviving (atom, row) pair is a task; a wavefront scan
@@ -28,8 +30,13 @@
 //   4. the finished tile is streamed to HBM, each lane writing 32 contiguous
 //      bytes (two adjacent 16-byte stores), every output element exactly once,
 //      zeros included.  Tiles no atom touches skip LDS and store zeros.
-// No barrier is needed: a wavefront only touches its own LDS slice, which holds
-// the tile in output order (LDS index = output index - first index of the tile).
+// The tile sits in LDS in output order (LDS index = output index - first index of
+// the tile).  With more than one wavefront there are two barriers per tile: after
+// the zero fill and the decision between fixed point and float (which needs the
+// bound over all wavefronts), and before the tile is read back.  Splitting a tile
+// over two wavefronts halves the time a tile occupies its LDS, so that the
+// 12-13 tiles per CU that the store pattern wants (see below) are enough to keep
+// the CU busy.
 //
 // Why 8 KB tiles on 4 KB boundaries: measured on this chip, one-wavefront
 // workgroups that each write one aligned 4 KB or 8 KB run sustain 6.3-6.6 TB/s
@@ -54,7 +61,7 @@ namespace mg {
 
 namespace {
 
-constexpr int kTaskCap = 512;                   // (atom, row) tasks staged per round
+constexpr int kTaskCap = 256;                   // (atom, row) tasks staged per round
 constexpr float kFixedOne = 16777216.0f;        // 2^24
 constexpr float kFixedLimit = 120.0f;           // largest |sum| trusted to fixed point
 
@@ -62,7 +69,7 @@ struct FwdParams {
     GridSpec gs;
     const float4 *rec;
     const int *idx;
-    const int2 *range;
+    const TileInfo *tinfo;
     const float *weights;
     const float *radii;
     const float *centers;
@@ -85,8 +92,9 @@ struct FwdParams {
 // what a wavefront keeps for the tile it is working on (all wave-uniform)
 struct TileCtx {
     float *tile;                // LDS: tile_floats floats, in output order
-    unsigned char *marks;       // LDS: marks[first task of atom in lane l] = l + 1, else 0
-    int lane;
+    unsigned char *marks;       // LDS (per wavefront): marks[first task of the atom in lane l] = l + 1
+    int *shared;                // LDS (workgroup): [0] bound on |sum| (1/256 units), [1] any task
+    int lane, wave;
     int D, n;                   // points per side; floats in this tile
     int nrows;                  // grid rows the tile touches
     int c0, c1;                 // first column of its first row, last column of its last row
@@ -216,22 +224,24 @@ __device__ inline void run_tasks(const TileCtx &cx, const Cand &cd, int ntasks)
             const int khi = min(clip_hi, (int)floorf(fz + hz));
             const int nz = act ? khi - klo + 1 : 0;
             const float z0 = ((float)klo - fz) * stepk;
+            float cA = cx.cA;
+            asm volatile("" : "+v"(cA));        // keep it in a VGPR across the loop
             float fi = 0.0f;
             for (int i = 0; i < nz; ++i) {
                 const float zs = fmaf(fi, stepk, z0);
                 fi += 1.0f;
                 const float x2 = fmaf(zs, zs, x2b);
                 const float e = __builtin_amdgcn_exp2f(-x2);
-                const float u = fminf(fmaf(__builtin_amdgcn_sqrtf(x2), cx.sA, -cx.cA), 0.0f);
+                const float u = fminf(fmaf(__builtin_amdgcn_sqrtf(x2), cx.sA, -cA), 0.0f);
                 const float rho = x2 <= cx.g2k ? e : u * u;                 // 0 beyond the cutoff
                 if (FIXED) {
                     const int q = VECTOR ? (int)rintf(w * rho * kFixedOne)
                                          : (int)fmaf(rho, kFixedOne, 0.5f);
                     __hip_atomic_fetch_add(reinterpret_cast<int *>(rowp) + klo + i, q,
-                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 } else {
                     __hip_atomic_fetch_add(rowp + klo + i, VECTOR ? w * rho : rho, __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_WAVEFRONT);
+                                           __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
         }
@@ -269,13 +279,18 @@ __device__ inline int plane_rows(const TileCtx &cx, const FwdParams &p, const At
     return ok ? jhi - jlo + 1 : 0;
 }
 
-// One batch of up to 64 atoms (one per lane) against the rows of planes iA and iA + 1 that
-// belong to the tile.  mode: state of the whole tile;  bound: running bound on |sum|
-template <bool VECTOR, bool BINARY, int ITERS>
-__device__ inline void pair_batch(const TileCtx &cx, const FwdParams &p, const Atom &at, float gxA,
-                                  float gxB, int jaA, int jbA, int jaB, int jbB, int &mode,
-                                  float &bound)
+// What one lane found for its atom in planes iA and iA + 1 of the tile.
+struct PairHit {
+    Cand cd;
+    int nA, nB;         // rows reached in plane A, plane B
+};
+
+// One atom per lane against the rows of planes A and B that belong to the tile.
+template <bool VECTOR, bool BINARY>
+__device__ inline PairHit pair_test(const TileCtx &cx, const FwdParams &p, const Atom &at, float gxA,
+                                    float gxB, int jaA, int jbA, int jaB, int jbB)
 {
+    PairHit h;
     const float r = at.a.w;
     // per atom: position in grid steps, scale of its distances
     const float fy = (at.a.y - cx.oy) * cx.inv_res;
@@ -283,91 +298,92 @@ __device__ inline void pair_batch(const TileCtx &cx, const FwdParams &p, const A
     const float sks = at.valid ? p.sk * __builtin_amdgcn_rcpf(r) : 0.0f;
     const float stepk = cx.res * sks;
     const float inv_stepk = r * cx.inv_res * p.inv_sk;
-    float pxA, pxB;
-    int jloA, jloB;
-    int nA = plane_rows<BINARY>(cx, p, at, gxA, jaA, jbA, sks, inv_stepk, fy, fz, pxA, jloA);
-    int nB = plane_rows<BINARY>(cx, p, at, gxB, jaB, jbB, sks, inv_stepk, fy, fz, pxB, jloB);
-    if (cx.debug == 1) { nA = 0; nB = 0; }
-    if (nA == 0) jloA = 0;          // both are packed into bit fields below
-    if (nB == 0) jloB = 0;
-    const unsigned long long maskA = __ballot(nA > 0), maskB = __ballot(nB > 0);
-    if ((maskA | maskB) == 0ull) return;
-
-    // upper bound on what this batch can add to one voxel (rho <= 1); the two planes
-    // share no voxel
-    if (VECTOR) {
-        float sa = nA > 0 ? fabsf(at.w) : 0.0f, sb = nB > 0 ? fabsf(at.w) : 0.0f;
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
-            sa += __shfl_xor(sa, d, 64);
-            sb += __shfl_xor(sb, d, 64);
-        }
-        bound += fmaxf(sa, sb);
-    } else {
-        bound += (float)max(__builtin_popcountll(maskA), __builtin_popcountll(maskB));
-    }
-    if (mode == kUntouched) {
-        mode = (BINARY || bound > kFixedLimit) ? kFloat : kFixed;
-        const float4 z4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);     // same bits as integer zeros
-#pragma unroll
-        for (int it = 0; it < 2 * ITERS; ++it)
-            reinterpret_cast<float4 *>(cx.tile)[it * 64 + cx.lane] = z4;
-    } else if (mode == kFixed && bound > kFixedLimit) {
-        mode = kFloat;                                               // leave fixed point
-        for (int o = cx.lane; o < ITERS * 512; o += 64)
-            cx.tile[o] = (float)reinterpret_cast<int *>(cx.tile)[o] * (1.0f / kFixedOne);
-    }
-
-    // tasks of this lane's atom: rows of plane A, then rows of plane B
-    Cand cd;
+    int jloA, jloB = 0;
+    h.nA = plane_rows<BINARY>(cx, p, at, gxA, jaA, jbA, sks, inv_stepk, fy, fz, h.cd.pxA, jloA);
+    h.nB = 0;
+    h.cd.pxB = 0.0f;
+    if (jaB < jbB)      // uniform: most tiles of small tile sizes lie in one plane
+        h.nB = plane_rows<BINARY>(cx, p, at, gxB, jaB, jbB, sks, inv_stepk, fy, fz, h.cd.pxB, jloB);
+    if (cx.debug == 1) { h.nA = 0; h.nB = 0; }
+    if (h.nA == 0) jloA = 0;        // both are packed into bit fields below
+    if (h.nB == 0) jloB = 0;
     if (BINARY) {
         const float reach = r + 1.0e-3f * cx.res;
-        cd.c0 = at.a.y; cd.c1 = at.a.z; cd.c2 = r * r; cd.c3 = reach * reach;
+        h.cd.c0 = at.a.y; h.cd.c1 = at.a.z; h.cd.c2 = r * r; h.cd.c3 = reach * reach;
     } else {
-        cd.c0 = fy; cd.c1 = fz; cd.c2 = stepk; cd.c3 = VECTOR ? at.w : inv_stepk;
+        h.cd.c0 = fy; h.cd.c1 = fz; h.cd.c2 = stepk; h.cd.c3 = VECTOR ? at.w : inv_stepk;
     }
-    cd.pxA = pxA; cd.pxB = pxB;
-    cd.start = 0;
-    cd.pack = jloA | (nA << 10) | (jloB << 20);
-    int todo = nA + nB;             // lanes still to be staged have todo > 0
+    h.cd.start = 0;
+    h.cd.pack = jloA | (h.nA << 10) | (jloB << 20);
+    return h;
+}
+
+// What the hits of this wavefront can add to one voxel at most (rho <= 1), in 1/256.
+template <bool VECTOR>
+__device__ inline int pair_bound(const PairHit &h, const Atom &at)
+{
+    const bool hit = h.nA + h.nB > 0;
+    if (VECTOR) {
+        float s = hit ? fminf(fabsf(at.w), 4096.0f) : 0.0f;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
+        return (int)ceilf(s * 256.0f);
+    }
+    return 256 * (int)__builtin_popcountll(__ballot(hit));
+}
+
+// Stage the tasks of the hits (rows of plane A, then rows of plane B, atom after atom)
+// and run them.
+template <bool VECTOR, bool BINARY>
+__device__ inline void pair_run(const TileCtx &cx, PairHit &h, bool fixed)
+{
+    int todo = h.nA + h.nB;         // lanes still to be staged have todo > 0
+    if (__ballot(todo > 0) == 0ull) return;
+    if (cx.lane == 0) cx.shared[1] = 1;
     while (true) {
         const int incl = wave_inclusive_scan(todo);
-        const bool now = todo > 0 && incl <= kTaskCap;              // fits this round
-        const int total = bcast(wave_inclusive_scan(now ? todo : 0), 63);
+        int total = bcast(incl, 63);
         if (total == 0) break;
+        bool now = todo > 0;
+        if (total > kTaskCap) {     // rare: the rest waits for the next round
+            now = now && incl <= kTaskCap;
+            total = bcast(wave_inclusive_scan(now ? todo : 0), 63);
+            if (total == 0) break;
+        }
         if (cx.lane < kTaskCap / 16)
             reinterpret_cast<float4 *>(cx.marks)[cx.lane] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         if (now) {
-            cd.start = incl - todo;
-            cx.marks[cd.start] = (unsigned char)(cx.lane + 1);
+            h.cd.start = incl - todo;
+            cx.marks[h.cd.start] = (unsigned char)(cx.lane + 1);
             todo = 0;
         }
         lds_sync();
-        if (mode == kFixed) run_tasks<VECTOR, BINARY, true>(cx, cd, total);
-        else run_tasks<VECTOR, BINARY, false>(cx, cd, total);
+        if (fixed) run_tasks<VECTOR, BINARY, true>(cx, h.cd, total);
+        else run_tasks<VECTOR, BINARY, false>(cx, h.cd, total);
     }
 }
 
-// Stream a finished tile to HBM (or zeros if no atom touched it).
-// ITERS = tile_floats / 512: each pass of the wavefront covers 2 KB.
-template <bool ALIGNED, int ITERS>
-__device__ inline void store_tile(const TileCtx &cx, float *dst, int mode)
+// Stream the finished tile to HBM (zeros if no atom touched it).  ITERS = tile_floats / 512
+// chunks of 2 KB; wavefront w of NW takes chunks w, w + NW, ...
+template <bool ALIGNED, int ITERS, int NW>
+__device__ inline void store_tile(const TileCtx &cx, float *dst, bool touched, bool fixed)
 {
     if (ALIGNED) {
+        constexpr int MINE = ITERS / NW;            // chunks per wavefront
         const int n4 = cx.n >> 2;                   // even: D^3 and the tile size are multiples of 8
         float4 *dst4 = reinterpret_cast<float4 *>(dst);
         const float4 *src4 = reinterpret_cast<const float4 *>(cx.tile);
         // Constant trip count, fully unrolled; the tile comes from LDS into registers
-        // under a wave-uniform branch (zeros otherwise), so that the stores below are one
+        // under a uniform branch (zeros otherwise), so that the stores below are one
         // straight sequence with no load between them.
-        float4 v[2 * ITERS];
-        if (mode != kUntouched) {
+        float4 v[2 * MINE];
+        if (touched) {
 #pragma unroll
-            for (int it = 0; it < 2 * ITERS; ++it)
-                v[it] = src4[(it >> 1) * 128 + cx.lane * 2 + (it & 1)];
-            if (mode == kFixed) {
+            for (int it = 0; it < 2 * MINE; ++it)
+                v[it] = src4[((it >> 1) * NW + cx.wave) * 128 + cx.lane * 2 + (it & 1)];
+            if (fixed) {
 #pragma unroll
-                for (int it = 0; it < 2 * ITERS; ++it) {
+                for (int it = 0; it < 2 * MINE; ++it) {
                     const float sc = 1.0f / kFixedOne;
                     v[it] = make_float4((float)__float_as_int(v[it].x) * sc,
                                         (float)__float_as_int(v[it].y) * sc,
@@ -377,38 +393,38 @@ __device__ inline void store_tile(const TileCtx &cx, float *dst, int mode)
             }
         } else {
 #pragma unroll
-            for (int it = 0; it < 2 * ITERS; ++it) v[it] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            for (int it = 0; it < 2 * MINE; ++it) v[it] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         }
         // the two 16-byte halves of a lane's 32 bytes go out back to back, under one
         // predicate: separated by other instructions they are markedly slower
 #pragma unroll
-        for (int it = 0; it < ITERS; ++it) {
-            const int o = it * 128 + cx.lane * 2;
+        for (int it = 0; it < MINE; ++it) {
+            const int o = (it * NW + cx.wave) * 128 + cx.lane * 2;
             if (o < n4) {
                 dst4[o] = v[2 * it];
                 dst4[o + 1] = v[2 * it + 1];
             }
         }
     } else {
-        for (int o = cx.lane; o < cx.n; o += 64) {
+        for (int o = cx.wave * 64 + cx.lane; o < cx.n; o += 64 * NW) {
             float v = 0.0f;
-            if (mode == kFloat) v = cx.tile[o];
-            if (mode == kFixed)
-                v = (float)reinterpret_cast<const int *>(cx.tile)[o] * (1.0f / kFixedOne);
+            if (touched)
+                v = fixed ? (float)reinterpret_cast<const int *>(cx.tile)[o] * (1.0f / kFixedOne)
+                          : cx.tile[o];
             dst[o] = v;
         }
     }
 }
 
-template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS>
-__global__ __launch_bounds__(64) void forward_kernel(FwdParams p)
+template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS, int NW>
+__global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
 {
-    extern __shared__ __attribute__((aligned(16))) float lds[];   // tile | marks
+    extern __shared__ __attribute__((aligned(16))) float lds[];   // tile | marks per wave | shared
 
-    // One wavefront per tile.  Workgroup ids go round the 8 XCDs (id % 8), each with its
-    // own L2: runs of consecutive tiles, which read the same atom records, are given to
-    // one XCD.
-    const int lane = threadIdx.x;
+    // One workgroup per tile.  Workgroup ids go round the 8 XCDs (id % 8), each with its
+    // own L2: runs of consecutive tiles, which read the same atom records, can be given
+    // to one XCD.
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const GridSpec &gs = p.gs;
     const int D = gs.D, T = p.T, N = p.N;
     unsigned u = blockIdx.x;
@@ -431,8 +447,10 @@ __global__ __launch_bounds__(64) void forward_kernel(FwdParams p)
 
     TileCtx cx;
     cx.tile = lds;
-    cx.marks = reinterpret_cast<unsigned char *>(lds + ITERS * 512);
+    cx.marks = reinterpret_cast<unsigned char *>(lds + ITERS * 512) + wave * kTaskCap;
+    cx.shared = reinterpret_cast<int *>(lds + ITERS * 512 + NW * (kTaskCap / 4));
     cx.lane = lane;
+    cx.wave = wave;
     cx.D = D;
     cx.n = f1 - f0;
     cx.nrows = R1 - R0;
@@ -447,34 +465,32 @@ __global__ __launch_bounds__(64) void forward_kernel(FwdParams p)
 
     float *dst = p.out + ((size_t)b * T + t) * (size_t)total + f0;
     if (p.debug == 3) {         // timing aid: nothing but the zero stores
-        store_tile<ALIGNED, ITERS>(cx, dst, kUntouched);
+        store_tile<ALIGNED, ITERS, NW>(cx, dst, false, false);
         return;
     }
     const size_t group = (size_t)b * T + (VECTOR ? 0 : t);
-    // All the scalar loads of the preamble are issued together (one trip to L2, which is
-    // slow while the chip streams stores): the span of records that can reach planes
-    // i_lo .. i_hi (counted from the example's first record) and the grid centre.
-    const int2 *span = p.range + group * D;
-    const float *cen = p.centers ? p.centers + 3 * b : reinterpret_cast<const float *>(span);
-    const int r0 = span[i_lo].x;
-    const int r1_loaded = span[i_hi].y;
-    const float cen_x = cen[0], cen_y = cen[1], cen_z = cen[2];
-    asm volatile("" ::"s"(r0), "s"(r1_loaded), "s"(cen_x), "s"(cen_y), "s"(cen_z));  // all in flight before the first wait
-    const int r1 = p.debug == 2 ? r0 : r1_loaded;
-    const float ox = (p.centers ? cen_x : 0.0f) - gs.half;
-    cx.oy = (p.centers ? cen_y : 0.0f) - gs.half;
-    cx.oz = (p.centers ? cen_z : 0.0f) - gs.half;
+    // One 32-byte entry written by the prep kernel holds what the tile needs first (one
+    // scalar load, one trip to L2, which is slow while the chip streams stores): the span
+    // of records that can reach the tile's planes and the grid origin.
+    const TileInfo ti = p.tinfo[group * p.tiles + tile_in_chan];
+    const int r0 = ti.r0;
+    const int r1 = p.debug == 2 ? r0 : ti.r1;
+    const float ox = ti.ox;
+    cx.oy = ti.oy;
+    cx.oz = ti.oz;
     const float r_chan = VECTOR ? gs.radius_scale * p.radii[t] : 0.0f;
 
     const float4 *rec = p.rec + (size_t)b * N + r0;
     const int *idx = p.idx + (size_t)b * N + r0;
     const int count = r1 - r0;
+    if (count <= 0) {           // uniform: nothing can reach this tile
+        store_tile<ALIGNED, ITERS, NW>(cx, dst, false, false);
+        return;
+    }
 
-    int mode = kUntouched;
-    float bound = 0.0f;         // over all batches and planes: never too small
-    for (int base = 0; base < count; base += 64) {
-        // one atom per lane
-        const int e = base + lane;
+    // atom e of the span goes to lane e / NW of wavefront e % NW, round after round
+    auto load_atom = [&](int base) {
+        const int e = base + lane * NW + wave;
         Atom at;
         at.a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         at.w = 1.0f;
@@ -487,18 +503,64 @@ __global__ __launch_bounds__(64) void forward_kernel(FwdParams p)
             at.a.w = r_chan;
             at.valid = at.valid && (r_chan > 0.0f) && (BINARY ? (at.w > 0.0f) : (at.w != 0.0f));
         }
-        // the planes the tile touches, two at a time
-        for (int iA = i_lo; iA <= i_hi; iA += 2) {
-            cx.rowA = iA * D - R0;
-            cx.rowB = cx.rowA + D;
-            const int jaA = max(-cx.rowA, 0), jbA = min(R1 - R0 - cx.rowA, D);
-            const int jaB = max(-cx.rowB, 0), jbB = iA < i_hi ? min(R1 - R0 - cx.rowB, D) : 0;
-            pair_batch<VECTOR, BINARY, ITERS>(cx, p, at, ox + (float)iA * gs.res,
-                                              ox + (float)(iA + 1) * gs.res, jaA, jbA, jaB, jbB,
-                                              mode, bound);
+        return at;
+    };
+    auto test_pair = [&](const Atom &at, int iA) {
+        cx.rowA = iA * D - R0;
+        cx.rowB = cx.rowA + D;
+        const int jaA = max(-cx.rowA, 0), jbA = min(R1 - R0 - cx.rowA, D);
+        const int jaB = max(-cx.rowB, 0), jbB = iA < i_hi ? min(R1 - R0 - cx.rowB, D) : 0;
+        return pair_test<VECTOR, BINARY>(cx, p, at, ox + (float)iA * gs.res,
+                                         ox + (float)(iA + 1) * gs.res, jaA, jbA, jaB, jbB);
+    };
+
+    // the loads of the first round are under way; clear the tile meanwhile
+    Atom at0 = load_atom(0);
+    {
+        const float4 z4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);     // same bits as integer zeros
+#pragma unroll
+        for (int it = 0; it < 2 * ITERS / NW; ++it)
+            reinterpret_cast<float4 *>(cx.tile)[it * 64 * NW + threadIdx.x] = z4;
+        if (threadIdx.x < 2) cx.shared[threadIdx.x] = 0;
+    }
+    const bool single = count <= 64 * NW && i_hi - i_lo <= 1;      // one round, one pair of planes
+    PairHit h0;
+    if (NW > 1) __syncthreads();                    // shared[] is clear
+    // pass 1: what can be added to one voxel at most decides fixed point or float
+    if (single) {
+        h0 = test_pair(at0, i_lo);
+        if (!BINARY) {
+            const int bnd = pair_bound<VECTOR>(h0, at0);
+            if (lane == 0 && bnd > 0) atomicAdd(&cx.shared[0], bnd);
+        }
+    } else if (!BINARY) {
+        for (int base = 0; base < count; base += 64 * NW) {
+            const Atom at = base == 0 ? at0 : load_atom(base);
+            for (int iA = i_lo; iA <= i_hi; iA += 2) {
+                const PairHit h = test_pair(at, iA);
+                const int bnd = pair_bound<VECTOR>(h, at);
+                // once past the limit the exact value does not matter (and must not overflow)
+                if (lane == 0 && bnd > 0 && cx.shared[0] <= (int)(kFixedLimit * 256.0f))
+                    atomicAdd(&cx.shared[0], min(bnd, 1 << 24));
+            }
         }
     }
-    store_tile<ALIGNED, ITERS>(cx, dst, mode);
+    __syncthreads();                                // tile and shared[0] are ready
+    const bool fixed = !BINARY && cx.shared[0] <= (int)(kFixedLimit * 256.0f);
+    // pass 2: the tasks
+    if (single) {
+        pair_run<VECTOR, BINARY>(cx, h0, fixed);
+    } else {
+        for (int base = 0; base < count; base += 64 * NW) {
+            const Atom at = base == 0 ? at0 : load_atom(base);
+            for (int iA = i_lo; iA <= i_hi; iA += 2) {
+                PairHit h = test_pair(at, iA);
+                pair_run<VECTOR, BINARY>(cx, h, fixed);
+            }
+        }
+    }
+    __syncthreads();                                // every wavefront's additions are in the tile
+    store_tile<ALIGNED, ITERS, NW>(cx, dst, cx.shared[1] != 0, fixed);
 }
 
 }  // namespace
@@ -523,15 +585,15 @@ unsigned long long magic64(unsigned d)      // ceil(2^64 / d); 0 stands for d ==
 }  // namespace
 
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws, float *out,
-                          int tile_floats, int xcd_run, int lds_pad, int debug,
-                          hipStream_t stream)
+                          int tile_floats, int waves_per_tile, int xcd_run, int lds_floor,
+                          int debug, hipStream_t stream)
 {
     const ForwardGeometry fg = forward_geometry(gs.D, tile_floats);
     FwdParams p;
     p.gs = gs;
     p.rec = ws.rec;
     p.idx = ws.idx;
-    p.range = ws.range;
+    p.tinfo = ws.tinfo;
     p.weights = bt.weights;
     p.radii = bt.radii;
     p.centers = bt.centers;
@@ -559,19 +621,26 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     p.c2k = (float)((double)gs.c * (double)gs.c * k);
     p.sA = (float)std::sqrt((double)gs.A / k);
     p.cA = (float)((double)gs.c * std::sqrt((double)gs.A));
-    const size_t lds_bytes = (size_t)tile_floats * sizeof(float) + kTaskCap + lds_pad;
+    const int iters = tile_floats / 512;
+    const int nw = waves_per_tile < iters ? waves_per_tile : iters;
+    // tile | marks of each wavefront | shared words; lds_floor raises the request to cap how
+    // many tiles are resident on a CU (the store pattern wants about 12 tiles of 8 KB)
+    size_t lds_bytes = (size_t)tile_floats * sizeof(float) + (size_t)nw * kTaskCap + 16;
+    if (lds_floor < 0) lds_floor = 0;
+    if (lds_bytes < (size_t)lds_floor) lds_bytes = (size_t)lds_floor;
     const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)out & 15u) == 0);
     const bool vec = bt.weights != nullptr;
-    const dim3 blk(64), grd((unsigned)groups);
-#define MG_LAUNCH4(V, Bn, Al, It) \
-    hipLaunchKernelGGL((forward_kernel<V, Bn, Al, It>), grd, blk, lds_bytes, stream, p)
-#define MG_LAUNCH(V, Bn, Al)                            \
-    switch (tile_floats) {                              \
-    case 512: MG_LAUNCH4(V, Bn, Al, 1); break;          \
-    case 1024: MG_LAUNCH4(V, Bn, Al, 2); break;         \
-    case 2048: MG_LAUNCH4(V, Bn, Al, 4); break;         \
-    case 4096: MG_LAUNCH4(V, Bn, Al, 8); break;         \
-    default: return hipErrorInvalidValue;               \
+    const dim3 blk(64 * nw), grd((unsigned)groups);
+#define MG_LAUNCH5(V, Bn, Al, It, Nw) \
+    hipLaunchKernelGGL((forward_kernel<V, Bn, Al, It, Nw>), grd, blk, lds_bytes, stream, p)
+#define MG_LAUNCH(V, Bn, Al)                                                    \
+    switch (iters * 8 + nw) {                                                   \
+    case 2 * 8 + 1: MG_LAUNCH5(V, Bn, Al, 2, 1); break;                         \
+    case 2 * 8 + 2: MG_LAUNCH5(V, Bn, Al, 2, 2); break;                         \
+    case 4 * 8 + 1: MG_LAUNCH5(V, Bn, Al, 4, 1); break;                         \
+    case 4 * 8 + 2: MG_LAUNCH5(V, Bn, Al, 4, 2); break;                         \
+    case 4 * 8 + 4: MG_LAUNCH5(V, Bn, Al, 4, 4); break;                         \
+    default: return hipErrorInvalidValue;                                       \
     }
     if (vec) {
         if (gs.binary) { if (aligned) MG_LAUNCH(true, true, true) else MG_LAUNCH(true, true, false) }
@@ -581,7 +650,7 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
         else           { if (aligned) MG_LAUNCH(false, false, true) else MG_LAUNCH(false, false, false) }
     }
 #undef MG_LAUNCH
-#undef MG_LAUNCH4
+#undef MG_LAUNCH5
     return hipGetLastError();
 }
 

@@ -130,12 +130,14 @@ def test_forward_protein_ligand_subset_and_determinism(mg):
     assert got.max() > 1.0
     again = run_forward_index(mg, w)
     assert np.array_equal(got.view(np.uint32), again.view(np.uint32))
-    for tile_floats in (512, 1024, 4096):
+    for tile_floats, waves in ((1024, 1), (1024, 2), (2048, 2), (2048, 4)):
         mg.set_option("tile_floats", tile_floats)
+        mg.set_option("waves_per_tile", waves)
         try:
             other = run_forward_index(mg, w)
         finally:
             mg.set_option("tile_floats", 2048)
+            mg.set_option("waves_per_tile", 1)
         # the knob changes the order in which overlapping atoms are summed: equal to rounding
         assert np.abs(got - other).max() <= 2e-6
         assert np.abs(other - ref).max() <= GRID_TOL

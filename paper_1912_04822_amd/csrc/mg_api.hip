@@ -162,7 +162,7 @@ int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T, const float *c
     const mg::Batch bt = make_batch(B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
                                     translations);
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_tile_floats, nullptr, nullptr, (hipStream_t)stream));
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
         return mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_waves_per_tile, g_xcd_run,
@@ -189,7 +189,7 @@ int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *
     const mg::Batch bt = make_batch(B, N, T, coords, nullptr, weights, radii, natoms, centers,
                                     quats, translations);
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_tile_floats, nullptr, nullptr, (hipStream_t)stream));
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
         return mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_waves_per_tile, g_xcd_run,
@@ -217,7 +217,7 @@ int mg_backward_index(const mg_gridmaker *gm, int B, int N, int T, const float *
     const mg::Batch bt = make_batch(B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
                                     translations);
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_tile_floats, grad_coords, nullptr, (hipStream_t)stream));
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {
         return mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, nullptr,
@@ -246,7 +246,7 @@ int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T, const float 
     const mg::Batch bt = make_batch(B, N, T, coords, nullptr, weights, radii, natoms, centers,
                                     quats, translations);
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, g_tile_floats, grad_coords, grad_weights,
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, grad_weights,
                                     (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(timed((hipStream_t)stream, [&] {

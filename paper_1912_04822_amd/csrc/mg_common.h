@@ -48,28 +48,22 @@ struct GridSpec {
 //   meta  [B][T] int4     {first, live, all, sorted}; sorted = 0 means the
 //                         group was too long to bin: its records are in atom
 //                         order, culled ones carry r = 0, and live == all
-//   tinfo [B][T][tiles] TileInfo  what the forward workgroup of tile q of a
-//                         channel needs first, in one 32-byte entry: the span
-//                         [r0, r1) of records, counted from the example's first
-//                         record rec[b][0], that can reach the x-planes the tile
-//                         touches, and the grid origin (centre - half extent)
+//   range [B][T][D] int2  for x-plane i: the span [r0, r1) of records, counted from
+//                         the example's first record rec[b][0], that can reach
+//                         the plane; r0 and r1 do not decrease with i, so planes
+//                         i..k are reached by [range[i].x, range[k].y).  The table
+//                         is small and every line of it is read by several
+//                         forward workgroups: reads that miss L2 while the chip
+//                         streams stores cost far more than their bytes
 //   rot   [B][12] float   rotation matrix rows (9 used), for the backward pass
 // ---------------------------------------------------------------------------
-struct alignas(32) TileInfo {
-    int r0, r1;
-    float ox, oy, oz;
-    int pad[3];
-};
-
 struct Workspace {
-    float4   *rec;
-    int      *idx;
-    int4     *meta;
-    TileInfo *tinfo;
-    float    *rot;
+    float4 *rec;
+    int    *idx;
+    int4   *meta;
+    int2   *range;
+    float  *rot;
 };
-
-constexpr int kMinTileFloats = 1024;    // smallest forward tile: sizes the tinfo table
 
 size_t workspace_bytes(int B, int N, int T, int D);
 Workspace carve_workspace(void *base, int B, int N, int T, int D);
@@ -103,7 +97,7 @@ extern int g_prep_stop;                 // timing aid: stop the prep kernel afte
 hipError_t launch_transform(int B, int N, const float *coords, const float *centers,
                             const float *quats, const float *translations, float *out,
                             hipStream_t stream);
-hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws, int tile_floats,
+hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                        float *grad_coords_to_clear, float *grad_weights_to_clear,
                        hipStream_t stream);
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws,

@@ -69,7 +69,7 @@ struct FwdParams {
     GridSpec gs;
     const float4 *rec;
     const int *idx;
-    const TileInfo *tinfo;
+    const int2 *range;
     const float *weights;
     const float *radii;
     const float *centers;
@@ -472,12 +472,19 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     // One 32-byte entry written by the prep kernel holds what the tile needs first (one
     // scalar load, one trip to L2, which is slow while the chip streams stores): the span
     // of records that can reach the tile's planes and the grid origin.
-    const TileInfo ti = p.tinfo[group * p.tiles + tile_in_chan];
-    const int r0 = ti.r0;
-    const int r1 = p.debug == 2 ? r0 : ti.r1;
-    const float ox = ti.ox;
-    cx.oy = ti.oy;
-    cx.oz = ti.oz;
+    // All the scalar loads of the preamble are issued together (one trip to L2, which is
+    // slow while the chip streams stores): the span of records that can reach planes
+    // i_lo .. i_hi (counted from the example's first record) and the grid centre.
+    const int2 *span = p.range + group * D;
+    const float *cen = p.centers ? p.centers + 3 * b : reinterpret_cast<const float *>(span);
+    const int r0 = span[i_lo].x;
+    int r1 = span[i_hi].y;
+    const float cen_x = cen[0], cen_y = cen[1], cen_z = cen[2];
+    asm volatile("" ::"s"(r0), "s"(r1), "s"(cen_x), "s"(cen_y), "s"(cen_z));  // all in flight before the first wait
+    const float ox = (p.centers ? cen_x : 0.0f) - gs.half;
+    cx.oy = (p.centers ? cen_y : 0.0f) - gs.half;
+    cx.oz = (p.centers ? cen_z : 0.0f) - gs.half;
+    if (p.debug == 2) r1 = r0;
     const float r_chan = VECTOR ? gs.radius_scale * p.radii[t] : 0.0f;
 
     const float4 *rec = p.rec + (size_t)b * N + r0;
@@ -593,7 +600,7 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     p.gs = gs;
     p.rec = ws.rec;
     p.idx = ws.idx;
-    p.tinfo = ws.tinfo;
+    p.range = ws.range;
     p.weights = bt.weights;
     p.radii = bt.radii;
     p.centers = bt.centers;

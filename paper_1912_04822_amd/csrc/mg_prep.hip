@@ -23,8 +23,7 @@
 //   2. exclusive scan of the counts = where each (type, bin) starts;
 //   3. atoms are placed, each bin is put in atom order (so the order in which
 //      the forward kernel sums is fixed), records are written bin by bin;
-//   4. for every type and forward tile, the span of records that can reach the
-//      x-planes the tile touches.
+//   4. for every type and x-plane, the span of records that can reach it.
 // Large N or very many (type, bin) pairs take the slower kernel below it: one
 // wavefront per group (example b, type t; vector types: example b) that scans
 // the example's types for its own atoms.
@@ -117,18 +116,6 @@ __device__ inline int wave_exclusive_scan(int v, int *total)
 
 __device__ inline void lds_sync() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); }
 
-// Planes [i_lo, i_hi] touched by tile q (tile_floats consecutive floats of a D^3 channel).
-__device__ inline void tile_planes(int q, int tile_floats, int D, int *i_lo, int *i_hi)
-{
-    const long long total = (long long)D * D * D;
-    const long long f0 = (long long)q * tile_floats;
-    long long f1 = f0 + tile_floats;
-    if (f1 > total) f1 = total;
-    const long long dd = (long long)D * D;
-    *i_lo = (int)(f0 / dd);
-    *i_hi = (int)((f1 - 1) / dd);
-}
-
 struct Culler {
     float org[3];       // grid origin (center - half)
     float span;         // (D-1)*res
@@ -190,8 +177,7 @@ struct ExLayout {       // LDS, in ints
 
 template <bool VECTOR>
 __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, Batch bt,
-                                                                  Workspace ws, int tile_floats,
-                                                                  int tiles, float *gclear,
+                                                                  Workspace ws, float *gclear,
                                                                   float *wclear, int stop)
 {
     extern __shared__ int s_mem[];
@@ -327,29 +313,21 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
         const int end = tg + 1 < Tg ? s_pos[(tg + 1) * nb] : total;
         ws.meta[(size_t)b * T + tg] = make_int4(first, dead - first, end - first, 1);
     }
-    for (int e = tid; e < Tg * tiles; e += kExThreads) {
-        const int tg = e / tiles, q = e - tg * tiles;
-        int i_lo, i_hi;
-        tile_planes(q, tile_floats, D, &i_lo, &i_hi);
-        // planes i_lo .. i_hi are reached from bins [i_lo - Rv, i_hi + Rv + 1]
+    for (int e = tid; e < Tg * D; e += kExThreads) {
+        const int tg = e / D, i = e - tg * D;
+        // plane i is reached from bins [i - Rv, i + Rv + 1]
         const float rmax = VECTOR ? vec_reach
                                   : __int_as_float(s_rmax[tg]) * (gs.binary ? 1.0f : gs.c);
         const int Rv = (int)ceilf(rmax * gs.inv_res + cu.pad) + 1;
-        const int lo = max(0, i_lo - Rv), hi = min(D + 1, i_hi + Rv + 1);
-        TileInfo ti;
-        ti.r0 = s_pos[tg * nb + lo];
-        ti.r1 = s_pos[tg * nb + hi + 1];
-        ti.ox = cu.org[0]; ti.oy = cu.org[1]; ti.oz = cu.org[2];
-        ti.pad[0] = 0; ti.pad[1] = 0; ti.pad[2] = 0;
-        ws.tinfo[((size_t)b * T + tg) * tiles + q] = ti;
+        const int lo = max(0, i - Rv), hi = min(D + 1, i + Rv + 1);
+        ws.range[((size_t)b * T + tg) * D + i] = make_int2(s_pos[tg * nb + lo], s_pos[tg * nb + hi + 1]);
     }
 }
 
 // One wavefront per group: no barriers, the scans are wavefront shuffles.
 template <bool VECTOR>
 __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspace ws,
-                                                  int tile_floats, int tiles, float *gclear,
-                                                  float *wclear, int stop)
+                                                  float *gclear, float *wclear, int stop)
 {
     __shared__ int s_list[kSortCap];                // atom index of match m
     __shared__ unsigned short s_bin[kSortCap];      // x-bin of match m, 0xFFFF = culled
@@ -418,7 +396,6 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
     int *idx = ws.idx + (size_t)b * N + first;
     const size_t group = (size_t)b * T + t;
     const int nbins = D + 2;
-    TileInfo *tinfo = ws.tinfo + group * tiles;
 
     if (M <= kSortCap) {
         // ---- 2. match list, transform, cull, count per x-bin ----
@@ -466,20 +443,13 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
             run += s_cnt[k];
         }
         lds_sync();
-        // ---- 4. span of records that can reach each forward tile ----
-        // planes i_lo .. i_hi are reached from bins [i_lo - Rv, i_hi + Rv + 1]
+        // ---- 4. span of records that can reach each plane ----
+        // plane i is reached from bins [i - Rv, i + Rv + 1]
         const float rmax = VECTOR ? vec_reach : __int_as_float(s_rmax) * (gs.binary ? 1.0f : gs.c);
         const int Rv = (int)ceilf(rmax * gs.inv_res + cu.pad) + 1;
-        for (int q = lane; q < tiles; q += 64) {
-            int i_lo, i_hi;
-            tile_planes(q, tile_floats, D, &i_lo, &i_hi);
-            const int lo = max(0, i_lo - Rv), hi = min(D + 1, i_hi + Rv + 1);
-            TileInfo ti;
-            ti.r0 = first + s_pos[lo];
-            ti.r1 = first + (hi + 1 < nbins ? s_pos[hi + 1] : L);
-            ti.ox = cu.org[0]; ti.oy = cu.org[1]; ti.oz = cu.org[2];
-            ti.pad[0] = 0; ti.pad[1] = 0; ti.pad[2] = 0;
-            tinfo[q] = ti;
+        for (int i = lane; i < D; i += 64) {
+            const int lo = max(0, i - Rv), hi = min(D + 1, i + Rv + 1);
+            ws.range[group * D + i] = make_int2(first + s_pos[lo], first + (hi + 1 < nbins ? s_pos[hi + 1] : L));
         }
         lds_sync();
         if (stop == 5) return;
@@ -539,13 +509,7 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
             }
             lds_sync();
         }
-        for (int q = lane; q < tiles; q += 64) {
-            TileInfo ti;
-            ti.r0 = first; ti.r1 = first + M;
-            ti.ox = cu.org[0]; ti.oy = cu.org[1]; ti.oz = cu.org[2];
-            ti.pad[0] = 0; ti.pad[1] = 0; ti.pad[2] = 0;
-            tinfo[q] = ti;
-        }
+        for (int i = lane; i < D; i += 64) ws.range[group * D + i] = make_int2(first, first + M);
         if (lane == 0) ws.meta[group] = make_int4(first, M, M, 0);
     }
 
@@ -564,12 +528,6 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
 
 size_t align16(size_t v) { return (v + 15) / 16 * 16; }
 
-size_t max_tiles(int D)
-{
-    const size_t total = (size_t)D * D * D;
-    return (total + kMinTileFloats - 1) / kMinTileFloats;
-}
-
 }  // namespace
 
 size_t workspace_bytes(int B, int N, int T, int D)
@@ -578,8 +536,7 @@ size_t workspace_bytes(int B, int N, int T, int D)
     size_t bytes = bn * sizeof(float4);                     // rec
     bytes += align16(bn * sizeof(int));                     // idx
     bytes += bt * sizeof(int4);                             // meta
-    bytes = (bytes + 31) / 32 * 32;
-    bytes += bt * max_tiles(D) * sizeof(TileInfo);          // tinfo (sized for the smallest tile)
+    bytes += align16(bt * (size_t)D * sizeof(int2));        // range
     bytes += (size_t)B * 12 * sizeof(float);                // rot
     return bytes;
 }
@@ -595,9 +552,8 @@ Workspace carve_workspace(void *base, int B, int N, int T, int D)
     p += align16(bn * sizeof(int));
     ws.meta = (int4 *)p;
     p += bt * sizeof(int4);
-    p = (char *)base + ((size_t)(p - (char *)base) + 31) / 32 * 32;
-    ws.tinfo = (TileInfo *)p;
-    p += bt * max_tiles(D) * sizeof(TileInfo);
+    ws.range = (int2 *)p;
+    p += align16(bt * (size_t)D * sizeof(int2));
     ws.rot = (float *)p;
     return ws;
 }
@@ -613,11 +569,10 @@ hipError_t launch_transform(int B, int N, const float *coords, const float *cent
 }
 
 int g_prep_stop = 0;
-hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws, int tile_floats,
-                       float *gclear, float *wclear, hipStream_t stream)
+hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws, float *gclear,
+                       float *wclear, hipStream_t stream)
 {
     const int stop = g_prep_stop;
-    const int tiles = forward_geometry(gs.D, tile_floats).tiles;
     const bool vec = bt.weights != nullptr;
     ExLayout L;
     L.Tg = vec ? 1 : bt.T;
@@ -628,18 +583,18 @@ hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
     if (K <= kExMaxKeys && bt.N <= kExMaxAtoms && lds_bytes <= 64 * 1024 && stop <= 1) {
         if (vec)
             hipLaunchKernelGGL(prep_example_kernel<true>, dim3(bt.B), dim3(kExThreads), lds_bytes,
-                               stream, gs, bt, ws, tile_floats, tiles, gclear, wclear, stop);
+                               stream, gs, bt, ws, gclear, wclear, stop);
         else
             hipLaunchKernelGGL(prep_example_kernel<false>, dim3(bt.B), dim3(kExThreads), lds_bytes,
-                               stream, gs, bt, ws, tile_floats, tiles, gclear, wclear, stop);
+                               stream, gs, bt, ws, gclear, wclear, stop);
         return hipGetLastError();
     }
     if (vec) {
         hipLaunchKernelGGL(prep_kernel<true>, dim3(1, bt.B), dim3(kPrepThreads), 0, stream, gs, bt,
-                           ws, tile_floats, tiles, gclear, wclear, stop);
+                           ws, gclear, wclear, stop);
     } else {
         hipLaunchKernelGGL(prep_kernel<false>, dim3(bt.T, bt.B), dim3(kPrepThreads), 0, stream, gs,
-                           bt, ws, tile_floats, tiles, gclear, wclear, stop);
+                           bt, ws, gclear, wclear, stop);
     }
     return hipGetLastError();
 }

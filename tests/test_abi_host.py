@@ -80,9 +80,7 @@ def test_calls_reject_bad_arguments_before_any_launch(L):
     assert rc == 0
     n = sz()
     assert L.mg_workspace_bytes(h, 50, 2040, 28, ctypes.byref(n)) == 0
-    # records + indices, group descriptors, one 32-byte entry per (channel, 4 KB of its grid), rotations
-    tiles = (48 ** 3 + 1023) // 1024
-    assert 50 * 2040 * 20 <= n.value <= 50 * 2040 * 20 + 50 * 28 * (16 + tiles * 32) + 50 * 48 + 64
+    assert 50 * 2040 * 20 <= n.value <= 50 * 2040 * 20 + 50 * 28 * (16 + 48 * 8) + 50 * 48 + 64
     assert L.mg_workspace_bytes(h, 0, 2040, 28, ctypes.byref(n)) == -2
     assert L.mg_workspace_bytes(h, 50, 2040, 28, None) == -1
     assert L.mg_workspace_bytes(None, 50, 2040, 28, ctypes.byref(n)) == -1

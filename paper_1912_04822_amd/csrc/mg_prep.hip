@@ -168,10 +168,10 @@ struct ExLayout {       // LDS, in ints
     __host__ __device__ int cnt() const { return 0; }
     __host__ __device__ int pos() const { return K; }
     __host__ __device__ int rmax() const { return 2 * K; }
-    __host__ __device__ int part() const { return 2 * K + Tg; }
-    __host__ __device__ int key() const { return 2 * K + Tg + 32; }             // ushort[N]
-    __host__ __device__ int slot() const { return key() + (N + 1) / 2; }        // ushort[N]
-    __host__ __device__ int order() const { return slot() + (N + 1) / 2; }      // ushort[N]
+    __host__ __device__ int rad() const { return 2 * K + Tg; }                  // float[Tg]
+    __host__ __device__ int part() const { return 2 * K + 2 * Tg; }
+    __host__ __device__ int key() const { return 2 * K + 2 * Tg + 32; }         // ushort[N]
+    __host__ __device__ int order() const { return key() + (N + 1) / 2; }       // ushort[N]
     __host__ __device__ int ints() const { return order() + (N + 1) / 2; }
 };
 
@@ -181,6 +181,7 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
                                                                   float *wclear, int stop)
 {
     extern __shared__ int s_mem[];
+    constexpr int kPer = kExMaxAtoms / kExThreads;      // atoms per thread, at most
     const int b = blockIdx.x, tid = threadIdx.x;
     const int N = bt.N, T = bt.T, D = gs.D;
     if (stop == 1) return;
@@ -192,17 +193,38 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     int *s_cnt = s_mem + L.cnt();
     int *s_pos = s_mem + L.pos();
     int *s_rmax = s_mem + L.rmax();
+    float *s_rad = reinterpret_cast<float *>(s_mem + L.rad());
     int *s_part = s_mem + L.part();
     unsigned short *s_key = reinterpret_cast<unsigned short *>(s_mem + L.key());
-    unsigned short *s_slot = reinterpret_cast<unsigned short *>(s_mem + L.slot());
     unsigned short *s_order = reinterpret_cast<unsigned short *>(s_mem + L.order());
 
+    // Everything this thread needs from HBM is requested before anything is waited for:
+    // its atoms (thread tid owns atoms tid, tid + 1024, ...), the radii table, the pose.
+    const int32_t *ty = VECTOR ? nullptr : bt.types + (size_t)b * N;
+    int my_t[kPer];
+    float my_c[kPer][3], my_r[kPer];
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+        const int a = tid + u * kExThreads;
+        my_t[u] = -1;
+        my_c[u][0] = 0.0f; my_c[u][1] = 0.0f; my_c[u][2] = 0.0f;
+        my_r[u] = 0.0f;
+        if (a < N) {
+            const size_t k = ((size_t)b * N + a) * 3;
+            my_t[u] = VECTOR ? 0 : ty[a];
+            my_c[u][0] = bt.coords[k];
+            my_c[u][1] = bt.coords[k + 1];
+            my_c[u][2] = bt.coords[k + 2];
+            if (!VECTOR && !gs.radius_type_indexed) my_r[u] = bt.radii[(size_t)b * N + a];
+        }
+    }
+    if (!VECTOR && gs.radius_type_indexed)
+        for (int k = tid; k < Tg; k += kExThreads) s_rad[k] = bt.radii[k];
     int n = N;
     if (bt.natoms) {
         n = bt.natoms[b];
         n = n < 0 ? 0 : (n > N ? N : n);
     }
-    const int32_t *ty = VECTOR ? nullptr : bt.types + (size_t)b * N;
     Xform X;
     load_xform(X, b, bt.centers, bt.quats, bt.translations);
     if (tid < 9) ws.rot[b * 12 + tid] = (float)X.R[tid];
@@ -219,37 +241,55 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     cu.span = (float)(D - 1) * gs.res;
     for (int m = 0; m < 3; ++m) cu.org[m] = (bt.centers ? bt.centers[3 * b + m] : 0.0f) - gs.half;
 
+    if (stop == 2) return;
     for (int k = tid; k < K; k += kExThreads) s_cnt[k] = 0;
     for (int k = tid; k < Tg; k += kExThreads) s_rmax[k] = 0;
     __syncthreads();
 
-    // ---- 1. key and rank inside its bin for every atom ----
-    for (int a = tid; a < N; a += kExThreads) {
-        int tg = 0;
-        bool member = a < n;
-        if (!VECTOR && member) {
-            tg = ty[a];
-            member = tg >= 0 && tg < T;
-        }
-        int key = 0xFFFF;
+    // ---- 1. key and a slot inside its bin for every atom ----
+    int my_key[kPer], my_slot[kPer];
+    float my_p[kPer][3], my_w[kPer];        // transformed position, radius (0: culled)
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+        const int a = tid + u * kExThreads;
+        my_key[u] = 0xFFFF;
+        my_slot[u] = 0;
+        my_w[u] = 0.0f;
+        my_p[u][0] = 0.0f; my_p[u][1] = 0.0f; my_p[u][2] = 0.0f;
+        if (a >= N) continue;
+        const int tg = my_t[u];
+        const bool member = a < n && tg >= 0 && tg < Tg;
         if (member) {
-            float p[3], r;
-            const bool live = place_atom<VECTOR>(gs, bt, X, cu, b, tg, a, vec_reach, p, &r);
+            apply_xform(X, my_c[u], my_p[u]);
+            float r, reach;
+            if (VECTOR) {
+                r = 1.0f;
+                reach = vec_reach;
+            } else {
+                r = gs.radius_scale * (gs.radius_type_indexed ? s_rad[tg] : my_r[u]);
+                reach = gs.binary ? r : r * gs.c;
+            }
+            bool live = (r > 0.0f) && (reach < 1.0e30f);
+            for (int k = 0; k < 3; ++k)     // also false for NaN / infinite coordinates
+                live = live && (my_p[u][k] >= cu.org[k] - reach - cu.pad) &&
+                       (my_p[u][k] <= cu.org[k] + cu.span + reach + cu.pad);
             int bin = D + 2;
             if (live) {
-                const float f = floorf((p[0] - cu.org[0]) * gs.inv_res);
+                const float f = floorf((my_p[u][0] - cu.org[0]) * gs.inv_res);
                 bin = f < 0.0f ? 0 : (f >= (float)D ? D + 1 : (int)f + 1);
                 atomicMax(&s_rmax[tg], __float_as_int(r));      // r > 0: ordered like ints
+                my_w[u] = r;
             }
-            key = tg * nb + bin;
-            s_slot[a] = (unsigned short)atomicAdd(&s_cnt[key], 1);
+            my_key[u] = tg * nb + bin;
+            my_slot[u] = atomicAdd(&s_cnt[my_key[u]], 1);
             if (!live) clear_grads(gclear, wclear, (size_t)b * N + a, T);
         } else {
             clear_grads(gclear, wclear, (size_t)b * N + a, T);   // no group owns this atom
         }
-        s_key[a] = (unsigned short)key;
+        s_key[a] = (unsigned short)my_key[u];
     }
     __syncthreads();
+    if (stop == 3) return;
 
     // ---- 2. exclusive scan of the counts ----
     const int chunk = (K + kExThreads - 1) / kExThreads;
@@ -275,38 +315,12 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
         run += s_cnt[k];
     }
     __syncthreads();
+    if (stop == 4) return;
 
-    // ---- 3. placement, then every live bin in atom order ----
-    for (int a = tid; a < N; a += kExThreads) {
-        const int key = s_key[a];
-        if (key != 0xFFFF) s_order[s_pos[key] + s_slot[a]] = (unsigned short)a;
-    }
-    __syncthreads();
-    for (int k = tid; k < K; k += kExThreads) {
-        const int bin = k - (k / nb) * nb;
-        if (bin == D + 2) continue;         // the order of culled atoms does not matter
-        const int lo = s_pos[k], hi = lo + s_cnt[k];
-        for (int i = lo + 1; i < hi; ++i) {
-            const unsigned short v = s_order[i];
-            int j = i - 1;
-            while (j >= lo && s_order[j] > v) {
-                s_order[j + 1] = s_order[j];
-                --j;
-            }
-            s_order[j + 1] = v;
-        }
-    }
-    __syncthreads();
-
-    // ---- 4. records, group descriptors, spans per plane ----
-    for (int pos = tid; pos < total; pos += kExThreads) {
-        const int a = s_order[pos];
-        const int tg = VECTOR ? 0 : ty[a];
-        float p[3], r;
-        const bool live = place_atom<VECTOR>(gs, bt, X, cu, b, tg, a, vec_reach, p, &r);
-        ws.rec[(size_t)b * N + pos] = make_float4(p[0], p[1], p[2], live ? r : 0.0f);
-        ws.idx[(size_t)b * N + pos] = a;
-    }
+    // ---- 3. atoms into their bins in any order; group descriptors and spans meanwhile ----
+#pragma unroll
+    for (int u = 0; u < kPer; ++u)
+        if (my_key[u] != 0xFFFF) s_order[s_pos[my_key[u]] + my_slot[u]] = (unsigned short)(tid + u * kExThreads);
     for (int tg = tid; tg < Tg; tg += kExThreads) {
         const int first = s_pos[tg * nb];
         const int dead = s_pos[tg * nb + D + 2];
@@ -321,6 +335,27 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
         const int Rv = (int)ceilf(rmax * gs.inv_res + cu.pad) + 1;
         const int lo = max(0, i - Rv), hi = min(D + 1, i + Rv + 1);
         ws.range[((size_t)b * T + tg) * D + i] = make_int2(s_pos[tg * nb + lo], s_pos[tg * nb + hi + 1]);
+    }
+    __syncthreads();
+    if (stop == 5) return;
+
+    // ---- 4. every atom writes its record where its rank inside the bin puts it ----
+    // (rank = how many atoms of the bin have a smaller index: the order in which the
+    // forward kernel sums is fixed; the order of culled atoms does not matter)
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+        const int key = my_key[u];
+        if (key == 0xFFFF) continue;
+        const int a = tid + u * kExThreads;
+        const int lo = s_pos[key];
+        int rank = my_slot[u];
+        if (key - (key / nb) * nb != D + 2) {
+            const int cnt = s_cnt[key];
+            rank = 0;
+            for (int i = 0; i < cnt; ++i) rank += s_order[lo + i] < a ? 1 : 0;
+        }
+        ws.rec[(size_t)b * N + lo + rank] = make_float4(my_p[u][0], my_p[u][1], my_p[u][2], my_w[u]);
+        ws.idx[(size_t)b * N + lo + rank] = a;
     }
 }
 
@@ -580,7 +615,7 @@ hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
     const long long K = (long long)L.Tg * (gs.D + 3);
     L.K = (int)(K <= kExMaxKeys ? K : 0);
     const size_t lds_bytes = (size_t)L.ints() * sizeof(int);
-    if (K <= kExMaxKeys && bt.N <= kExMaxAtoms && lds_bytes <= 64 * 1024 && stop <= 1) {
+    if (K <= kExMaxKeys && bt.N <= kExMaxAtoms && lds_bytes <= 64 * 1024) {
         if (vec)
             hipLaunchKernelGGL(prep_example_kernel<true>, dim3(bt.B), dim3(kExThreads), lds_bytes,
                                stream, gs, bt, ws, gclear, wclear, stop);

@@ -99,7 +99,10 @@ struct TileCtx {
     int nrows;                  // grid rows the tile touches
     int c0, c1;                 // first column of its first row, last column of its last row
     int rowA, rowB;             // tile row of row 0 of plane A / plane B (may be negative)
-    float res, inv_res, oy, oz;
+    float res, inv_res, oy, oz;     // oy, oz: grid origin (binary mode works from it)
+    float cen_x, cen_y, cen_z, hD;  // grid centre; (D-1)/2.  The real density works in
+                                    // coordinates relative to the centre: differences of
+                                    // nearby numbers, no rounding of an origin
     float g2k, c2k, sA, cA;
     int debug;
 };
@@ -156,7 +159,8 @@ struct Atom {
 // What a task needs of its atom; it stays in the registers of the atom's lane and the
 // task's lane fetches it with ds_bpermute (register exchange, no LDS storage).
 struct Cand {
-    float c0, c1, c2, c3;       // fy, fz, stepk, inv_stepk | w     (binary: y', z', r^2, reach^2)
+    float c0, c1, c2, c3;       // fy, fz (grid steps from the centre), stepk, inv_stepk | w
+                                // (binary: y', z', r^2, reach^2)
     float pxA, pxB;             // plane term of d^2 for plane A, plane B
     int start;                  // index of the atom's first task
     int pack;                   // jloA | nA << 10 | jloB << 20
@@ -215,15 +219,16 @@ __device__ inline void run_tasks(const TileCtx &cx, const Cand &cd, int ntasks)
             const float fy = p0.x, fz = p0.y, stepk = p0.z;
             const float w = p0.w;                                           // vector types
             const float inv_stepk = VECTOR ? __builtin_amdgcn_rcpf(stepk) : p0.w;
-            const float dyk = ((float)j - fy) * stepk;
+            const float dyk = (((float)j - cx.hD) - fy) * stepk;
             const float x2b = fmaf(dyk, dyk, px2);
             const float rem = cx.c2k - x2b;
             act = act && rem > 0.0f;
             const float hz = __builtin_amdgcn_sqrtf(fmaxf(rem, 0.0f)) * inv_stepk + 1.0e-3f;
-            const int klo = max(clip_lo, (int)ceilf(fz - hz));
-            const int khi = min(clip_hi, (int)floorf(fz + hz));
+            const float fzi = fz + cx.hD;                                   // as a grid index
+            const int klo = max(clip_lo, (int)ceilf(fzi - hz));
+            const int khi = min(clip_hi, (int)floorf(fzi + hz));
             const int nz = act ? khi - klo + 1 : 0;
-            const float z0 = ((float)klo - fz) * stepk;
+            const float z0 = (((float)klo - cx.hD) - fz) * stepk;
             float cA = cx.cA;
             asm volatile("" : "+v"(cA));        // keep it in a VGPR across the loop
             float fi = 0.0f;
@@ -253,20 +258,21 @@ __device__ inline void run_tasks(const TileCtx &cx, const Cand &cd, int ntasks)
 //   out: px2 = plane term of the squared distance (scaled units; binary: dx^2), rows [jlo, jlo+n)
 template <bool BINARY>
 __device__ inline int plane_rows(const TileCtx &cx, const FwdParams &p, const Atom &at, float gx,
-                                 int ja, int jb, float sks, float inv_stepk, float fy, float fz,
-                                 float &px2, int &jlo)
+                                 float xc, int ja, int jb, float sks, float inv_stepk, float fy,
+                                 float fz, float &px2, int &jlo)
 {
+    // gx: x of the plane; xc: the same relative to the grid centre; fy, fz: grid indices
     float hv;
     bool ok = at.valid && ja < jb;
-    const float dx = gx - at.a.x;
     if (BINARY) {
+        const float dx = gx - at.a.x;
         const float reach = at.a.w + 1.0e-3f * cx.res;
         px2 = dx * dx;
         const float h2 = reach * reach - px2;
         ok = ok && h2 > 0.0f;
         hv = __builtin_amdgcn_sqrtf(fmaxf(h2, 0.0f)) * cx.inv_res + 1.0e-3f;
     } else {
-        const float dxk = dx * sks;
+        const float dxk = (xc - (at.a.x - cx.cen_x)) * sks;
         px2 = dxk * dxk;
         const float h2 = cx.c2k - px2;
         ok = ok && h2 > 0.0f;
@@ -287,23 +293,27 @@ struct PairHit {
 
 // One atom per lane against the rows of planes A and B that belong to the tile.
 template <bool VECTOR, bool BINARY>
-__device__ inline PairHit pair_test(const TileCtx &cx, const FwdParams &p, const Atom &at, float gxA,
-                                    float gxB, int jaA, int jbA, int jaB, int jbB)
+__device__ inline PairHit pair_test(const TileCtx &cx, const FwdParams &p, const Atom &at, float ox,
+                                    int iA, int jaA, int jbA, int jaB, int jbB)
 {
     PairHit h;
     const float r = at.a.w;
     // per atom: position in grid steps, scale of its distances
-    const float fy = (at.a.y - cx.oy) * cx.inv_res;
-    const float fz = (at.a.z - cx.oz) * cx.inv_res;
+    const float fy = (at.a.y - cx.cen_y) * cx.inv_res;      // from the grid centre
+    const float fz = (at.a.z - cx.cen_z) * cx.inv_res;
+    const float fyi = BINARY ? (at.a.y - cx.oy) * cx.inv_res : fy + cx.hD;   // as grid indices
+    const float fzi = BINARY ? (at.a.z - cx.oz) * cx.inv_res : fz + cx.hD;
     const float sks = at.valid ? p.sk * __builtin_amdgcn_rcpf(r) : 0.0f;
     const float stepk = cx.res * sks;
     const float inv_stepk = r * cx.inv_res * p.inv_sk;
     int jloA, jloB = 0;
-    h.nA = plane_rows<BINARY>(cx, p, at, gxA, jaA, jbA, sks, inv_stepk, fy, fz, h.cd.pxA, jloA);
+    const float gxA = ox + (float)iA * cx.res, gxB = ox + (float)(iA + 1) * cx.res;
+    const float xcA = ((float)iA - cx.hD) * cx.res, xcB = ((float)(iA + 1) - cx.hD) * cx.res;
+    h.nA = plane_rows<BINARY>(cx, p, at, gxA, xcA, jaA, jbA, sks, inv_stepk, fyi, fzi, h.cd.pxA, jloA);
     h.nB = 0;
     h.cd.pxB = 0.0f;
     if (jaB < jbB)      // uniform: most tiles of small tile sizes lie in one plane
-        h.nB = plane_rows<BINARY>(cx, p, at, gxB, jaB, jbB, sks, inv_stepk, fy, fz, h.cd.pxB, jloB);
+        h.nB = plane_rows<BINARY>(cx, p, at, gxB, xcB, jaB, jbB, sks, inv_stepk, fyi, fzi, h.cd.pxB, jloB);
     if (cx.debug == 1) { h.nA = 0; h.nB = 0; }
     if (h.nA == 0) jloA = 0;        // both are packed into bit fields below
     if (h.nB == 0) jloB = 0;
@@ -481,9 +491,13 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     int r1 = span[i_hi].y;
     const float cen_x = cen[0], cen_y = cen[1], cen_z = cen[2];
     asm volatile("" ::"s"(r0), "s"(r1), "s"(cen_x), "s"(cen_y), "s"(cen_z));  // all in flight before the first wait
-    const float ox = (p.centers ? cen_x : 0.0f) - gs.half;
-    cx.oy = (p.centers ? cen_y : 0.0f) - gs.half;
-    cx.oz = (p.centers ? cen_z : 0.0f) - gs.half;
+    cx.cen_x = p.centers ? cen_x : 0.0f;
+    cx.cen_y = p.centers ? cen_y : 0.0f;
+    cx.cen_z = p.centers ? cen_z : 0.0f;
+    cx.hD = 0.5f * (float)(D - 1);
+    const float ox = cx.cen_x - gs.half;
+    cx.oy = cx.cen_y - gs.half;
+    cx.oz = cx.cen_z - gs.half;
     if (p.debug == 2) r1 = r0;
     const float r_chan = VECTOR ? gs.radius_scale * p.radii[t] : 0.0f;
 
@@ -517,8 +531,7 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
         cx.rowB = cx.rowA + D;
         const int jaA = max(-cx.rowA, 0), jbA = min(R1 - R0 - cx.rowA, D);
         const int jaB = max(-cx.rowB, 0), jbB = iA < i_hi ? min(R1 - R0 - cx.rowB, D) : 0;
-        return pair_test<VECTOR, BINARY>(cx, p, at, ox + (float)iA * gs.res,
-                                         ox + (float)(iA + 1) * gs.res, jaA, jbA, jaB, jbB);
+        return pair_test<VECTOR, BINARY>(cx, p, at, ox, iA, jaA, jbA, jaB, jbB);
     };
 
     // the loads of the first round are under way; clear the tile meanwhile

@@ -155,23 +155,28 @@ const char *mg_strerror(int code);
 int mg_last_hip_error(void);
 
 /*
- * Tuning knobs of the forward kernel, for measurement only (results do not
- * depend on them beyond rounding).  key "tile_floats" (512, 1024, 2048 or 4096,
- * default 2048): consecutive output floats one wavefront produces; key "debug"
- * (0..3): 0 = normal, 1 = no density evaluation, 2 = no atoms, 3 = stores only
- * (the output is then wrong: for timing the parts of the kernel); key
- * "lds_pad" (0..40000): extra LDS bytes per workgroup, lowers residency; key
- * "prep_stop" (0..6): end the prep kernel after that stage (wrong output).
+ * Tuning knobs, for measurement only (results do not depend on them beyond
+ * rounding).  Process-wide; not meant to be changed while calls are in flight.
+ *   "tile_floats"     1024 or 2048 (default 2048): consecutive output floats one
+ *                     forward workgroup produces
+ *   "waves_per_tile"  1, 2 or 4 (default 1): wavefronts in that workgroup
+ *   "xcd_run"         0 or a power of two (default 0): runs of this many
+ *                     consecutive tiles go to one XCD
+ *   "lds_floor"       -1..65536 (default -1 = none): least LDS bytes a forward
+ *                     workgroup requests; caps how many are resident on a CU
+ *   "debug"           0..3: 0 = normal, 1 = no density evaluation, 2 = no atoms,
+ *                     3 = stores only (output then wrong: times parts of the kernel)
+ *   "prep_stop"       0..6: end the prep kernel after that stage (output wrong)
  * Returns MG_EPARAM for an unknown key or value.
  */
 int mg_set_option(const char *key, int value);
 
 /*
- * Measurement hook: the next forward or backward call made by this thread
- * records `start` just before and `stop` just after its main kernel (the
- * forward gather / the backward reduction; not the prep kernel) on the call's
- * stream.  Both are hipEvent_t handles created by the caller with timing
- * enabled; the hook is cleared by that call.  Pass NULL, NULL to clear it.
+ * Measurement hook: the next forward or backward call made by this thread has
+ * `start` stamped when its main kernel (the forward gather / the backward
+ * reduction; not the prep kernel) begins and `stop` when it ends.  Both are
+ * hipEvent_t handles created by the caller with timing enabled; the hook is
+ * cleared by the call that launches.  Pass NULL, NULL to clear it.
  */
 int mg_time_next_kernel(void *start_event, void *stop_event);
 

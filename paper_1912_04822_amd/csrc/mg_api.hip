@@ -24,17 +24,13 @@ int g_xcd_run = 0;
 int g_lds_floor = -1;     // < 0: chosen by the launcher
 int g_debug = 0;
 
-// Runs `launch` (the main kernel of a call) between the caller's timing events, if set.
-template <class F>
-hipError_t timed(hipStream_t stream, F launch)
+// The caller's timing events for the main kernel of this call, if set (cleared by the call).
+mg::KernelEvents take_events()
 {
-    hipEvent_t e0 = g_ev_start, e1 = g_ev_stop;
+    mg::KernelEvents ev = {g_ev_start, g_ev_stop};
     g_ev_start = nullptr;
     g_ev_stop = nullptr;
-    if (e0) (void)hipEventRecord(e0, stream);
-    const hipError_t rc = launch();
-    if (e1) (void)hipEventRecord(e1, stream);
-    return rc;
+    return ev;
 }
 
 bool finite_pos(float v) { return std::isfinite(v) && v > 0.0f; }
@@ -164,11 +160,9 @@ int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T, const float *c
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
-    return hip_status(timed((hipStream_t)stream, [&] {
-        return mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_waves_per_tile, g_xcd_run,
-                                  g_lds_floor, g_debug,
-                                  (hipStream_t)stream);
-    }));
+    return hip_status(mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_waves_per_tile,
+                                         g_xcd_run, g_lds_floor, g_debug, take_events(),
+                                         (hipStream_t)stream));
 }
 
 int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
@@ -191,11 +185,9 @@ int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
-    return hip_status(timed((hipStream_t)stream, [&] {
-        return mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_waves_per_tile, g_xcd_run,
-                                  g_lds_floor, g_debug,
-                                  (hipStream_t)stream);
-    }));
+    return hip_status(mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_waves_per_tile,
+                                         g_xcd_run, g_lds_floor, g_debug, take_events(),
+                                         (hipStream_t)stream));
 }
 
 int mg_backward_index(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
@@ -219,10 +211,8 @@ int mg_backward_index(const mg_gridmaker *gm, int B, int N, int T, const float *
     const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
-    return hip_status(timed((hipStream_t)stream, [&] {
-        return mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, nullptr,
-                                   (hipStream_t)stream);
-    }));
+    return hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, nullptr,
+                                          take_events(), (hipStream_t)stream));
 }
 
 int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
@@ -249,10 +239,8 @@ int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T, const float 
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, grad_weights,
                                     (hipStream_t)stream));
     if (rc != MG_OK) return rc;
-    return hip_status(timed((hipStream_t)stream, [&] {
-        return mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, grad_weights,
-                                   (hipStream_t)stream);
-    }));
+    return hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, grad_weights,
+                                          take_events(), (hipStream_t)stream));
 }
 
 const char *mg_strerror(int code)

@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
 
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                            const float *grad_out, float *grad_coords, float *grad_weights,
-                           hipStream_t stream)
+                           KernelEvents ev, hipStream_t stream)
 {
     BwdParams p;
     p.gs = gs;
@@ -206,11 +206,11 @@ hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace 
     const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)grad_out & 15u) == 0);
     const dim3 grd(bt.N, bt.B), blk(256);
     if (bt.weights) {
-        if (aligned) hipLaunchKernelGGL((backward_kernel<true, true>), grd, blk, 0, stream, p);
-        else hipLaunchKernelGGL((backward_kernel<true, false>), grd, blk, 0, stream, p);
+        if (aligned) hipExtLaunchKernelGGL((backward_kernel<true, true>), grd, blk, 0, stream, ev.start, ev.stop, 0, p);
+        else hipExtLaunchKernelGGL((backward_kernel<true, false>), grd, blk, 0, stream, ev.start, ev.stop, 0, p);
     } else {
-        if (aligned) hipLaunchKernelGGL((backward_kernel<false, true>), grd, blk, 0, stream, p);
-        else hipLaunchKernelGGL((backward_kernel<false, false>), grd, blk, 0, stream, p);
+        if (aligned) hipExtLaunchKernelGGL((backward_kernel<false, true>), grd, blk, 0, stream, ev.start, ev.stop, 0, p);
+        else hipExtLaunchKernelGGL((backward_kernel<false, false>), grd, blk, 0, stream, ev.start, ev.stop, 0, p);
     }
     return hipGetLastError();
 }

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -91,6 +92,13 @@ ForwardGeometry forward_geometry(int D, int tile_floats);
 
 constexpr int kSortCap = 2048;          // longest group the prep kernel bins by x-plane
 
+// Timing events for the main kernel of the current call (null: none).  The launchers pass
+// them to hipExtLaunchKernelGGL, which stamps them at the start and the end of that very
+// kernel.
+struct KernelEvents {
+    hipEvent_t start, stop;
+};
+
 extern int g_prep_stop;                 // timing aid: stop the prep kernel after a stage
 
 // Launchers (each enqueues on `stream`, returns the hipError_t of the launch).
@@ -102,9 +110,9 @@ hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                        hipStream_t stream);
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                           float *out, int tile_floats, int waves_per_tile, int xcd_run,
-                          int lds_floor, int debug, hipStream_t stream);
+                          int lds_floor, int debug, KernelEvents ev, hipStream_t stream);
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                            const float *grad_out, float *grad_coords, float *grad_weights,
-                           hipStream_t stream);
+                           KernelEvents ev, hipStream_t stream);
 
 }  // namespace mg

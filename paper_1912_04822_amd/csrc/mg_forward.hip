@@ -565,7 +565,7 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
             }
         }
     }
-    __syncthreads();                                // tile and shared[0] are ready
+    if (NW > 1) __syncthreads();                    // tile and shared[0] are ready
     const bool fixed = !BINARY && cx.shared[0] <= (int)(kFixedLimit * 256.0f);
     // pass 2: the tasks
     if (single) {
@@ -579,7 +579,7 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
             }
         }
     }
-    __syncthreads();                                // every wavefront's additions are in the tile
+    if (NW > 1) __syncthreads();                    // every wavefront's additions are in the tile
     store_tile<ALIGNED, ITERS, NW>(cx, dst, cx.shared[1] != 0, fixed);
 }
 
@@ -606,7 +606,7 @@ unsigned long long magic64(unsigned d)      // ceil(2^64 / d); 0 stands for d ==
 
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws, float *out,
                           int tile_floats, int waves_per_tile, int xcd_run, int lds_floor,
-                          int debug, hipStream_t stream)
+                          int debug, KernelEvents ev, hipStream_t stream)
 {
     const ForwardGeometry fg = forward_geometry(gs.D, tile_floats);
     FwdParams p;
@@ -652,7 +652,8 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     const bool vec = bt.weights != nullptr;
     const dim3 blk(64 * nw), grd((unsigned)groups);
 #define MG_LAUNCH5(V, Bn, Al, It, Nw) \
-    hipLaunchKernelGGL((forward_kernel<V, Bn, Al, It, Nw>), grd, blk, lds_bytes, stream, p)
+    hipExtLaunchKernelGGL((forward_kernel<V, Bn, Al, It, Nw>), grd, blk, (uint32_t)lds_bytes, stream, \
+                          ev.start, ev.stop, 0, p)
 #define MG_LAUNCH(V, Bn, Al)                                                    \
     switch (iters * 8 + nw) {                                                   \
     case 2 * 8 + 1: MG_LAUNCH5(V, Bn, Al, 2, 1); break;                         \

@@ -9,12 +9,12 @@
 // d = 0 contribute exactly 0 through u = 0).  The gradient with respect to the
 // caller's coordinates is R^T times that sum.
 //
-// One workgroup (4 wavefronts) per atom record: the 256 lanes spread over the
-// atom's cutoff box (x-planes x rows x 4-voxel z-segments), read the upstream
-// gradient with 16-byte loads, and the three partial sums are reduced with
-// wavefront shuffles, then across the wavefronts through LDS, in a fixed order.
-// Records are grouped by channel (and, within a channel, keep atom order), so
-// neighbouring workgroups read the same channel volume.
+// One wavefront per atom record (four records per workgroup, no barrier): the
+// 64 lanes spread over the atom's cutoff box (x-planes x rows x 4-voxel
+// z-segments), read the upstream gradient with 16-byte loads, and the three
+// partial sums are reduced with wavefront shuffles in a fixed order.  Records
+// are grouped by channel (and, within a channel, by x-plane), so neighbouring
+// wavefronts read the same part of the same channel volume.
 #include "mg_common.h"
 
 namespace mg {
@@ -77,7 +77,7 @@ __device__ inline void reduce_channel(const BwdParams &p, const float *Gc, const
     const int per_plane = bx.nr * bx.ns;
     const int slots = bx.np * per_plane;
     const float inv_pp = 1.0f / (float)per_plane, inv_ns = 1.0f / (float)bx.ns;
-    for (int s = threadIdx.x; s < slots; s += blockDim.x) {
+    for (int s = (int)(threadIdx.x & 63u); s < slots; s += 64) {
         const int pi = (int)(((float)s + 0.5f) * inv_pp);
         const int rem = s - pi * per_plane;
         const int row = (int)(((float)rem + 0.5f) * inv_ns);
@@ -119,26 +119,15 @@ __device__ inline void reduce_channel(const BwdParams &p, const float *Gc, const
     }
 }
 
-// Sum v over the block; the result is valid in thread 0.  s_part: [4] floats.
-__device__ inline float block_sum(float v, float *s_part)
-{
-    v = wave_sum(v);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    __syncthreads();
-    if (lane == 0) s_part[wave] = v;
-    __syncthreads();
-    return ((s_part[0] + s_part[1]) + s_part[2]) + s_part[3];
-}
-
 template <bool VECTOR, bool ALIGNED>
 __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
 {
-    __shared__ float s_part[4];
     const GridSpec &gs = p.gs;
-    const int b = blockIdx.y, slot = blockIdx.x;
+    const int b = blockIdx.y, slot = (int)(blockIdx.x * 4u + (threadIdx.x >> 6));
+    const int lane = (int)(threadIdx.x & 63u);
     const int N = p.N, T = p.T, D = gs.D;
     const int4 last = p.meta[(size_t)b * T + (VECTOR ? 0 : T - 1)];
-    if (slot >= last.x + last.z) return;            // past the last group's slots (uniform)
+    if (slot >= last.x + last.z) return;            // past the last group's slots (per wavefront)
     const float4 a = p.rec[(size_t)b * N + slot];
     if (!(a.w > 0.0f)) return;                      // dead record: the prep kernel wrote its zeros
     const int ai = p.idx[(size_t)b * N + slot];
@@ -157,9 +146,9 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
             reduce_channel<ALIGNED, false>(p, p.G + ((size_t)b * T + t) * D3, a, 1.0f / (r * r), bx, ox,
                                            oy, oz, sx, sy, sz, sv);
         const float inv_r2 = 1.0f / (r * r);
-        tx = block_sum(sx, s_part) * inv_r2;
-        ty = block_sum(sy, s_part) * inv_r2;
-        tz = block_sum(sz, s_part) * inv_r2;
+        tx = wave_sum(sx) * inv_r2;
+        ty = wave_sum(sy) * inv_r2;
+        tz = wave_sum(sz) * inv_r2;
     } else {
         for (int t = 0; t < T; ++t) {
             const float r = gs.radius_scale * p.radii[t];
@@ -171,17 +160,17 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
                                               ox, oy, oz, sx, sy, sz, sv);
             const float inv_r2 = r > 0.0f ? 1.0f / (r * r) : 0.0f;
             if (p.grad_coords) {
-                tx = fmaf(w * inv_r2, block_sum(sx, s_part), tx);
-                ty = fmaf(w * inv_r2, block_sum(sy, s_part), ty);
-                tz = fmaf(w * inv_r2, block_sum(sz, s_part), tz);
+                tx = fmaf(w * inv_r2, wave_sum(sx), tx);
+                ty = fmaf(w * inv_r2, wave_sum(sy), ty);
+                tz = fmaf(w * inv_r2, wave_sum(sz), tz);
             }
             if (p.grad_weights) {
-                const float val = block_sum(sv, s_part);
-                if (threadIdx.x == 0) p.grad_weights[((size_t)b * N + ai) * T + t] = val;
+                const float val = wave_sum(sv);
+                if (lane == 0) p.grad_weights[((size_t)b * N + ai) * T + t] = val;
             }
         }
     }
-    if (threadIdx.x == 0 && p.grad_coords) {
+    if (lane == 0 && p.grad_coords) {
         const float *R = p.rot + b * 12;
         float *o = p.grad_coords + ((size_t)b * N + ai) * 3;
         o[0] = (R[0] * tx + R[3] * ty) + R[6] * tz;
@@ -204,7 +193,7 @@ hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace 
     p.B = bt.B; p.N = bt.N; p.T = bt.T;
     p.kexp = -2.8853900817779268f;
     const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)grad_out & 15u) == 0);
-    const dim3 grd(bt.N, bt.B), blk(256);
+    const dim3 grd((bt.N + 3) / 4, bt.B), blk(256);
     if (bt.weights) {
         if (aligned) hipExtLaunchKernelGGL((backward_kernel<true, true>), grd, blk, 0, stream, ev.start, ev.stop, 0, p);
         else hipExtLaunchKernelGGL((backward_kernel<true, false>), grd, blk, 0, stream, ev.start, ev.stop, 0, p);

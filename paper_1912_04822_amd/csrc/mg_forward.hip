@@ -344,12 +344,12 @@ __device__ inline int pair_bound(const PairHit &h, const Atom &at)
 
 // Stage the tasks of the hits (rows of plane A, then rows of plane B, atom after atom)
 // and run them.
+// Returns whether there was any task.
 template <bool VECTOR, bool BINARY>
-__device__ inline void pair_run(const TileCtx &cx, PairHit &h, bool fixed)
+__device__ inline bool pair_run(const TileCtx &cx, PairHit &h, bool fixed)
 {
     int todo = h.nA + h.nB;         // lanes still to be staged have todo > 0
-    if (__ballot(todo > 0) == 0ull) return;
-    if (cx.lane == 0) cx.shared[1] = 1;
+    if (__ballot(todo > 0) == 0ull) return false;
     while (true) {
         const int incl = wave_inclusive_scan(todo);
         int total = bcast(incl, 63);
@@ -371,6 +371,7 @@ __device__ inline void pair_run(const TileCtx &cx, PairHit &h, bool fixed)
         if (fixed) run_tasks<VECTOR, BINARY, true>(cx, h.cd, total);
         else run_tasks<VECTOR, BINARY, false>(cx, h.cd, total);
     }
+    return true;
 }
 
 // Stream the finished tile to HBM (zeros if no atom touched it).  ITERS = tile_floats / 512
@@ -391,28 +392,28 @@ __device__ inline void store_tile(const TileCtx &cx, float *dst, bool touched, b
 #pragma unroll
             for (int it = 0; it < 2 * MINE; ++it)
                 v[it] = src4[((it >> 1) * NW + cx.wave) * 128 + cx.lane * 2 + (it & 1)];
-            if (fixed) {
-#pragma unroll
-                for (int it = 0; it < 2 * MINE; ++it) {
-                    const float sc = 1.0f / kFixedOne;
-                    v[it] = make_float4((float)__float_as_int(v[it].x) * sc,
-                                        (float)__float_as_int(v[it].y) * sc,
-                                        (float)__float_as_int(v[it].z) * sc,
-                                        (float)__float_as_int(v[it].w) * sc);
-                }
-            }
         } else {
 #pragma unroll
             for (int it = 0; it < 2 * MINE; ++it) v[it] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         }
-        // the two 16-byte halves of a lane's 32 bytes go out back to back, under one
-        // predicate: separated by other instructions they are markedly slower
+        const bool convert = touched && fixed;
+        // chunk after chunk: convert its two float4s, then the two 16-byte halves of a lane's
+        // 32 bytes go out back to back, under one predicate (separated by other instructions
+        // they are markedly slower); the first stores leave while later chunks are converted
 #pragma unroll
         for (int it = 0; it < MINE; ++it) {
+            float4 a = v[2 * it], b = v[2 * it + 1];
+            if (convert) {
+                const float sc = 1.0f / kFixedOne;
+                a = make_float4((float)__float_as_int(a.x) * sc, (float)__float_as_int(a.y) * sc,
+                                (float)__float_as_int(a.z) * sc, (float)__float_as_int(a.w) * sc);
+                b = make_float4((float)__float_as_int(b.x) * sc, (float)__float_as_int(b.y) * sc,
+                                (float)__float_as_int(b.z) * sc, (float)__float_as_int(b.w) * sc);
+            }
             const int o = (it * NW + cx.wave) * 128 + cx.lane * 2;
             if (o < n4) {
-                dst4[o] = v[2 * it];
-                dst4[o + 1] = v[2 * it + 1];
+                dst4[o] = a;
+                dst4[o + 1] = b;
             }
         }
     } else {
@@ -544,43 +545,49 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
         if (threadIdx.x < 2) cx.shared[threadIdx.x] = 0;
     }
     const bool single = count <= 64 * NW && i_hi - i_lo <= 1;      // one round, one pair of planes
+    const int limit = (int)(kFixedLimit * 256.0f);
     PairHit h0;
     if (NW > 1) __syncthreads();                    // shared[] is clear
-    // pass 1: what can be added to one voxel at most decides fixed point or float
+    // pass 1: what can be added to one voxel at most decides fixed point or float (one
+    // wavefront keeps the bound in a register, several add theirs up in LDS)
+    int bound = 0;
     if (single) {
         h0 = test_pair(at0, i_lo);
-        if (!BINARY) {
-            const int bnd = pair_bound<VECTOR>(h0, at0);
-            if (lane == 0 && bnd > 0) atomicAdd(&cx.shared[0], bnd);
-        }
+        if (!BINARY) bound = pair_bound<VECTOR>(h0, at0);
     } else if (!BINARY) {
-        for (int base = 0; base < count; base += 64 * NW) {
+        for (int base = 0; base < count && bound <= limit; base += 64 * NW) {
             const Atom at = base == 0 ? at0 : load_atom(base);
             for (int iA = i_lo; iA <= i_hi; iA += 2) {
                 const PairHit h = test_pair(at, iA);
-                const int bnd = pair_bound<VECTOR>(h, at);
-                // once past the limit the exact value does not matter (and must not overflow)
-                if (lane == 0 && bnd > 0 && cx.shared[0] <= (int)(kFixedLimit * 256.0f))
-                    atomicAdd(&cx.shared[0], min(bnd, 1 << 24));
+                bound += min(pair_bound<VECTOR>(h, at), 1 << 24);   // past the limit the value does not matter
             }
         }
     }
-    if (NW > 1) __syncthreads();                    // tile and shared[0] are ready
-    const bool fixed = !BINARY && cx.shared[0] <= (int)(kFixedLimit * 256.0f);
+    if (NW > 1) {
+        if (lane == 0 && bound > 0) atomicAdd(&cx.shared[0], min(bound, 1 << 24));
+        __syncthreads();                            // tile and shared[0] are ready
+        bound = cx.shared[0];
+    }
+    const bool fixed = !BINARY && bound <= limit;
     // pass 2: the tasks
+    bool any = false;
     if (single) {
-        pair_run<VECTOR, BINARY>(cx, h0, fixed);
+        any = pair_run<VECTOR, BINARY>(cx, h0, fixed);
     } else {
         for (int base = 0; base < count; base += 64 * NW) {
             const Atom at = base == 0 ? at0 : load_atom(base);
             for (int iA = i_lo; iA <= i_hi; iA += 2) {
                 PairHit h = test_pair(at, iA);
-                pair_run<VECTOR, BINARY>(cx, h, fixed);
+                any = pair_run<VECTOR, BINARY>(cx, h, fixed) || any;
             }
         }
     }
-    if (NW > 1) __syncthreads();                    // every wavefront's additions are in the tile
-    store_tile<ALIGNED, ITERS, NW>(cx, dst, cx.shared[1] != 0, fixed);
+    if (NW > 1) {
+        if (any && lane == 0) cx.shared[1] = 1;
+        __syncthreads();                            // every wavefront's additions are in the tile
+        any = cx.shared[1] != 0;
+    }
+    store_tile<ALIGNED, ITERS, NW>(cx, dst, any, fixed);
 }
 
 }  // namespace

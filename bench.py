@@ -99,8 +99,9 @@ def time_call(torch, molgrid, fn, steps, warmup):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=150,
+                    help="untimed steps first; the chip needs ~10 ms of work (~80 steps) to reach its steady clocks")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--rows", action="store_true", help="also time vector/binary/backward rows")
     ap.add_argument("--tile-floats", type=int, default=None, help="forward kernel tuning knob")

@@ -105,6 +105,29 @@ def test_forward_ragged_small_unaligned_grid(mg, grm, scale):
     assert got[2].max() == 0.0
 
 
+@pytest.mark.parametrize("single_type", [False, True])
+def test_forward_backward_many_atoms_per_example(mg, single_type):
+    """N = 5000 is past what the one-workgroup-per-example prep kernel takes (the per-group
+    kernel runs instead); with every atom of one type the group is also too long for that
+    kernel to bin by x-plane (records stay in atom order)."""
+    w = workloads.ragged_small(seed=11, B=2, N=5000, T=3, D=16, resolution=0.5)
+    if single_type:
+        w.types[:] = 1
+    nat = np.array([5000, 4321], np.int32)
+    got = run_forward_index(mg, w, natoms=nat)
+    ref = oracle_forward_index(w, natoms=nat)
+    # dozens of atoms overlap in every voxel: float accumulation, error relative to the sums
+    assert np.abs(got - ref).max() <= GRID_TOL + 2e-6 * ref.max()
+    gotb = run_forward_index(mg, w, natoms=nat, binary=True)
+    refb = oracle_forward_index(w, natoms=nat, binary=True)
+    assert np.array_equal(gotb.view(np.uint32), refb.astype(np.float32).view(np.uint32))
+    gb = run_backward_index(mg, w, natoms=nat)
+    rb = oracle.backward_index(w.coords, w.types, w.radii, w.T, w.resolution, w.dimension,
+                               w.grad_out, natoms=nat, centers=w.centers, quats=w.quats,
+                               translations=w.translations)
+    assert grad_err(gb, rb) <= GRAD_RTOL
+
+
 @pytest.mark.parametrize("D,res", [(1, 1.0), (4, 0.5), (7, 0.3), (50, 0.5), (130, 0.125)])
 def test_forward_odd_grid_sizes(mg, D, res):
     w = workloads.ragged_small(seed=D, B=2, N=50, T=3, D=D, resolution=res)

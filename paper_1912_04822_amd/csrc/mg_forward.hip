@@ -438,7 +438,18 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const GridSpec &gs = p.gs;
     const int D = gs.D, T = p.T, N = p.N;
-    unsigned u = blockIdx.x;
+    // Every kernel argument the preamble needs is fetched now, in one go, instead of in five
+    // dependent trips to the scalar cache spread over the preamble: they are inputs of an
+    // asm statement whose result (zero) enters the very first computation.  (Not `asm
+    // volatile`: after one, the compiler no longer uses scalar loads for the spans.)
+    unsigned zero;
+    asm("s_mov_b32 %0, 0"
+        : "=s"(zero)
+        : "s"((unsigned long long)p.range), "s"((unsigned long long)p.rec),
+          "s"((unsigned long long)p.centers), "s"((unsigned long long)p.out), "s"(p.tiles_magic),
+          "s"(p.t_magic), "s"(p.div_magic), "s"(p.tiles), "s"(p.xcd_shift), "s"(p.n_remap), "s"(D),
+          "s"(T), "s"(N), "s"(p.debug), "s"(gs.half));
+    unsigned u = blockIdx.x + zero;
     if (p.xcd_shift >= 0 && u < p.n_remap) {
         const unsigned xcd = u & 7u, slot = u >> 3, sh = (unsigned)p.xcd_shift;
         u = ((slot >> sh) << (sh + 3)) + (xcd << sh) + (slot & ((1u << sh) - 1u));

@@ -45,13 +45,22 @@ struct Xform {
 __device__ inline void load_xform(Xform &X, int b, const float *centers, const float *quats,
                                   const float *translations)
 {
-    double w = 1.0, x = 0.0, y = 0.0, z = 0.0;
-    if (quats) {
-        w = (double)quats[4 * b + 0];
-        x = (double)quats[4 * b + 1];
-        y = (double)quats[4 * b + 2];
-        z = (double)quats[4 * b + 3];
+    // the ten floats of the pose are requested together (absent arrays read a dummy that is
+    // there, then take their default): one trip to memory instead of up to ten
+    const float *any = quats ? quats : (centers ? centers : translations);
+    const float *q4 = quats ? quats + 4 * b : any;
+    const float *c3 = centers ? centers + 3 * b : any;
+    const float *t3 = translations ? translations + 3 * b : any;
+    float qv[4] = {1.0f, 0.0f, 0.0f, 0.0f}, cv[3] = {0.0f, 0.0f, 0.0f}, tv[3] = {0.0f, 0.0f, 0.0f};
+    if (any) {
+        for (int m = 0; m < 4; ++m) qv[m] = q4[quats ? m : 0];
+        for (int m = 0; m < 3; ++m) cv[m] = c3[centers ? m : 0];
+        for (int m = 0; m < 3; ++m) tv[m] = t3[translations ? m : 0];
+        asm volatile("" ::"s"(qv[0]), "s"(qv[1]), "s"(qv[2]), "s"(qv[3]), "s"(cv[0]), "s"(cv[1]),
+                     "s"(cv[2]), "s"(tv[0]), "s"(tv[1]), "s"(tv[2]));
     }
+    const double w = quats ? (double)qv[0] : 1.0, x = quats ? (double)qv[1] : 0.0,
+                 y = quats ? (double)qv[2] : 0.0, z = quats ? (double)qv[3] : 0.0;
     const double n = ((w * w + x * x) + y * y) + z * z;
     if (!(n > 0.0) || !(n < 1.0e300)) {
         X.R[0] = 1.0; X.R[1] = 0.0; X.R[2] = 0.0;
@@ -68,8 +77,8 @@ __device__ inline void load_xform(Xform &X, int b, const float *centers, const f
         X.R[6] = xz - wy;         X.R[7] = yz + wx;         X.R[8] = 1.0 - (xx + yy);
     }
     for (int m = 0; m < 3; ++m) {
-        X.c[m] = centers ? (double)centers[3 * b + m] : 0.0;
-        X.t[m] = translations ? (double)translations[3 * b + m] : 0.0;
+        X.c[m] = centers ? (double)cv[m] : 0.0;
+        X.t[m] = translations ? (double)tv[m] : 0.0;
     }
 }
 
@@ -201,6 +210,8 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     // Everything this thread needs from HBM is requested before anything is waited for:
     // its atoms (thread tid owns atoms tid, tid + 1024, ...), the radii table, the pose.
     const int32_t *ty = VECTOR ? nullptr : bt.types + (size_t)b * N;
+    const float *crd = bt.coords + (size_t)b * N * 3;           // 32-bit offsets from here on
+    const float *rad_b = bt.radii + ((!VECTOR && !gs.radius_type_indexed) ? (size_t)b * N : 0);
     int my_t[kPer];
     float my_c[kPer][3], my_r[kPer];
 #pragma unroll
@@ -210,16 +221,13 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
         my_c[u][0] = 0.0f; my_c[u][1] = 0.0f; my_c[u][2] = 0.0f;
         my_r[u] = 0.0f;
         if (a < N) {
-            const size_t k = ((size_t)b * N + a) * 3;
             my_t[u] = VECTOR ? 0 : ty[a];
-            my_c[u][0] = bt.coords[k];
-            my_c[u][1] = bt.coords[k + 1];
-            my_c[u][2] = bt.coords[k + 2];
-            if (!VECTOR && !gs.radius_type_indexed) my_r[u] = bt.radii[(size_t)b * N + a];
+            my_c[u][0] = crd[a * 3];
+            my_c[u][1] = crd[a * 3 + 1];
+            my_c[u][2] = crd[a * 3 + 2];
+            if (!VECTOR && !gs.radius_type_indexed) my_r[u] = rad_b[a];
         }
     }
-    if (!VECTOR && gs.radius_type_indexed)
-        for (int k = tid; k < Tg; k += kExThreads) s_rad[k] = bt.radii[k];
     int n = N;
     if (bt.natoms) {
         n = bt.natoms[b];
@@ -241,6 +249,8 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     cu.span = (float)(D - 1) * gs.res;
     for (int m = 0; m < 3; ++m) cu.org[m] = (bt.centers ? bt.centers[3 * b + m] : 0.0f) - gs.half;
 
+    if (!VECTOR && gs.radius_type_indexed)
+        for (int k = tid; k < Tg; k += kExThreads) s_rad[k] = bt.radii[k];
     if (stop == 2) return;
     for (int k = tid; k < K; k += kExThreads) s_cnt[k] = 0;
     for (int k = tid; k < Tg; k += kExThreads) s_rmax[k] = 0;

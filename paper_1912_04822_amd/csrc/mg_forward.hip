@@ -557,46 +557,73 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     }
     const bool single = count <= 64 * NW && i_hi - i_lo <= 1;      // one round, one pair of planes
     const int limit = (int)(kFixedLimit * 256.0f);
-    PairHit h0;
-    if (NW > 1) __syncthreads();                    // shared[] is clear
-    // pass 1: what can be added to one voxel at most decides fixed point or float (one
-    // wavefront keeps the bound in a register, several add theirs up in LDS)
-    int bound = 0;
-    if (single) {
-        h0 = test_pair(at0, i_lo);
-        if (!BINARY) bound = pair_bound<VECTOR>(h0, at0);
-    } else if (!BINARY) {
-        for (int base = 0; base < count && bound <= limit; base += 64 * NW) {
-            const Atom at = base == 0 ? at0 : load_atom(base);
-            for (int iA = i_lo; iA <= i_hi; iA += 2) {
-                const PairHit h = test_pair(at, iA);
-                bound += min(pair_bound<VECTOR>(h, at), 1 << 24);   // past the limit the value does not matter
-            }
-        }
-    }
-    if (NW > 1) {
-        if (lane == 0 && bound > 0) atomicAdd(&cx.shared[0], min(bound, 1 << 24));
-        __syncthreads();                            // tile and shared[0] are ready
-        bound = cx.shared[0];
-    }
-    const bool fixed = !BINARY && bound <= limit;
-    // pass 2: the tasks
-    bool any = false;
-    if (single) {
-        any = pair_run<VECTOR, BINARY>(cx, h0, fixed);
-    } else {
-        for (int base = 0; base < count; base += 64 * NW) {
-            const Atom at = base == 0 ? at0 : load_atom(base);
+    bool any = false, fixed = !BINARY;
+    if (NW == 1 && !single) {
+        // One wavefront, several rounds: a single pass.  The tile starts in fixed point and
+        // the bound on what can reach one voxel is kept up round by round; the moment it
+        // passes the limit, the tile is turned into floats and stays so.  The records of
+        // the next round are requested before this round's tasks run.
+        int bound = 0;
+        Atom at = at0;
+        for (int base = 0; base < count; base += 64) {
+            Atom next = at;
+            if (base + 64 < count) next = load_atom(base + 64);
             for (int iA = i_lo; iA <= i_hi; iA += 2) {
                 PairHit h = test_pair(at, iA);
+                if (!BINARY && fixed) {
+                    bound += min(pair_bound<VECTOR>(h, at), 1 << 24);
+                    if (bound > limit) {
+                        fixed = false;
+                        for (int o = lane; o < ITERS * 512; o += 64)
+                            cx.tile[o] = (float)reinterpret_cast<int *>(cx.tile)[o] * (1.0f / kFixedOne);
+                        lds_sync();
+                    }
+                }
                 any = pair_run<VECTOR, BINARY>(cx, h, fixed) || any;
             }
+            at = next;
         }
-    }
-    if (NW > 1) {
-        if (any && lane == 0) cx.shared[1] = 1;
-        __syncthreads();                            // every wavefront's additions are in the tile
-        any = cx.shared[1] != 0;
+    } else {
+        PairHit h0;
+        if (NW > 1) __syncthreads();                // shared[] is clear
+        // pass 1: what can be added to one voxel at most decides fixed point or float (one
+        // wavefront keeps the bound in a register, several add theirs up in LDS)
+        int bound = 0;
+        if (single) {
+            h0 = test_pair(at0, i_lo);
+            if (!BINARY) bound = pair_bound<VECTOR>(h0, at0);
+        } else if (!BINARY) {
+            for (int base = 0; base < count && bound <= limit; base += 64 * NW) {
+                const Atom at = base == 0 ? at0 : load_atom(base);
+                for (int iA = i_lo; iA <= i_hi; iA += 2) {
+                    const PairHit h = test_pair(at, iA);
+                    bound += min(pair_bound<VECTOR>(h, at), 1 << 24);   // past the limit the value does not matter
+                }
+            }
+        }
+        if (NW > 1) {
+            if (lane == 0 && bound > 0) atomicAdd(&cx.shared[0], min(bound, 1 << 24));
+            __syncthreads();                        // tile and shared[0] are ready
+            bound = cx.shared[0];
+        }
+        fixed = !BINARY && bound <= limit;
+        // pass 2: the tasks
+        if (single) {
+            any = pair_run<VECTOR, BINARY>(cx, h0, fixed);
+        } else {
+            for (int base = 0; base < count; base += 64 * NW) {
+                const Atom at = base == 0 ? at0 : load_atom(base);
+                for (int iA = i_lo; iA <= i_hi; iA += 2) {
+                    PairHit h = test_pair(at, iA);
+                    any = pair_run<VECTOR, BINARY>(cx, h, fixed) || any;
+                }
+            }
+        }
+        if (NW > 1) {
+            if (any && lane == 0) cx.shared[1] = 1;
+            __syncthreads();                        // every wavefront's additions are in the tile
+            any = cx.shared[1] != 0;
+        }
     }
     store_tile<ALIGNED, ITERS, NW>(cx, dst, any, fixed);
 }

@@ -24,7 +24,7 @@
 //   3. atoms are placed, each bin is put in atom order (so the order in which
 //      the forward kernel sums is fixed), records are written bin by bin;
 //   4. for every type and x-plane, the span of records that can reach it.
-// Large N or very many (type, bin) pairs take the slower kernel below it: one
+// N > 8192 or very many (type, bin) pairs take the slower kernel below it: one
 // wavefront per group (example b, type t; vector types: example b) that scans
 // the example's types for its own atoms.
 #include "mg_common.h"
@@ -169,7 +169,7 @@ __device__ inline void clear_grads(float *gclear, float *wclear, size_t atom, in
 // One workgroup per example: counting sort by (type, x-bin) in LDS.
 // ---------------------------------------------------------------------------
 constexpr int kExThreads = 1024;
-constexpr int kExMaxAtoms = 4096;
+constexpr int kExMaxAtoms = 8192;           // 8 atoms per thread (4 in the kernel for N <= 4096)
 constexpr int kExMaxKeys = 12288;
 
 struct ExLayout {       // LDS, in ints
@@ -184,13 +184,12 @@ struct ExLayout {       // LDS, in ints
     __host__ __device__ int ints() const { return order() + (N + 1) / 2; }
 };
 
-template <bool VECTOR>
+template <bool VECTOR, int kPer>
 __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, Batch bt,
                                                                   Workspace ws, float *gclear,
                                                                   float *wclear, int stop)
 {
     extern __shared__ int s_mem[];
-    constexpr int kPer = kExMaxAtoms / kExThreads;      // atoms per thread, at most
     const int b = blockIdx.x, tid = threadIdx.x;
     const int N = bt.N, T = bt.T, D = gs.D;
     if (stop == 1) return;
@@ -626,12 +625,22 @@ hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
     L.K = (int)(K <= kExMaxKeys ? K : 0);
     const size_t lds_bytes = (size_t)L.ints() * sizeof(int);
     if (K <= kExMaxKeys && bt.N <= kExMaxAtoms && lds_bytes <= 64 * 1024) {
-        if (vec)
-            hipLaunchKernelGGL(prep_example_kernel<true>, dim3(bt.B), dim3(kExThreads), lds_bytes,
-                               stream, gs, bt, ws, gclear, wclear, stop);
-        else
-            hipLaunchKernelGGL(prep_example_kernel<false>, dim3(bt.B), dim3(kExThreads), lds_bytes,
-                               stream, gs, bt, ws, gclear, wclear, stop);
+        const dim3 grd(bt.B), blk(kExThreads);
+        if (bt.N <= 4 * kExThreads) {
+            if (vec)
+                hipLaunchKernelGGL((prep_example_kernel<true, 4>), grd, blk, lds_bytes, stream, gs, bt,
+                                   ws, gclear, wclear, stop);
+            else
+                hipLaunchKernelGGL((prep_example_kernel<false, 4>), grd, blk, lds_bytes, stream, gs,
+                                   bt, ws, gclear, wclear, stop);
+        } else {
+            if (vec)
+                hipLaunchKernelGGL((prep_example_kernel<true, 8>), grd, blk, lds_bytes, stream, gs, bt,
+                                   ws, gclear, wclear, stop);
+            else
+                hipLaunchKernelGGL((prep_example_kernel<false, 8>), grd, blk, lds_bytes, stream, gs,
+                                   bt, ws, gclear, wclear, stop);
+        }
         return hipGetLastError();
     }
     if (vec) {

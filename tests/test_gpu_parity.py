@@ -105,15 +105,15 @@ def test_forward_ragged_small_unaligned_grid(mg, grm, scale):
     assert got[2].max() == 0.0
 
 
-@pytest.mark.parametrize("single_type", [False, True])
-def test_forward_backward_many_atoms_per_example(mg, single_type):
-    """N = 5000 is past what the one-workgroup-per-example prep kernel takes (the per-group
-    kernel runs instead); with every atom of one type the group is also too long for that
-    kernel to bin by x-plane (records stay in atom order)."""
-    w = workloads.ragged_small(seed=11, B=2, N=5000, T=3, D=16, resolution=0.5)
+@pytest.mark.parametrize("N,single_type", [(5000, False), (9000, False), (9000, True)])
+def test_forward_backward_many_atoms_per_example(mg, N, single_type):
+    """N = 5000: eight atoms per thread in the one-workgroup-per-example prep kernel.  N = 9000 is
+    past what that kernel takes (the per-group kernel runs instead); with every atom of one type
+    the group is also too long for that kernel to bin by x-plane (records stay in atom order)."""
+    w = workloads.ragged_small(seed=11, B=2, N=N, T=3, D=16, resolution=0.5)
     if single_type:
         w.types[:] = 1
-    nat = np.array([5000, 4321], np.int32)
+    nat = np.array([N, N - 679], np.int32)
     got = run_forward_index(mg, w, natoms=nat)
     ref = oracle_forward_index(w, natoms=nat)
     # dozens of atoms overlap in every voxel: float accumulation, error relative to the sums

@@ -124,3 +124,15 @@ def test_calls_reject_bad_arguments_before_any_launch(L):
     assert L.mg_set_option(b"nope", 0) == -3
     for hh in (h, hb, hp):
         L.mg_gridmaker_destroy(hh)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU; with --gpus above 1 it says so and exits (before touching a GPU)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr
+    assert r.stdout.strip() == ""

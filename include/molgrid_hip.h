@@ -157,8 +157,9 @@ int mg_last_hip_error(void);
 /*
  * Tuning knobs, for measurement only (results do not depend on them beyond
  * rounding).  Process-wide; not meant to be changed while calls are in flight.
- *   "tile_floats"     1024 or 2048 (default 2048): consecutive output floats one
- *                     forward workgroup produces
+ *   "tile_floats"     1024, 2048 or 4096 (default 2048; 4096 needs 2 or 4
+ *                     wavefronts): consecutive output floats one forward
+ *                     workgroup produces
  *   "waves_per_tile"  1, 2 or 4 (default 1): wavefronts in that workgroup
  *   "xcd_run"         0 or a power of two (default 0): runs of this many
  *                     consecutive tiles go to one XCD

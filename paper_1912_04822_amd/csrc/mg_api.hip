@@ -271,7 +271,7 @@ int mg_set_option(const char *key, int value)
 {
     if (!key) return MG_ENULL;
     if (std::strcmp(key, "tile_floats") == 0) {
-        if (value != 1024 && value != 2048) return MG_EPARAM;
+        if (value != 1024 && value != 2048 && value != 4096) return MG_EPARAM;
         g_tile_floats = value;
         return MG_OK;
     }

@@ -85,7 +85,7 @@ struct Batch {
 // `tile_floats` consecutive floats of one channel (the last tile of a channel
 // may be shorter).
 struct ForwardGeometry {
-    int tile_floats;    // 1024 or 2048
+    int tile_floats;    // 1024, 2048 or 4096
     int tiles;          // tiles per channel = ceil(D^3 / tile_floats)
 };
 ForwardGeometry forward_geometry(int D, int tile_floats);

@@ -521,9 +521,20 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
         return;
     }
 
-    // atom e of the span goes to lane e / NW of wavefront e % NW, round after round
+    // How the wavefronts share the work: the `nsplit` wavefronts of a set take the atoms of
+    // the span in turn (atom e goes to lane e / nsplit of member e % nsplit, round after
+    // round) and every set works through the plane pairs pA0, pA0 + 2, ... pA1.  Usually
+    // there is one set (all wavefronts, all pairs); four wavefronts on a tile with exactly
+    // two plane pairs form two sets of two, one per pair.
+    int nsplit = NW, sub = wave, pA0 = i_lo, pA1 = i_hi;
+    if (NW == 4 && i_hi - i_lo >= 2 && i_hi - i_lo <= 3) {
+        nsplit = 2;
+        sub = wave & 1;
+        pA0 = i_lo + 2 * (wave >> 1);
+        pA1 = min(pA0 + 1, i_hi);
+    }
     auto load_atom = [&](int base) {
-        const int e = base + lane * NW + wave;
+        const int e = base + lane * nsplit + sub;
         Atom at;
         at.a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         at.w = 1.0f;
@@ -555,7 +566,7 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
             reinterpret_cast<float4 *>(cx.tile)[it * 64 * NW + threadIdx.x] = z4;
         if (threadIdx.x < 2) cx.shared[threadIdx.x] = 0;
     }
-    const bool single = count <= 64 * NW && i_hi - i_lo <= 1;      // one round, one pair of planes
+    const bool single = count <= 64 * nsplit && pA1 - pA0 <= 1;    // one round, one pair of planes
     const int limit = (int)(kFixedLimit * 256.0f);
     bool any = false, fixed = !BINARY;
     if (NW == 1 && !single) {
@@ -568,7 +579,7 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
         for (int base = 0; base < count; base += 64) {
             Atom next = at;
             if (base + 64 < count) next = load_atom(base + 64);
-            for (int iA = i_lo; iA <= i_hi; iA += 2) {
+            for (int iA = pA0; iA <= pA1; iA += 2) {
                 PairHit h = test_pair(at, iA);
                 if (!BINARY && fixed) {
                     bound += min(pair_bound<VECTOR>(h, at), 1 << 24);
@@ -588,32 +599,34 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
         if (NW > 1) __syncthreads();                // shared[] is clear
         // pass 1: what can be added to one voxel at most decides fixed point or float (one
         // wavefront keeps the bound in a register, several add theirs up in LDS)
+        // (index types: every record adds at most 1 to a voxel, so a short span needs no count)
+        const bool short_span = !VECTOR && count <= (int)kFixedLimit;
         int bound = 0;
         if (single) {
-            h0 = test_pair(at0, i_lo);
-            if (!BINARY) bound = pair_bound<VECTOR>(h0, at0);
-        } else if (!BINARY) {
-            for (int base = 0; base < count && bound <= limit; base += 64 * NW) {
+            h0 = test_pair(at0, pA0);
+            if (!BINARY && !short_span) bound = pair_bound<VECTOR>(h0, at0);
+        } else if (!BINARY && !short_span) {
+            for (int base = 0; base < count && bound <= limit; base += 64 * nsplit) {
                 const Atom at = base == 0 ? at0 : load_atom(base);
-                for (int iA = i_lo; iA <= i_hi; iA += 2) {
+                for (int iA = pA0; iA <= pA1; iA += 2) {
                     const PairHit h = test_pair(at, iA);
                     bound += min(pair_bound<VECTOR>(h, at), 1 << 24);   // past the limit the value does not matter
                 }
             }
         }
         if (NW > 1) {
-            if (lane == 0 && bound > 0) atomicAdd(&cx.shared[0], min(bound, 1 << 24));
+            if (!short_span && lane == 0 && bound > 0) atomicAdd(&cx.shared[0], min(bound, 1 << 24));
             __syncthreads();                        // tile and shared[0] are ready
-            bound = cx.shared[0];
+            if (!short_span) bound = cx.shared[0];
         }
         fixed = !BINARY && bound <= limit;
         // pass 2: the tasks
         if (single) {
             any = pair_run<VECTOR, BINARY>(cx, h0, fixed);
         } else {
-            for (int base = 0; base < count; base += 64 * NW) {
+            for (int base = 0; base < count; base += 64 * nsplit) {
                 const Atom at = base == 0 ? at0 : load_atom(base);
-                for (int iA = i_lo; iA <= i_hi; iA += 2) {
+                for (int iA = pA0; iA <= pA1; iA += 2) {
                     PairHit h = test_pair(at, iA);
                     any = pair_run<VECTOR, BINARY>(cx, h, fixed) || any;
                 }
@@ -706,6 +719,8 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     case 4 * 8 + 1: MG_LAUNCH5(V, Bn, Al, 4, 1); break;                         \
     case 4 * 8 + 2: MG_LAUNCH5(V, Bn, Al, 4, 2); break;                         \
     case 4 * 8 + 4: MG_LAUNCH5(V, Bn, Al, 4, 4); break;                         \
+    case 8 * 8 + 2: MG_LAUNCH5(V, Bn, Al, 8, 2); break;                         \
+    case 8 * 8 + 4: MG_LAUNCH5(V, Bn, Al, 8, 4); break;                         \
     default: return hipErrorInvalidValue;                                       \
     }
     if (vec) {

@@ -153,7 +153,7 @@ def test_forward_protein_ligand_subset_and_determinism(mg):
     assert got.max() > 1.0
     again = run_forward_index(mg, w)
     assert np.array_equal(got.view(np.uint32), again.view(np.uint32))
-    for tile_floats, waves in ((1024, 1), (1024, 2), (2048, 2), (2048, 4)):
+    for tile_floats, waves in ((1024, 1), (1024, 2), (2048, 2), (2048, 4), (4096, 2), (4096, 4)):
         mg.set_option("tile_floats", tile_floats)
         mg.set_option("waves_per_tile", waves)
         try:
@@ -264,6 +264,31 @@ def test_forward_vector_binary_is_bit_exact(mg):
     ref = oracle.forward_binary(w.coords, w.radii, w.T, w.resolution, w.dimension, weights=wt,
                                 centers=w.centers, quats=w.quats, translations=w.translations)
     assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("tile_floats,waves", [(1024, 2), (2048, 4), (4096, 4)])
+def test_tile_shapes_binary_and_vector(mg, tile_floats, waves):
+    """The other tile sizes and workgroup shapes of the forward kernel, in binary and vector mode
+    (several wavefronts per tile, several rounds of atoms, more than one pair of planes)."""
+    mg.set_option("tile_floats", tile_floats)
+    mg.set_option("waves_per_tile", waves)
+    try:
+        w = workloads.protein_ligand(B=2, with_weights=True)
+        got = run_forward_index(mg, w, binary=True)
+        ref = oracle_forward_index(w, binary=True)
+        assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+        got = run_forward_vector(mg, w)
+        ref = oracle.forward_vector(w.coords, w.weights, w.radii, w.resolution, w.dimension,
+                                    centers=w.centers, quats=w.quats, translations=w.translations)
+        assert np.abs(got - ref).max() <= GRID_TOL
+        w = workloads.ragged_small()
+        nat = w.extra["natoms"]
+        got = run_forward_index(mg, w, natoms=nat)
+        ref = oracle_forward_index(w, natoms=nat)
+        assert np.abs(got - ref).max() <= GRID_TOL
+    finally:
+        mg.set_option("tile_floats", 2048)
+        mg.set_option("waves_per_tile", 1)
 
 
 # ---------------------------------------------------------------------------

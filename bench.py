@@ -210,6 +210,10 @@ def main():
         add("backward_index", lambda: gm.mg_backward_index(
             coords, types, radii, w.T, G, centers=centers, quats=quats, translations=trans,
             grad_coords=gc, workspace=ws), w.out_bytes, args.steps)
+        gw = torch.empty((w.B, w.N, w.T), dtype=torch.float32, device="cuda")
+        add("backward_vector", lambda: gm.mg_backward_vector(
+            coords, weights, radii, G, centers=centers, quats=quats, translations=trans,
+            grad_coords=gc, grad_weights=gw, workspace=ws), w.out_bytes, k)
         result["rows"] = rows
 
     if not args.no_cpu:

@@ -15,6 +15,8 @@
 // partial sums are reduced with wavefront shuffles in a fixed order.  Records
 // are grouped by channel (and, within a channel, by x-plane), so neighbouring
 // wavefronts read the same part of the same channel volume.
+#include <cmath>
+
 #include "mg_common.h"
 
 namespace mg {
@@ -35,7 +37,9 @@ struct BwdParams {
     float *grad_coords;
     float *grad_weights;
     int B, N, T;
-    float kexp;
+    float sk, g2k;          // sqrt(k), g^2 k with k = 2 log2(e)
+    float A2, cAk2;         // 2A, 2A c sqrt(k)
+    float sAk, cA;          // sqrt(A/k), c sqrt(A)
 };
 
 __device__ inline float wave_sum(float v)
@@ -66,9 +70,12 @@ __device__ inline bool atom_box(const GridSpec &gs, float reach, const float4 &a
     return bx.np > 0 && bx.nr > 0 && bx.ns > 0 && khi >= klo;
 }
 
-// Accumulate over one channel volume.  gsum: sum G f u (3), vsum: sum G rho.
+// Accumulate over one channel volume, in coordinates scaled to units of r/sqrt(k),
+// k = 2 log2(e) (then exp(-2x^2) = exp2(-x'^2)):  (sx, sy, sz) += sum G f u',  sv += sum G rho.
+//   f = -4 exp2(-x'^2)                   x'^2 <= g^2 k
+//     = min(2A - 2A c sqrt(k) / x', 0)   beyond (zero from the cutoff on)
 template <bool ALIGNED, bool WANT_VALUE>
-__device__ inline void reduce_channel(const BwdParams &p, const float *Gc, const float4 &a, float inv_r2,
+__device__ inline void reduce_channel(const BwdParams &p, const float *Gc, const float4 &a, float r,
                                       const Box &bx, float ox, float oy, float oz, float &sx,
                                       float &sy, float &sz, float &sv)
 {
@@ -77,9 +84,11 @@ __device__ inline void reduce_channel(const BwdParams &p, const float *Gc, const
     const int per_plane = bx.nr * bx.ns;
     const int slots = bx.np * per_plane;
     const float inv_pp = 1.0f / (float)per_plane, inv_ns = 1.0f / (float)bx.ns;
-    for (int s = (int)(threadIdx.x & 63u); s < slots; s += 64) {
-        const int pi = (int)(((float)s + 0.5f) * inv_pp);
-        const int rem = s - pi * per_plane;
+    const float s = p.sk / r, step = gs.res * s;
+    const float azs = (a.z - oz) * s;
+    for (int sl = (int)(threadIdx.x & 63u); sl < slots; sl += 64) {
+        const int pi = (int)(((float)sl + 0.5f) * inv_pp);
+        const int rem = sl - pi * per_plane;
         const int row = (int)(((float)rem + 0.5f) * inv_ns);
         const int seg = rem - row * bx.ns;
         const int i = bx.ilo + pi, j = bx.jlo + row, k4 = (bx.seg0 + seg) << 2;
@@ -92,25 +101,25 @@ __device__ inline void reduce_channel(const BwdParams &p, const float *Gc, const
 #pragma unroll
             for (int u = 0; u < 4; ++u) gv[u] = (k4 + u < D) ? src[u] : 0.0f;
         }
-        const float ux = a.x - (ox + (float)i * gs.res);
-        const float uy = a.y - (oy + (float)j * gs.res);
+        const float ux = (a.x - (ox + (float)i * gs.res)) * s;
+        const float uy = (a.y - (oy + (float)j * gs.res)) * s;
         const float b2 = ux * ux + uy * uy;
+        const float uz0 = azs - (float)k4 * step;
         float fsum = 0.0f;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const float uz = a.z - (oz + (float)(k4 + u) * gs.res);
-            const float x2 = fmaf(uz, uz, b2) * inv_r2;
-            const float e = __builtin_amdgcn_exp2f(x2 * p.kexp);
+            const float uz = uz0 - (float)u * step;
+            const float x2 = fmaf(uz, uz, b2);
+            const float e = __builtin_amdgcn_exp2f(-x2);
             const float rs = __builtin_amdgcn_rsqf(x2);
-            float f = x2 <= gs.g2 ? -4.0f * e : 2.0f * gs.A * (1.0f - gs.c * rs);
-            f = x2 < gs.c2 ? f : 0.0f;
+            const float ft = fminf(fmaf(-p.cAk2, rs, p.A2), 0.0f);
+            const float f = x2 <= p.g2k ? -4.0f * e : ft;
             const float gf = gv[u] * f;
             fsum += gf;
             sz = fmaf(gf, uz, sz);
             if (WANT_VALUE) {
-                const float tl = x2 * rs - gs.c;            // x - c
-                float rho = x2 <= gs.g2 ? e : gs.A * tl * tl;
-                rho = x2 < gs.c2 ? rho : 0.0f;
+                const float tl = fminf(fmaf(x2 * rs, p.sAk, -p.cA), 0.0f);     // sqrt(A) (x - c)
+                const float rho = x2 <= p.g2k ? e : tl * tl;
                 sv = fmaf(gv[u], rho, sv);
             }
         }
@@ -143,9 +152,9 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
         Box bx;
         float sx = 0.0f, sy = 0.0f, sz = 0.0f, sv = 0.0f;
         if (atom_box(gs, r * gs.c, a, ox, oy, oz, bx))
-            reduce_channel<ALIGNED, false>(p, p.G + ((size_t)b * T + t) * D3, a, 1.0f / (r * r), bx, ox,
+            reduce_channel<ALIGNED, false>(p, p.G + ((size_t)b * T + t) * D3, a, r, bx, ox,
                                            oy, oz, sx, sy, sz, sv);
-        const float inv_r2 = 1.0f / (r * r);
+        const float inv_r2 = 1.0f / (r * p.sk);         // 1/r^2 times r/sqrt(k): the sums are in scaled units
         tx = wave_sum(sx) * inv_r2;
         ty = wave_sum(sy) * inv_r2;
         tz = wave_sum(sz) * inv_r2;
@@ -156,9 +165,9 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
             float sx = 0.0f, sy = 0.0f, sz = 0.0f, sv = 0.0f;
             Box bx;
             if (r > 0.0f && atom_box(gs, r * gs.c, a, ox, oy, oz, bx))
-                reduce_channel<ALIGNED, true>(p, p.G + ((size_t)b * T + t) * D3, a, 1.0f / (r * r), bx,
+                reduce_channel<ALIGNED, true>(p, p.G + ((size_t)b * T + t) * D3, a, r, bx,
                                               ox, oy, oz, sx, sy, sz, sv);
-            const float inv_r2 = r > 0.0f ? 1.0f / (r * r) : 0.0f;
+            const float inv_r2 = r > 0.0f ? 1.0f / (r * p.sk) : 0.0f;   // sums are in scaled units
             if (p.grad_coords) {
                 tx = fmaf(w * inv_r2, wave_sum(sx), tx);
                 ty = fmaf(w * inv_r2, wave_sum(sy), ty);
@@ -191,7 +200,15 @@ hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace 
     p.types = bt.types; p.weights = bt.weights; p.radii = bt.radii; p.centers = bt.centers;
     p.G = grad_out; p.grad_coords = grad_coords; p.grad_weights = grad_weights;
     p.B = bt.B; p.N = bt.N; p.T = bt.T;
-    p.kexp = -2.8853900817779268f;
+    {
+        const double k = 2.8853900817779268;    // 2 / ln 2
+        p.sk = (float)std::sqrt(k);
+        p.g2k = (float)((double)gs.g2 * k);
+        p.A2 = (float)(2.0 * (double)gs.A);
+        p.cAk2 = (float)(2.0 * (double)gs.A * (double)gs.c * std::sqrt(k));
+        p.sAk = (float)std::sqrt((double)gs.A / k);
+        p.cA = (float)((double)gs.c * std::sqrt((double)gs.A));
+    }
     const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)grad_out & 15u) == 0);
     const dim3 grd((bt.N + 3) / 4, bt.B), blk(256);
     if (bt.weights) {

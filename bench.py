@@ -204,6 +204,17 @@ def main():
         add("forward_binary", lambda: gmb.mg_forward_index(
             coords, types, radii, w.T, centers=centers, quats=quats, translations=trans, out=out,
             workspace=ws), w.out_bytes, args.steps)
+        qa = torch.empty((w.B, 4), dtype=torch.float32, device="cuda")
+        ta = torch.empty((w.B, 3), dtype=torch.float32, device="cuda")
+        counter = [0]
+
+        def augmented():        # transforms drawn on the device, a new draw per call, then forward
+            counter[0] += 1
+            molgrid.mg_draw_transforms(2024, counter[0], w.B, True, 2.0, qa, ta)
+            gm.mg_forward_index(coords, types, radii, w.T, centers=centers, quats=qa,
+                                translations=ta, out=out, workspace=ws)
+
+        add("forward_augmented", augmented, w.out_bytes, args.steps)
         add("forward_vector", lambda: gm.mg_forward_vector(
             coords, weights, radii, centers=centers, quats=quats, translations=trans, out=out,
             workspace=ws), w.out_bytes, k)

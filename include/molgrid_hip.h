@@ -91,6 +91,37 @@ int mg_transform_forward(int B, int N, const float *coords, const float *centers
                          float *out, void *stream);
 
 /*
+ * The inverse of mg_transform_forward (same arrays, precision and rounding):
+ *   out[b][a] = R(quats[b])^T ((coords[b][a] - translations[b]) - centers[b]) + centers[b]
+ * The paper shows Transform.forward only; this brings transformed coordinates
+ * back to the caller's frame and, with centers = translations = NULL, rotates
+ * vectors such as gradients back (R^T v).
+ */
+int mg_transform_backward(int B, int N, const float *coords, const float *centers,
+                          const float *quats, const float *translations,
+                          float *out, void *stream);
+
+/*
+ * Random augmentation drawn on the device (Transformations section: a random
+ * rotation, and a random translation of at most a given distance, per
+ * example).  Writes quats [B][4] (w,x,y,z; (1,0,0,0) when random_rotation is
+ * 0) and translations [B][3] (zero when max_translation is 0) -- device
+ * arrays that the caller then passes to forward / backward, and keeps if the
+ * applied transforms are wanted afterwards.
+ * The paper fixes no generator or distribution.  Here: Philox4x32-10 with key
+ * = seed and counter = (b, draw, block), so example b's transform depends on
+ * (seed, draw, b) only (advance `draw` once per batch); a word w becomes
+ * u = (w + 0.5) / 2^32; rotation uniform over SO(3) (Shoemake):
+ * q = (sqrt(u0) cos 2pi u2, sqrt(1-u0) sin 2pi u1, sqrt(1-u0) cos 2pi u1,
+ * sqrt(u0) sin 2pi u2) from block 0; translation t_m = T (2 u_m - 1) per axis
+ * from block 1.  Double arithmetic, rounded once to float.
+ * max_translation must be finite and >= 0 (else MG_EPARAM).
+ */
+int mg_draw_transforms(uint64_t seed, uint64_t draw, int B, int random_rotation,
+                       float max_translation, float *quats, float *translations,
+                       void *stream);
+
+/*
  * Forward, index types (GridMaker section):
  *   out[b][t][p] = sum over atoms a of example b with types[b][a] == t of
  *                  rho(|p - x'_a| / r_a),         r_a = radius_scale * radius

@@ -124,6 +124,43 @@ def transform(coords, centers=None, quats=None, translations=None, as_float=True
     return o32 if as_float else o64
 
 
+def transform_inverse(coords, centers=None, quats=None, translations=None, as_float=True):
+    """x = R(q)^T ((x' - t) - c) + c per example.  Returns float32 (rounded once) or float64."""
+    coords = _f32(coords)
+    B, N, _ = coords.shape
+    centers = _f32(centers, (B, 3))
+    quats = _f32(quats, (B, 4))
+    translations = _f32(translations, (B, 3))
+    o32 = np.empty((B, N, 3), np.float32) if as_float else None
+    o64 = None if as_float else np.empty((B, N, 3), np.float64)
+    lib().orc_transform_inverse(ctypes.c_int(B), ctypes.c_int(N), _p(coords, _f32p),
+                                _p(centers, _f32p), _p(quats, _f32p), _p(translations, _f32p),
+                                _p(o32, _f32p), _p(o64, _f64p))
+    return o32 if as_float else o64
+
+
+def philox4x32_10(counter, key) -> np.ndarray:
+    """One block of the Philox-4x32-10 bijection: 4 counter words, 2 key words -> 4 words."""
+    c = np.ascontiguousarray(counter, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    assert c.shape == (4,) and k.shape == (2,)
+    o = np.empty(4, np.uint32)
+    u32p = ctypes.POINTER(ctypes.c_uint32)
+    lib().orc_philox4x32_10(c.ctypes.data_as(u32p), k.ctypes.data_as(u32p), o.ctypes.data_as(u32p))
+    return o
+
+
+def draw_transforms(seed: int, draw: int, B: int, random_rotation: bool = True,
+                    max_translation: float = 0.0):
+    """Per-example random quaternions [B,4] (w,x,y,z) and translations [B,3] (float32)."""
+    q = np.empty((B, 4), np.float32)
+    t = np.empty((B, 3), np.float32)
+    lib().orc_draw_transforms(ctypes.c_uint64(seed & (2**64 - 1)), ctypes.c_uint64(draw & (2**64 - 1)),
+                              ctypes.c_int(B), ctypes.c_int(1 if random_rotation else 0),
+                              ctypes.c_double(max_translation), _p(q, _f32p), _p(t, _f32p))
+    return q, t
+
+
 def _common(coords, natoms, centers, quats, translations):
     coords = _f32(coords)
     B, N, three = coords.shape

@@ -29,7 +29,9 @@
  * variant == brute force bitwise, rotation against scipy's Rotation, 90-degree
  * rotation equivariance, one-hot vector types == index types, ball lattice
  * counts for binary mode, backward against central finite differences and the
- * translational-invariance identity.  Nothing here is "parity unpinned"
+ * translational-invariance identity, the Philox known answers, Haar and
+ * uniform-box statistics of the drawn transforms, inverse(forward) = identity.
+ * Nothing here is "parity unpinned"
  * except agreement with the original libmolgrid binaries, which do not exist
  * in this build (stated in the design notes).
  */
@@ -147,6 +149,121 @@ int orc_transform(int B, int N, const float *coords, const float *centers,
                 if (out32) out32[k + m] = (float)o[m];
                 if (out64) out64[k + m] = o[m];
             }
+        }
+    }
+    return 0;
+}
+
+/*
+ * Inverse of the transform above:  x = R^T ((x' - t) - c) + c, double, fixed
+ * order, rounded once for out32.  (The paper shows Transform.forward only;
+ * the inverse is what brings transformed coordinates, and with c = t = 0
+ * gradient vectors, back to the caller's frame.)
+ */
+int orc_transform_inverse(int B, int N, const float *coords, const float *centers,
+                          const float *quats, const float *translations,
+                          float *out32, double *out64)
+{
+    for (int b = 0; b < B; ++b) {
+        xform X;
+        load_xform(&X, b, centers, quats, translations);
+        for (int a = 0; a < N; ++a) {
+            const size_t k = ((size_t)b * N + a) * 3;
+            double u[3], o[3];
+            for (int m = 0; m < 3; ++m) u[m] = ((double)coords[k + m] - X.t[m]) - X.c[m];
+            for (int m = 0; m < 3; ++m)
+                o[m] = ((X.R[0 + m] * u[0] + X.R[3 + m] * u[1]) + X.R[6 + m] * u[2]) + X.c[m];
+            for (int m = 0; m < 3; ++m) {
+                if (out32) out32[k + m] = (float)o[m];
+                if (out64) out64[k + m] = o[m];
+            }
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Random augmentation (Transformations section: a random rotation and a     */
+/* random translation of at most a given distance per example, drawn inside  */
+/* GridMaker.forward or by a Transform).  The paper names no generator and   */
+/* no distribution; the reading taken here:                                  */
+/*   - generator: Philox4x32-10 (Salmon, Moraes, Dror, Shaw, "Parallel       */
+/*     random numbers: as easy as 1, 2, 3", SC'11), key = the 64-bit seed    */
+/*     (low word, high word), counter = (example index b, low and high word  */
+/*     of a 64-bit draw number the caller advances per batch, block), block  */
+/*     0 for the rotation and 1 for the translation;                         */
+/*   - a 32-bit word w becomes the uniform u = (w + 0.5) / 2^32 in (0, 1);   */
+/*   - rotation: uniform over SO(3) by Shoemake's construction ("Uniform     */
+/*     random rotations", Graphics Gems III, 1992) from the first three      */
+/*     words of block 0:  s1 = sqrt(1-u0), s2 = sqrt(u0), a1 = 2 pi u1,      */
+/*     a2 = 2 pi u2,  q = (w,x,y,z) = (s2 cos a2, s1 sin a1, s1 cos a1,      */
+/*     s2 sin a2);                                                           */
+/*   - translation: each axis uniform in [-T, T], t_m = T (2 u_m - 1) from   */
+/*     the first three words of block 1.                                     */
+/* Everything is double and rounded once to float.                           */
+/* ------------------------------------------------------------------------ */
+
+static void mulhilo32(uint32_t a, uint32_t b, uint32_t *hi, uint32_t *lo)
+{
+    const uint64_t p = (uint64_t)a * (uint64_t)b;
+    *hi = (uint32_t)(p >> 32);
+    *lo = (uint32_t)p;
+}
+
+/* Ten rounds of the Philox-4x32 bijection; the key is bumped by the Weyl
+   constants (golden ratio, sqrt(3)-1) between rounds. */
+void orc_philox4x32_10(const uint32_t *ctr, const uint32_t *key, uint32_t *out)
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        uint32_t hi0, lo0, hi1, lo1;
+        mulhilo32(0xD2511F53u, c0, &hi0, &lo0);
+        mulhilo32(0xCD9E8D57u, c2, &hi1, &lo1);
+        const uint32_t n0 = hi1 ^ c1 ^ k0, n1 = lo1, n2 = hi0 ^ c3 ^ k1, n3 = lo0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+static double word_to_uniform(uint32_t w) { return ((double)w + 0.5) * (1.0 / 4294967296.0); }
+
+/*
+ * Per-example random transforms.  quats [B][4] (w,x,y,z), translations [B][3].
+ * random_rotation == 0 gives the identity quaternion (1,0,0,0);
+ * max_translation == 0 gives zero translations.  Example b's draw depends on
+ * (seed, draw, b) only.
+ */
+int orc_draw_transforms(uint64_t seed, uint64_t draw, int B, int random_rotation,
+                        double max_translation, float *quats, float *translations)
+{
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    const double two_pi = 6.283185307179586476925286766559;
+    for (int b = 0; b < B; ++b) {
+        uint32_t ctr[4] = {(uint32_t)b, (uint32_t)draw, (uint32_t)(draw >> 32), 0u}, w[4];
+        float *q = quats + 4 * (size_t)b, *t = translations + 3 * (size_t)b;
+        if (random_rotation) {
+            orc_philox4x32_10(ctr, key, w);
+            const double u0 = word_to_uniform(w[0]);
+            const double a1 = two_pi * word_to_uniform(w[1]);
+            const double a2 = two_pi * word_to_uniform(w[2]);
+            const double s1 = sqrt(1.0 - u0), s2 = sqrt(u0);
+            q[0] = (float)(s2 * cos(a2));
+            q[1] = (float)(s1 * sin(a1));
+            q[2] = (float)(s1 * cos(a1));
+            q[3] = (float)(s2 * sin(a2));
+        } else {
+            q[0] = 1.f; q[1] = 0.f; q[2] = 0.f; q[3] = 0.f;
+        }
+        if (max_translation != 0.0) {
+            ctr[3] = 1u;
+            orc_philox4x32_10(ctr, key, w);
+            for (int m = 0; m < 3; ++m)
+                t[m] = (float)(max_translation * (2.0 * word_to_uniform(w[m]) - 1.0));
+        } else {
+            t[0] = 0.f; t[1] = 0.f; t[2] = 0.f;
         }
     }
     return 0;

@@ -129,8 +129,9 @@ int mg_workspace_bytes(const mg_gridmaker *gm, int B, int N, int T, size_t *byte
     return MG_OK;
 }
 
-int mg_transform_forward(int B, int N, const float *coords, const float *centers,
-                         const float *quats, const float *translations, float *out, void *stream)
+static int transform_call(int B, int N, const float *coords, const float *centers,
+                          const float *quats, const float *translations, float *out,
+                          bool inverse, void *stream)
 {
     if (!coords || !out) return MG_ENULL;
     if (B < 1 || N < 1 || B > 65535) return MG_ESHAPE;
@@ -138,7 +139,31 @@ int mg_transform_forward(int B, int N, const float *coords, const float *centers
         misaligned4(translations))
         return MG_EALIGN;
     return hip_status(mg::launch_transform(B, N, coords, centers, quats, translations, out,
-                                           (hipStream_t)stream));
+                                           inverse, (hipStream_t)stream));
+}
+
+int mg_transform_forward(int B, int N, const float *coords, const float *centers,
+                         const float *quats, const float *translations, float *out, void *stream)
+{
+    return transform_call(B, N, coords, centers, quats, translations, out, false, stream);
+}
+
+int mg_transform_backward(int B, int N, const float *coords, const float *centers,
+                          const float *quats, const float *translations, float *out, void *stream)
+{
+    return transform_call(B, N, coords, centers, quats, translations, out, true, stream);
+}
+
+int mg_draw_transforms(uint64_t seed, uint64_t draw, int B, int random_rotation,
+                       float max_translation, float *quats, float *translations, void *stream)
+{
+    if (!quats || !translations) return MG_ENULL;
+    if (B < 1 || B > 65535) return MG_ESHAPE;
+    if (!(max_translation >= 0.0f) || !std::isfinite(max_translation)) return MG_EPARAM;
+    if (misaligned4(quats) || misaligned4(translations)) return MG_EALIGN;
+    return hip_status(mg::launch_draw_transforms(seed, draw, B, random_rotation != 0,
+                                                 max_translation, quats, translations,
+                                                 (hipStream_t)stream));
 }
 
 int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T, const float *coords,

@@ -104,7 +104,10 @@ extern int g_prep_stop;                 // timing aid: stop the prep kernel afte
 // Launchers (each enqueues on `stream`, returns the hipError_t of the launch).
 hipError_t launch_transform(int B, int N, const float *coords, const float *centers,
                             const float *quats, const float *translations, float *out,
-                            hipStream_t stream);
+                            bool inverse, hipStream_t stream);
+hipError_t launch_draw_transforms(uint64_t seed, uint64_t draw, int B, bool random_rotation,
+                                  float max_translation, float *quats, float *translations,
+                                  hipStream_t stream);
 hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                        float *grad_coords_to_clear, float *grad_weights_to_clear,
                        hipStream_t stream);

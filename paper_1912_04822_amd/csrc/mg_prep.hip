@@ -92,6 +92,18 @@ __device__ inline void apply_xform(const Xform &X, const float *p, float *o)
     o[2] = (float)((((X.R[6] * u0 + X.R[7] * u1) + X.R[8] * u2) + X.c[2]) + X.t[2]);
 }
 
+// the inverse map, same precision and rounding:  x = R^T ((x' - t) - c) + c
+__device__ inline void apply_xform_inverse(const Xform &X, const float *p, float *o)
+{
+    const double u0 = ((double)p[0] - X.t[0]) - X.c[0];
+    const double u1 = ((double)p[1] - X.t[1]) - X.c[1];
+    const double u2 = ((double)p[2] - X.t[2]) - X.c[2];
+    o[0] = (float)(((X.R[0] * u0 + X.R[3] * u1) + X.R[6] * u2) + X.c[0]);
+    o[1] = (float)(((X.R[1] * u0 + X.R[4] * u1) + X.R[7] * u2) + X.c[1]);
+    o[2] = (float)(((X.R[2] * u0 + X.R[5] * u1) + X.R[8] * u2) + X.c[2]);
+}
+
+template <bool INVERSE>
 __global__ __launch_bounds__(256) void transform_kernel(int B, int N, const float *coords,
                                                         const float *centers, const float *quats,
                                                         const float *translations, float *out)
@@ -103,7 +115,10 @@ __global__ __launch_bounds__(256) void transform_kernel(int B, int N, const floa
     load_xform(X, b, centers, quats, translations);
     const size_t k = ((size_t)b * N + a) * 3;
     float o[3];
-    apply_xform(X, coords + k, o);
+    if (INVERSE)
+        apply_xform_inverse(X, coords + k, o);
+    else
+        apply_xform(X, coords + k, o);
     out[k + 0] = o[0];
     out[k + 1] = o[1];
     out[k + 2] = o[2];
@@ -604,11 +619,15 @@ Workspace carve_workspace(void *base, int B, int N, int T, int D)
 
 hipError_t launch_transform(int B, int N, const float *coords, const float *centers,
                             const float *quats, const float *translations, float *out,
-                            hipStream_t stream)
+                            bool inverse, hipStream_t stream)
 {
     dim3 grid((N + 255) / 256, B);
-    hipLaunchKernelGGL(transform_kernel, grid, dim3(256), 0, stream, B, N, coords, centers, quats,
-                       translations, out);
+    if (inverse)
+        hipLaunchKernelGGL(transform_kernel<true>, grid, dim3(256), 0, stream, B, N, coords,
+                           centers, quats, translations, out);
+    else
+        hipLaunchKernelGGL(transform_kernel<false>, grid, dim3(256), 0, stream, B, N, coords,
+                           centers, quats, translations, out);
     return hipGetLastError();
 }
 

@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libmolgrid_hip.so")
 MG_OK = 0
 EXPORTS = [
     "mg_gridmaker_create", "mg_gridmaker_destroy", "mg_gridmaker_points_per_side",
-    "mg_workspace_bytes", "mg_transform_forward", "mg_forward_index", "mg_forward_vector",
+    "mg_workspace_bytes", "mg_transform_forward", "mg_transform_backward", "mg_draw_transforms",
+    "mg_forward_index", "mg_forward_vector",
     "mg_backward_index", "mg_backward_vector", "mg_strerror", "mg_last_hip_error",
     "mg_set_option", "mg_time_next_kernel",
 ]
@@ -51,6 +52,10 @@ def lib() -> ctypes.CDLL:
         L.mg_workspace_bytes.argtypes = [vp, ci, ci, ci, ctypes.POINTER(sz)]
         L.mg_transform_forward.restype = ci
         L.mg_transform_forward.argtypes = [ci, ci, vp, vp, vp, vp, vp, vp]
+        L.mg_transform_backward.restype = ci
+        L.mg_transform_backward.argtypes = [ci, ci, vp, vp, vp, vp, vp, vp]
+        L.mg_draw_transforms.restype = ci
+        L.mg_draw_transforms.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ci, ci, cf, vp, vp, vp]
         L.mg_forward_index.restype = ci
         L.mg_forward_index.argtypes = [vp, ci, ci, ci] + [vp] * 8 + [vp, sz, vp]
         L.mg_forward_vector.restype = ci
@@ -117,6 +122,37 @@ def mg_transform_forward(coords, centers=None, quats=None, translations=None, ou
     if rc != MG_OK:
         raise MolgridError(rc, "mg_transform_forward")
     return out
+
+
+def mg_transform_backward(coords, centers=None, quats=None, translations=None, out=None):
+    """x = R(q)^T ((x' - t) - c) + c per example; [B,N,3] float32 device tensors."""
+    B, N, _ = coords.shape
+    if out is None:
+        out = torch.empty_like(coords)
+    rc = lib().mg_transform_backward(
+        B, N, _ptr(coords, torch.float32, "coords", (B, N, 3)),
+        _ptr(centers, torch.float32, "centers", (B, 3)), _ptr(quats, torch.float32, "quats", (B, 4)),
+        _ptr(translations, torch.float32, "translations", (B, 3)),
+        _ptr(out, torch.float32, "out", (B, N, 3)), _stream())
+    if rc != MG_OK:
+        raise MolgridError(rc, "mg_transform_backward")
+    return out
+
+
+def mg_draw_transforms(seed: int, draw: int, B: int, random_rotation: bool = True,
+                       max_translation: float = 0.0, quats=None, translations=None, device=None):
+    """Per-example random quaternions [B,4] and translations [B,3] drawn on the device."""
+    if quats is None:
+        quats = torch.empty((B, 4), dtype=torch.float32, device=device or "cuda")
+    if translations is None:
+        translations = torch.empty((B, 3), dtype=torch.float32, device=quats.device)
+    rc = lib().mg_draw_transforms(
+        int(seed) & (2 ** 64 - 1), int(draw) & (2 ** 64 - 1), B, 1 if random_rotation else 0,
+        float(max_translation), _ptr(quats, torch.float32, "quats", (B, 4)),
+        _ptr(translations, torch.float32, "translations", (B, 3)), _stream())
+    if rc != MG_OK:
+        raise MolgridError(rc, "mg_draw_transforms")
+    return quats, translations
 
 
 class GridMaker:

@@ -1,0 +1,81 @@
+"""``torch.autograd`` glue over the C-ABI binding (GridMaker section: the grid is generated
+in place on a Torch tensor, and ``backward`` turns a gradient on the grid into atomic gradients,
+so coordinates -- and, with vector types, type weights -- can be optimised through the grid).
+
+No arithmetic of the method happens here: ``forward`` calls ``mg_forward_*`` and ``backward``
+calls ``mg_backward_*``; this module only tells autograd which call belongs to which.
+A binary GridMaker has no gradient (the indicator is piecewise constant); asking for one raises.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import torch
+
+from . import molgrid
+
+
+class _IndexGrid(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, coords, gm, types, radii, T, natoms, centers, quats, translations):
+        ctx.gm, ctx.T = gm, T
+        ctx.save_for_backward(coords, types, radii, natoms, centers, quats, translations)
+        return gm.mg_forward_index(coords.detach(), types, radii, T, natoms=natoms, centers=centers,
+                                   quats=quats, translations=translations)
+
+    @staticmethod
+    def backward(ctx, grad_out):
+        if ctx.gm.binary:
+            raise RuntimeError("a binary GridMaker has no gradient")
+        coords, types, radii, natoms, centers, quats, translations = ctx.saved_tensors
+        g = ctx.gm.mg_backward_index(coords.detach(), types, radii, ctx.T, grad_out.contiguous(),
+                                     natoms=natoms, centers=centers, quats=quats,
+                                     translations=translations)
+        return (g,) + (None,) * 8
+
+
+class _VectorGrid(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, coords, weights, gm, radii, natoms, centers, quats, translations):
+        ctx.gm = gm
+        ctx.save_for_backward(coords, weights, radii, natoms, centers, quats, translations)
+        return gm.mg_forward_vector(coords.detach(), weights.detach(), radii, natoms=natoms,
+                                    centers=centers, quats=quats, translations=translations)
+
+    @staticmethod
+    def backward(ctx, grad_out):
+        if ctx.gm.binary:
+            raise RuntimeError("a binary GridMaker has no gradient")
+        coords, weights, radii, natoms, centers, quats, translations = ctx.saved_tensors
+        want_c, want_w = ctx.needs_input_grad[0], ctx.needs_input_grad[1]
+        gc, gw = ctx.gm.mg_backward_vector(
+            coords.detach(), weights.detach(), radii, grad_out.contiguous(), natoms=natoms,
+            centers=centers, quats=quats, translations=translations,
+            want_coords=True, want_weights=bool(want_w))
+        return (gc if want_c else None, gw if want_w else None) + (None,) * 6
+
+
+class GridLayer(torch.nn.Module):
+    """A GridMaker as a differentiable layer: ``layer(coords, types=... | weights=..., ...)``
+    returns the ``[B,T,D,D,D]`` grid; gradients flow to ``coords`` (and ``weights``)."""
+
+    def __init__(self, resolution=0.5, dimension=23.5, binary=False, radius_type_indexed=True,
+                 radius_scale=1.0, gaussian_radius_multiple=1.0):
+        super().__init__()
+        self.gm = molgrid.GridMaker(resolution, dimension, binary=binary,
+                                    radius_type_indexed=radius_type_indexed,
+                                    radius_scale=radius_scale,
+                                    gaussian_radius_multiple=gaussian_radius_multiple)
+
+    def forward(self, coords, radii, *, types: Optional[torch.Tensor] = None,
+                weights: Optional[torch.Tensor] = None, T: Optional[int] = None, natoms=None,
+                centers=None, quats=None, translations=None):
+        if (types is None) == (weights is None):
+            raise ValueError("give exactly one of types (index) or weights (vector)")
+        if types is not None:
+            if T is None:
+                raise ValueError("index types need the number of channels T")
+            return _IndexGrid.apply(coords, self.gm, types, radii, T, natoms, centers, quats,
+                                    translations)
+        return _VectorGrid.apply(coords, weights, self.gm, radii, natoms, centers, quats,
+                                 translations)

@@ -70,6 +70,29 @@ int mg_gridmaker_create(mg_gridmaker **out, float resolution, float dimension,
                         float gaussian_radius_multiple);
 void mg_gridmaker_destroy(mg_gridmaker *gm);
 
+/*
+ * A GridMaker with a subgrid decomposition (the paper's route to size-
+ * extensive models with cubic grids: a larger region is presented as a
+ * sequence of cubic subgrids).  The region is a cube of S*D lattice points per
+ * side (S = subgrids_per_side, D = round(dimension/resolution)+1, spacing
+ * resolution) centred on the example's centre; it is produced as S^3 grids of
+ * D points per side, subgrid (sx,sy,sz) holding lattice points
+ * [sx*D,(sx+1)*D) x [sy*D,(sy+1)*D) x [sz*D,(sz+1)*D).  Every forward /
+ * backward call of such a GridMaker then takes
+ *     out, grad_out:  [B][S][S][S][T][D][D][D]   (sx slowest)
+ * while all other arrays keep their shapes; gradients are summed over the
+ * subgrids; rotation is about the example's centre as before.  A subgrid's
+ * centre is, per axis and in float (product, then sum),
+ *     centers[b] + ((float)s - (S-1)/2) * ((float)D * resolution).
+ * 1 <= S <= MG_MAX_SUBGRIDS and B*S^3 <= 65535 (else MG_ESHAPE); S = 1 is
+ * mg_gridmaker_create.  mg_workspace_bytes accounts for S.
+ */
+#define MG_MAX_SUBGRIDS 16
+int mg_gridmaker_create_subgrids(mg_gridmaker **out, float resolution, float dimension,
+                                 int subgrids_per_side, int binary, int radius_type_indexed,
+                                 float radius_scale, float gaussian_radius_multiple);
+int mg_gridmaker_subgrids_per_side(const mg_gridmaker *gm, int *S);
+
 /* D = round(dimension/resolution) + 1. */
 int mg_gridmaker_points_per_side(const mg_gridmaker *gm, int *D);
 

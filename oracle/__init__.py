@@ -295,3 +295,90 @@ def backward_vector(coords, weights, radii, resolution, dimension, grad_out, *, 
         _p(quats, _f32p), _p(translations, _f32p), g32, g64, _p(gc, _f64p), _p(gw, _f64p),
         ctypes.c_int(threads))
     return gc, gw
+
+
+# --------------------------------------------------------------------------
+# Subgrid decomposition (the paper: size extensiveness with cubic grids "by performing a
+# subgrid decomposition").  Reading: a cube of S*D lattice points per side, spacing
+# `resolution`, centred on the example's centre, presented as S^3 grids of D points per
+# side; subgrid (sx,sy,sz) holds lattice points [sx*D,(sx+1)*D) x ... .  Written as a
+# composition of the functions above: transform once (rotation about the example's centre),
+# then one plain forward per subgrid about that subgrid's centre.
+# --------------------------------------------------------------------------
+
+def subgrid_centers(centers, S: int, D: int, resolution: float) -> np.ndarray:
+    """[B,S,S,S,3] float32 centres: c + ((float)s - (S-1)/2) * ((float)D * res), all in float."""
+    c = _f32(centers)
+    B = c.shape[0]
+    step = np.float32(D) * np.float32(resolution)
+    mid = np.float32(0.5) * np.float32(S - 1)
+    off = (np.arange(S, dtype=np.float32) - mid) * step              # float product
+    out = np.empty((B, S, S, S, 3), np.float32)
+    out[..., 0] = c[:, None, None, None, 0] + off[None, :, None, None]
+    out[..., 1] = c[:, None, None, None, 1] + off[None, None, :, None]
+    out[..., 2] = c[:, None, None, None, 2] + off[None, None, None, :]
+    return out
+
+
+def _virtual(arr, S3):
+    return None if arr is None else np.repeat(np.asarray(arr), S3, axis=0)
+
+
+def forward_subgrids(coords, radii, S, resolution, dimension, *, T=None, types=None, weights=None,
+                     binary=False, grm=1.0, radius_scale=1.0, radius_type_indexed=True,
+                     natoms=None, centers=None, quats=None, translations=None):
+    """[B,S,S,S,T,D,D,D]: every subgrid by the plain forward about its own centre."""
+    coords = _f32(coords)
+    B, N, _ = coords.shape
+    D = points_per_side(resolution, dimension)
+    S3 = S ** 3
+    cen = _f32(centers, (B, 3)) if centers is not None else np.zeros((B, 3), np.float32)
+    moved = transform(coords, centers, quats, translations)          # float, rounded once
+    gc = subgrid_centers(cen, S, D, resolution).reshape(B * S3, 3)
+    vc, vn = _virtual(moved, S3), _virtual(natoms, S3)
+    vr = radii if radius_type_indexed else _virtual(radii, S3)
+    if binary:
+        out = forward_binary(vc, vr, T, resolution, dimension, types=_virtual(types, S3),
+                             weights=_virtual(weights, S3), radius_scale=radius_scale,
+                             radius_type_indexed=radius_type_indexed, natoms=vn, centers=gc)
+    elif weights is not None:
+        out = forward_vector(vc, _virtual(weights, S3), vr, resolution, dimension, grm=grm,
+                             radius_scale=radius_scale, natoms=vn, centers=gc)
+    else:
+        out = forward_index(vc, _virtual(types, S3), vr, T, resolution, dimension, grm=grm,
+                            radius_scale=radius_scale, radius_type_indexed=radius_type_indexed,
+                            natoms=vn, centers=gc)
+    return out.reshape((B, S, S, S) + out.shape[1:])
+
+
+def backward_subgrids(coords, radii, S, resolution, dimension, grad_out, *, T=None, types=None,
+                      weights=None, grm=1.0, radius_scale=1.0, radius_type_indexed=True,
+                      natoms=None, centers=None, quats=None, translations=None):
+    """dL/dcoords [B,N,3] (and dL/dweights [B,N,T] for vector types), summed over subgrids and
+    rotated back to the caller's frame."""
+    coords = _f32(coords)
+    B, N, _ = coords.shape
+    D = points_per_side(resolution, dimension)
+    S3 = S ** 3
+    cen = _f32(centers, (B, 3)) if centers is not None else np.zeros((B, 3), np.float32)
+    moved = transform(coords, centers, quats, translations)
+    gc = subgrid_centers(cen, S, D, resolution).reshape(B * S3, 3)
+    vc, vn = _virtual(moved, S3), _virtual(natoms, S3)
+    vr = radii if radius_type_indexed else _virtual(radii, S3)
+    G = np.asarray(grad_out)
+    G = G.reshape((B * S3,) + G.shape[4:])
+    gw = None
+    if weights is not None:
+        g, gw = backward_vector(vc, _virtual(weights, S3), vr, resolution, dimension, G, grm=grm,
+                                radius_scale=radius_scale, natoms=vn, centers=gc)
+        gw = gw.reshape(B, S3, N, -1).sum(1)
+    else:
+        g = backward_index(vc, _virtual(types, S3), vr, T, resolution, dimension, G, grm=grm,
+                           radius_scale=radius_scale, radius_type_indexed=radius_type_indexed,
+                           natoms=vn, centers=gc)
+    g = g.reshape(B, S3, N, 3).sum(1)                                # in the transformed frame
+    out = np.empty_like(g)
+    for b in range(B):                                               # back by R^T
+        R = quat_to_matrix(quats[b]) if quats is not None else np.eye(3)
+        out[b] = g[b] @ R
+    return (out, gw) if weights is not None else out

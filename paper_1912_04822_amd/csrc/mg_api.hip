@@ -10,6 +10,7 @@
 
 struct mg_gridmaker {
     mg::GridSpec gs;
+    mg::Subgrids sub;
     float dimension;
     float grm;
 };
@@ -39,6 +40,8 @@ int check_shape(const mg_gridmaker *gm, int B, int N, int T)
 {
     if (!gm) return MG_ENULL;
     if (B < 1 || N < 1 || T < 1) return MG_ESHAPE;
+    if (B > 65535 / gm->sub.count) return MG_ESHAPE;        // B below counts virtual examples
+    B *= gm->sub.count;
     if (B > 65535 || T > 65535) return MG_ESHAPE;         // grid.y, grid.z of the launches
     const long long D = gm->gs.D;
     const long long tiles = (long long)B * T * ((D * D * D + 511) / 512);   // forward workgroups
@@ -52,7 +55,7 @@ int check_workspace(const mg_gridmaker *gm, int B, int N, int T, void *ws, size_
 {
         if (!ws) return MG_EWORKSPACE;
     if (((uintptr_t)ws & 31u) != 0) return MG_EWORKSPACE;
-    if (ws_bytes < mg::workspace_bytes(B, N, T, gm->gs.D)) return MG_EWORKSPACE;
+    if (ws_bytes < mg::workspace_bytes(gm->gs, gm->sub.count, B * gm->sub.count, N, T)) return MG_EWORKSPACE;
     return MG_OK;
 }
 
@@ -65,12 +68,14 @@ int hip_status(hipError_t e)
     return MG_EHIP;
 }
 
-mg::Batch make_batch(int B, int N, int T, const float *coords, const int32_t *types,
+// B: the caller's examples; the batch counts virtual examples (subgrids).
+mg::Batch make_batch(const mg_gridmaker *gm, int B, int N, int T, const float *coords, const int32_t *types,
                      const float *weights, const float *radii, const int32_t *natoms,
                      const float *centers, const float *quats, const float *translations)
 {
     mg::Batch bt;
-    bt.B = B; bt.N = N; bt.T = T;
+    bt.B = B * gm->sub.count; bt.N = N; bt.T = T;
+    bt.sub = gm->sub;
     bt.coords = coords; bt.types = types; bt.weights = weights; bt.radii = radii;
     bt.natoms = natoms; bt.centers = centers; bt.quats = quats; bt.translations = translations;
     return bt;
@@ -83,7 +88,16 @@ extern "C" {
 int mg_gridmaker_create(mg_gridmaker **out, float resolution, float dimension, int binary,
                         int radius_type_indexed, float radius_scale, float gaussian_radius_multiple)
 {
+    return mg_gridmaker_create_subgrids(out, resolution, dimension, 1, binary, radius_type_indexed,
+                                        radius_scale, gaussian_radius_multiple);
+}
+
+int mg_gridmaker_create_subgrids(mg_gridmaker **out, float resolution, float dimension,
+                                 int subgrids_per_side, int binary, int radius_type_indexed,
+                                 float radius_scale, float gaussian_radius_multiple)
+{
     if (!out) return MG_ENULL;
+    if (subgrids_per_side < 1 || subgrids_per_side > MG_MAX_SUBGRIDS) return MG_ESHAPE;
     if (!finite_pos(resolution) || !std::isfinite(dimension) || dimension < 0.0f ||
         !finite_pos(radius_scale) || !finite_pos(gaussian_radius_multiple))
         return MG_EPARAM;
@@ -105,6 +119,10 @@ int mg_gridmaker_create(mg_gridmaker **out, float resolution, float dimension, i
     gm->gs.c = (float)c;
     gm->gs.c2 = (float)(c * c);
     gm->gs.A = (float)(4.0 * g * g * std::exp(-2.0 * g * g));
+    gm->sub.per_side = subgrids_per_side;
+    gm->sub.count = subgrids_per_side * subgrids_per_side * subgrids_per_side;
+    gm->sub.mid = 0.5f * (float)(subgrids_per_side - 1);
+    gm->sub.step = (float)D * resolution;
     gm->dimension = dimension;
     gm->grm = gaussian_radius_multiple;
     *out = gm;
@@ -120,12 +138,19 @@ int mg_gridmaker_points_per_side(const mg_gridmaker *gm, int *D)
     return MG_OK;
 }
 
+int mg_gridmaker_subgrids_per_side(const mg_gridmaker *gm, int *S)
+{
+    if (!gm || !S) return MG_ENULL;
+    *S = gm->sub.per_side;
+    return MG_OK;
+}
+
 int mg_workspace_bytes(const mg_gridmaker *gm, int B, int N, int T, size_t *bytes)
 {
     if (!bytes) return MG_ENULL;
     const int rc = check_shape(gm, B, N, T);
     if (rc != MG_OK) return rc;
-    *bytes = mg::workspace_bytes(B, N, T, gm->gs.D);
+    *bytes = mg::workspace_bytes(gm->gs, gm->sub.count, B * gm->sub.count, N, T);
     return MG_OK;
 }
 
@@ -180,9 +205,9 @@ int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T, const float *c
         return MG_EALIGN;
     rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
     if (rc != MG_OK) return rc;
-    const mg::Batch bt = make_batch(B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
+    const mg::Batch bt = make_batch(gm, B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
                                     translations);
-    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
+    const mg::Workspace ws = mg::carve_workspace(gm->gs, gm->sub.count, workspace, bt.B, N, T);
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_waves_per_tile,
@@ -205,9 +230,9 @@ int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *
         return MG_EALIGN;
     rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
     if (rc != MG_OK) return rc;
-    const mg::Batch bt = make_batch(B, N, T, coords, nullptr, weights, radii, natoms, centers,
+    const mg::Batch bt = make_batch(gm, B, N, T, coords, nullptr, weights, radii, natoms, centers,
                                     quats, translations);
-    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
+    const mg::Workspace ws = mg::carve_workspace(gm->gs, gm->sub.count, workspace, bt.B, N, T);
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_waves_per_tile,
@@ -231,13 +256,18 @@ int mg_backward_index(const mg_gridmaker *gm, int B, int N, int T, const float *
         return MG_EALIGN;
     rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
     if (rc != MG_OK) return rc;
-    const mg::Batch bt = make_batch(B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
+    const mg::Batch bt = make_batch(gm, B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
                                     translations);
-    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, nullptr, (hipStream_t)stream));
+    const mg::Workspace ws = mg::carve_workspace(gm->gs, gm->sub.count, workspace, bt.B, N, T);
+    // with subgrids each virtual example's gradient goes to the workspace and they are summed
+    float *gc = gm->sub.count > 1 ? ws.gtmp : grad_coords;
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, gc, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
-    return hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, nullptr,
-                                          take_events(), (hipStream_t)stream));
+    rc = hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, gc, nullptr, take_events(),
+                                        (hipStream_t)stream));
+    if (rc != MG_OK || gm->sub.count == 1) return rc;
+    return hip_status(mg::launch_sum_subgrids(gm->sub.count, B, (size_t)N * 3, gc, grad_coords,
+                                              (hipStream_t)stream));
 }
 
 int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
@@ -258,14 +288,24 @@ int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T, const float 
         return MG_EALIGN;
     rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
     if (rc != MG_OK) return rc;
-    const mg::Batch bt = make_batch(B, N, T, coords, nullptr, weights, radii, natoms, centers,
+    const mg::Batch bt = make_batch(gm, B, N, T, coords, nullptr, weights, radii, natoms, centers,
                                     quats, translations);
-    const mg::Workspace ws = mg::carve_workspace(workspace, B, N, T, gm->gs.D);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, grad_coords, grad_weights,
-                                    (hipStream_t)stream));
+    const mg::Workspace ws = mg::carve_workspace(gm->gs, gm->sub.count, workspace, bt.B, N, T);
+    const bool sub = gm->sub.count > 1;
+    float *gc = (sub && grad_coords) ? ws.gtmp : grad_coords;
+    float *gw = (sub && grad_weights) ? ws.wtmp : grad_weights;
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, gc, gw, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
-    return hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, grad_coords, grad_weights,
-                                          take_events(), (hipStream_t)stream));
+    rc = hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, gc, gw, take_events(),
+                                        (hipStream_t)stream));
+    if (rc != MG_OK || !sub) return rc;
+    if (grad_coords)
+        rc = hip_status(mg::launch_sum_subgrids(gm->sub.count, B, (size_t)N * 3, gc, grad_coords,
+                                                (hipStream_t)stream));
+    if (rc == MG_OK && grad_weights)
+        rc = hip_status(mg::launch_sum_subgrids(gm->sub.count, B, (size_t)N * T, gw, grad_weights,
+                                                (hipStream_t)stream));
+    return rc;
 }
 
 const char *mg_strerror(int code)

@@ -32,11 +32,11 @@ struct BwdParams {
     const int32_t *types;
     const float *weights;
     const float *radii;
-    const float *centers;
+    const float *gcen;
     const float *G;
     float *grad_coords;
     float *grad_weights;
-    int B, N, T;
+    int subgrids, N, T;
     float sk, g2k;          // sqrt(k), g^2 k with k = 2 log2(e)
     float A2, cAk2;         // 2A, 2A c sqrt(k)
     float sAk, cA;          // sqrt(A/k), c sqrt(A)
@@ -141,13 +141,14 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
     if (!(a.w > 0.0f)) return;                      // dead record: the prep kernel wrote its zeros
     const int ai = p.idx[(size_t)b * N + slot];
     const size_t D3 = (size_t)D * D * D;
-    const float ox = (p.centers ? p.centers[3 * b + 0] : 0.0f) - gs.half;
-    const float oy = (p.centers ? p.centers[3 * b + 1] : 0.0f) - gs.half;
-    const float oz = (p.centers ? p.centers[3 * b + 2] : 0.0f) - gs.half;
+    const int bs = source_example(p.subgrids, b);          // types and weights are the source example's
+    const float ox = p.gcen[4 * b + 0] - gs.half;
+    const float oy = p.gcen[4 * b + 1] - gs.half;
+    const float oz = p.gcen[4 * b + 2] - gs.half;
 
     float tx = 0.0f, ty = 0.0f, tz = 0.0f;          // gradient in the transformed frame
     if (!VECTOR) {
-        const int t = p.types[(size_t)b * N + ai];
+        const int t = p.types[(size_t)bs * N + ai];
         const float r = a.w;
         Box bx;
         float sx = 0.0f, sy = 0.0f, sz = 0.0f, sv = 0.0f;
@@ -161,7 +162,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
     } else {
         for (int t = 0; t < T; ++t) {
             const float r = gs.radius_scale * p.radii[t];
-            const float w = p.weights[((size_t)b * N + ai) * T + t];
+            const float w = p.weights[((size_t)bs * N + ai) * T + t];
             float sx = 0.0f, sy = 0.0f, sz = 0.0f, sv = 0.0f;
             Box bx;
             if (r > 0.0f && atom_box(gs, r * gs.c, a, ox, oy, oz, bx))
@@ -188,7 +189,28 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
     }
 }
 
+// out[b][k] = sum over s < sub3 of tmp[b * sub3 + s][k], summed in order of s
+__global__ __launch_bounds__(256) void sum_subgrids_kernel(int sub3, size_t per_example,
+                                                           const float *tmp, float *out)
+{
+    const size_t k = (size_t)blockIdx.x * 256u + threadIdx.x;
+    if (k >= per_example) return;
+    const size_t b = blockIdx.y;
+    const float *src = tmp + b * (size_t)sub3 * per_example + k;
+    float acc = 0.0f;
+    for (int s = 0; s < sub3; ++s) acc += src[(size_t)s * per_example];
+    out[b * per_example + k] = acc;
+}
+
 }  // namespace
+
+hipError_t launch_sum_subgrids(int subgrid_count, int B_source, size_t per_example,
+                               const float *tmp, float *grad, hipStream_t stream)
+{
+    const dim3 grd((unsigned)((per_example + 255) / 256), B_source), blk(256);
+    hipLaunchKernelGGL(sum_subgrids_kernel, grd, blk, 0, stream, subgrid_count, per_example, tmp, grad);
+    return hipGetLastError();
+}
 
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                            const float *grad_out, float *grad_coords, float *grad_weights,
@@ -197,9 +219,9 @@ hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace 
     BwdParams p;
     p.gs = gs;
     p.rec = ws.rec; p.idx = ws.idx; p.meta = ws.meta; p.rot = ws.rot;
-    p.types = bt.types; p.weights = bt.weights; p.radii = bt.radii; p.centers = bt.centers;
+    p.types = bt.types; p.weights = bt.weights; p.radii = bt.radii; p.gcen = ws.gcen;
     p.G = grad_out; p.grad_coords = grad_coords; p.grad_weights = grad_weights;
-    p.B = bt.B; p.N = bt.N; p.T = bt.T;
+    p.subgrids = bt.sub.count; p.N = bt.N; p.T = bt.T;
     {
         const double k = 2.8853900817779268;    // 2 / ln 2
         p.sk = (float)std::sqrt(k);

@@ -33,6 +33,25 @@ struct GridSpec {
     float A;            // tail coefficient
 };
 
+// Subgrid decomposition (the paper's way to stay size-extensive with cubic grids): a cube
+// of per_side*D lattice points per side, spacing res, centred on the example's centre, is
+// produced as per_side^3 grids of D points per side.  The kernels see count = per_side^3
+// "virtual examples" per example: virtual example e reads the atoms and the pose of example
+// e / count and owns subgrid e % count = (sx*per_side + sy)*per_side + sz, whose centre is
+// centre + ((float)s - mid) * step per axis (float, product then sum).
+struct Subgrids {
+    int   per_side;     // 1: the plain GridMaker
+    int   count;        // per_side^3
+    float mid;          // (per_side-1)/2
+    float step;         // (float)D * res
+};
+
+// the example whose atoms and pose virtual example e reads
+__host__ __device__ inline int source_example(int subgrid_count, int e)
+{
+    return subgrid_count > 1 ? e / subgrid_count : e;
+}
+
 // ---------------------------------------------------------------------------
 // Workspace layout (device, caller-provided, 32-byte aligned).  A "group" is
 // the set of atoms one output channel reads: for index types the atoms of
@@ -57,6 +76,10 @@ struct GridSpec {
 //                         forward workgroups: reads that miss L2 while the chip
 //                         streams stores cost far more than their bytes
 //   rot   [B][12] float   rotation matrix rows (9 used), for the backward pass
+//   gcen  [B][4] float    centre of the example's grid (3 used)
+//   gtmp  [B][N][3] float, wtmp [B][N][T] float: with subgrids only, the
+//                         gradients per virtual example before they are summed
+// With subgrids B counts virtual examples everywhere above.
 // ---------------------------------------------------------------------------
 struct Workspace {
     float4 *rec;
@@ -64,13 +87,19 @@ struct Workspace {
     int4   *meta;
     int2   *range;
     float  *rot;
+    float  *gcen;
+    float  *gtmp;
+    float  *wtmp;
 };
 
-size_t workspace_bytes(int B, int N, int T, int D);
-Workspace carve_workspace(void *base, int B, int N, int T, int D);
+// B counts virtual examples; subgrid_count > 1 adds the gradient staging
+size_t workspace_bytes(const GridSpec &gs, int subgrid_count, int B, int N, int T);
+Workspace carve_workspace(const GridSpec &gs, int subgrid_count, void *base, int B, int N, int T);
 
+// B counts virtual examples (see Subgrids); the arrays are indexed by source example.
 struct Batch {
     int B, N, T;
+    Subgrids sub;
     const float   *coords;        // [B][N][3]
     const int32_t *types;         // [B][N] or null (vector types)
     const float   *weights;       // [B][N][T] or null (index types)
@@ -117,5 +146,8 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                            const float *grad_out, float *grad_coords, float *grad_weights,
                            KernelEvents ev, hipStream_t stream);
+// grad[b] = sum over the sub3 virtual examples of b, in order (subgrids only)
+hipError_t launch_sum_subgrids(int subgrid_count, int B_source, size_t per_example,
+                               const float *tmp, float *grad, hipStream_t stream);
 
 }  // namespace mg

@@ -72,9 +72,9 @@ struct FwdParams {
     const int2 *range;
     const float *weights;
     const float *radii;
-    const float *centers;
+    const float *gcen;          // [B][4] grid centres, written by the prep kernel
     float *out;
-    int B, N, T;
+    int subgrids, N, T;             // subgrids: virtual examples per example (weights are per example)
     int tile_floats;                // floats per tile (a multiple of 512)
     unsigned tiles;                 // tiles per channel
     unsigned long long div_magic;   // ceil(2^40 / D): x / D = (x * div_magic) >> 40 for x < D^3
@@ -446,7 +446,7 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     asm("s_mov_b32 %0, 0"
         : "=s"(zero)
         : "s"((unsigned long long)p.range), "s"((unsigned long long)p.rec),
-          "s"((unsigned long long)p.centers), "s"((unsigned long long)p.out), "s"(p.tiles_magic),
+          "s"((unsigned long long)p.gcen), "s"((unsigned long long)p.out), "s"(p.tiles_magic),
           "s"(p.t_magic), "s"(p.div_magic), "s"(p.tiles), "s"(p.xcd_shift), "s"(p.n_remap), "s"(D),
           "s"(T), "s"(N), "s"(p.debug), "s"(gs.half));
     unsigned u = blockIdx.x + zero;
@@ -498,14 +498,14 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     // slow while the chip streams stores): the span of records that can reach planes
     // i_lo .. i_hi (counted from the example's first record) and the grid centre.
     const int2 *span = p.range + group * D;
-    const float *cen = p.centers ? p.centers + 3 * b : reinterpret_cast<const float *>(span);
+    const float4 cen = *reinterpret_cast<const float4 *>(p.gcen + 4 * b);   // one 16-byte load
     const int r0 = span[i_lo].x;
     int r1 = span[i_hi].y;
-    const float cen_x = cen[0], cen_y = cen[1], cen_z = cen[2];
+    const float cen_x = cen.x, cen_y = cen.y, cen_z = cen.z;
     asm volatile("" ::"s"(r0), "s"(r1), "s"(cen_x), "s"(cen_y), "s"(cen_z));  // all in flight before the first wait
-    cx.cen_x = p.centers ? cen_x : 0.0f;
-    cx.cen_y = p.centers ? cen_y : 0.0f;
-    cx.cen_z = p.centers ? cen_z : 0.0f;
+    cx.cen_x = cen_x;
+    cx.cen_y = cen_y;
+    cx.cen_z = cen_z;
     cx.hD = 0.5f * (float)(D - 1);
     const float ox = cx.cen_x - gs.half;
     cx.oy = cx.cen_y - gs.half;
@@ -533,6 +533,9 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
         pA0 = i_lo + 2 * (wave >> 1);
         pA1 = min(pA0 + 1, i_hi);
     }
+    // vector types: the weights of this channel, one per atom of the source example
+    const float *wcol = VECTOR ? p.weights + (size_t)source_example(p.subgrids, b) * N * T + t
+                               : nullptr;
     auto load_atom = [&](int base) {
         const int e = base + lane * nsplit + sub;
         Atom at;
@@ -540,7 +543,7 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
         at.w = 1.0f;
         if (e < count) {
             at.a = rec[e];
-            if (VECTOR && at.a.w > 0.0f) at.w = p.weights[((size_t)b * N + idx[e]) * T + t];
+            if (VECTOR && at.a.w > 0.0f) at.w = wcol[(size_t)idx[e] * T];
         }
         at.valid = (e < count) && (at.a.w > 0.0f);
         if (VECTOR) {
@@ -674,9 +677,9 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     p.range = ws.range;
     p.weights = bt.weights;
     p.radii = bt.radii;
-    p.centers = bt.centers;
+    p.gcen = ws.gcen;
     p.out = out;
-    p.B = bt.B; p.N = bt.N; p.T = bt.T;
+    p.subgrids = bt.sub.count; p.N = bt.N; p.T = bt.T;
     p.tile_floats = fg.tile_floats;
     p.div_magic = ((1ULL << 40) + (unsigned long long)gs.D - 1ULL) / (unsigned long long)gs.D;
     p.tiles = (unsigned)fg.tiles;

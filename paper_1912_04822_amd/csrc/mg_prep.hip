@@ -146,7 +146,20 @@ struct Culler {
     float pad;
 };
 
-// Transformed position, radius and liveness of atom a of example b.
+// Centre of the grid of virtual example b (source example bs); X holds bs's centre (a float
+// widened to double, so narrowing it back is exact).
+__device__ inline void grid_center(const Subgrids &sub, const Xform &X, int b, int bs, float *gc)
+{
+    for (int m = 0; m < 3; ++m) gc[m] = (float)X.c[m];
+    if (sub.per_side > 1) {
+        const int s = b - bs * sub.count;
+        const int sxy = s / sub.per_side;
+        const int sv[3] = {sxy / sub.per_side, sxy % sub.per_side, s % sub.per_side};
+        for (int m = 0; m < 3; ++m) gc[m] = gc[m] + ((float)sv[m] - sub.mid) * sub.step;
+    }
+}
+
+// Transformed position, radius and liveness of atom a of (source) example b.
 template <bool VECTOR>
 __device__ inline bool place_atom(const GridSpec &gs, const Batch &bt, const Xform &X,
                                   const Culler &cu, int b, int t, int a, float vec_reach,
@@ -206,6 +219,7 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
 {
     extern __shared__ int s_mem[];
     const int b = blockIdx.x, tid = threadIdx.x;
+    const int bs = source_example(bt.sub.count, b);       // whose atoms and pose this (virtual) example reads
     const int N = bt.N, T = bt.T, D = gs.D;
     if (stop == 1) return;
     const int Tg = VECTOR ? 1 : T;      // groups per example
@@ -223,9 +237,9 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
 
     // Everything this thread needs from HBM is requested before anything is waited for:
     // its atoms (thread tid owns atoms tid, tid + 1024, ...), the radii table, the pose.
-    const int32_t *ty = VECTOR ? nullptr : bt.types + (size_t)b * N;
-    const float *crd = bt.coords + (size_t)b * N * 3;           // 32-bit offsets from here on
-    const float *rad_b = bt.radii + ((!VECTOR && !gs.radius_type_indexed) ? (size_t)b * N : 0);
+    const int32_t *ty = VECTOR ? nullptr : bt.types + (size_t)bs * N;
+    const float *crd = bt.coords + (size_t)bs * N * 3;          // 32-bit offsets from here on
+    const float *rad_b = bt.radii + ((!VECTOR && !gs.radius_type_indexed) ? (size_t)bs * N : 0);
     int my_t[kPer];
     float my_c[kPer][3], my_r[kPer];
 #pragma unroll
@@ -244,11 +258,11 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     }
     int n = N;
     if (bt.natoms) {
-        n = bt.natoms[b];
+        n = bt.natoms[bs];
         n = n < 0 ? 0 : (n > N ? N : n);
     }
     Xform X;
-    load_xform(X, b, bt.centers, bt.quats, bt.translations);
+    load_xform(X, bs, bt.centers, bt.quats, bt.translations);
     if (tid < 9) ws.rot[b * 12 + tid] = (float)X.R[tid];
     float vec_reach = 0.0f;         // reach of the widest channel, for vector types
     if (VECTOR) {
@@ -261,7 +275,10 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     Culler cu;
     cu.pad = 1.0e-3f * gs.res;
     cu.span = (float)(D - 1) * gs.res;
-    for (int m = 0; m < 3; ++m) cu.org[m] = (bt.centers ? bt.centers[3 * b + m] : 0.0f) - gs.half;
+    float gc[3];
+    grid_center(bt.sub, X, b, bs, gc);
+    if (tid < 3) ws.gcen[b * 4 + tid] = gc[tid];
+    for (int m = 0; m < 3; ++m) cu.org[m] = gc[m] - gs.half;
 
     if (!VECTOR && gs.radius_type_indexed)
         for (int k = tid; k < Tg; k += kExThreads) s_rad[k] = bt.radii[k];
@@ -396,17 +413,18 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
     __shared__ int s_rmax;
 
     const int b = blockIdx.y, t = blockIdx.x, lane = threadIdx.x;
+    const int bs = source_example(bt.sub.count, b);       // whose atoms and pose this (virtual) example reads
     const int N = bt.N, T = bt.T, D = gs.D;
     if (stop == 1) return;
     int n = N;
     if (bt.natoms) {
-        n = bt.natoms[b];
+        n = bt.natoms[bs];
         n = n < 0 ? 0 : (n > N ? N : n);
     }
-    const int32_t *ty = VECTOR ? nullptr : bt.types + (size_t)b * N;
+    const int32_t *ty = VECTOR ? nullptr : bt.types + (size_t)bs * N;
 
     Xform X;
-    load_xform(X, b, bt.centers, bt.quats, bt.translations);
+    load_xform(X, bs, bt.centers, bt.quats, bt.translations);
 
     // ---- 1. stable compaction: lane owns atoms [a0, a1) ----
     const int per = (n + 63) / 64;
@@ -449,7 +467,10 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
     Culler cu;
     cu.pad = 1.0e-3f * gs.res;
     cu.span = (float)(D - 1) * gs.res;
-    for (int m = 0; m < 3; ++m) cu.org[m] = (bt.centers ? bt.centers[3 * b + m] : 0.0f) - gs.half;
+    float gc[3];
+    grid_center(bt.sub, X, b, bs, gc);
+    if (t == 0 && lane < 3) ws.gcen[b * 4 + lane] = gc[lane];
+    for (int m = 0; m < 3; ++m) cu.org[m] = gc[m] - gs.half;
 
     float4 *rec = ws.rec + (size_t)b * N + first;
     int *idx = ws.idx + (size_t)b * N + first;
@@ -476,7 +497,7 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
         for (int m = lane; m < M; m += 64) {
             const int a = s_list[m];
             float p[3], r;
-            const bool live = place_atom<VECTOR>(gs, bt, X, cu, b, t, a, vec_reach, p, &r);
+            const bool live = place_atom<VECTOR>(gs, bt, X, cu, bs, t, a, vec_reach, p, &r);
             int bin = 0xFFFF;
             if (live) {
                 const float f = floorf((p[0] - cu.org[0]) * gs.inv_res);
@@ -537,7 +558,7 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
             if (pos < L) {
                 const int a = s_list[s_order[pos]];
                 float p[3], r;
-                (void)place_atom<VECTOR>(gs, bt, X, cu, b, t, a, vec_reach, p, &r);
+                (void)place_atom<VECTOR>(gs, bt, X, cu, bs, t, a, vec_reach, p, &r);
                 rec[pos] = make_float4(p[0], p[1], p[2], r);
                 idx[pos] = a;
             } else {
@@ -561,7 +582,7 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
             for (int m = lane; m < cnt; m += 64) {
                 const int a = s_list[m];
                 float p[3], r;
-                const bool live = place_atom<VECTOR>(gs, bt, X, cu, b, t, a, vec_reach, p, &r);
+                const bool live = place_atom<VECTOR>(gs, bt, X, cu, bs, t, a, vec_reach, p, &r);
                 rec[r0 + m] = make_float4(p[0], p[1], p[2], live ? r : 0.0f);
                 idx[r0 + m] = a;
                 if (!live) clear_grads(gclear, wclear, (size_t)b * N + a, T);
@@ -589,18 +610,23 @@ size_t align16(size_t v) { return (v + 15) / 16 * 16; }
 
 }  // namespace
 
-size_t workspace_bytes(int B, int N, int T, int D)
+size_t workspace_bytes(const GridSpec &gs, int subgrid_count, int B, int N, int T)
 {
     const size_t bn = (size_t)B * (size_t)N, bt = (size_t)B * (size_t)T;
     size_t bytes = bn * sizeof(float4);                     // rec
     bytes += align16(bn * sizeof(int));                     // idx
     bytes += bt * sizeof(int4);                             // meta
-    bytes += align16(bt * (size_t)D * sizeof(int2));        // range
+    bytes += align16(bt * (size_t)gs.D * sizeof(int2));     // range
     bytes += (size_t)B * 12 * sizeof(float);                // rot
+    bytes += (size_t)B * 4 * sizeof(float);                 // gcen
+    if (subgrid_count > 1) {
+        bytes += align16(bn * 3 * sizeof(float));           // gtmp
+        if (gs.radius_type_indexed) bytes += align16(bn * (size_t)T * sizeof(float));   // wtmp
+    }
     return bytes;
 }
 
-Workspace carve_workspace(void *base, int B, int N, int T, int D)
+Workspace carve_workspace(const GridSpec &gs, int subgrid_count, void *base, int B, int N, int T)
 {
     const size_t bn = (size_t)B * (size_t)N, bt = (size_t)B * (size_t)T;
     char *p = (char *)base;
@@ -612,8 +638,18 @@ Workspace carve_workspace(void *base, int B, int N, int T, int D)
     ws.meta = (int4 *)p;
     p += bt * sizeof(int4);
     ws.range = (int2 *)p;
-    p += align16(bt * (size_t)D * sizeof(int2));
+    p += align16(bt * (size_t)gs.D * sizeof(int2));
     ws.rot = (float *)p;
+    p += (size_t)B * 12 * sizeof(float);
+    ws.gcen = (float *)p;
+    p += (size_t)B * 4 * sizeof(float);
+    ws.gtmp = nullptr;
+    ws.wtmp = nullptr;
+    if (subgrid_count > 1) {
+        ws.gtmp = (float *)p;
+        p += align16(bn * 3 * sizeof(float));
+        if (gs.radius_type_indexed) ws.wtmp = (float *)p;
+    }
     return ws;
 }
 

@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libmolgrid_hip.so")
 
 MG_OK = 0
 EXPORTS = [
-    "mg_gridmaker_create", "mg_gridmaker_destroy", "mg_gridmaker_points_per_side",
+    "mg_gridmaker_create", "mg_gridmaker_create_subgrids", "mg_gridmaker_subgrids_per_side",
+    "mg_gridmaker_destroy", "mg_gridmaker_points_per_side",
     "mg_workspace_bytes", "mg_transform_forward", "mg_transform_backward", "mg_draw_transforms",
     "mg_forward_index", "mg_forward_vector",
     "mg_backward_index", "mg_backward_vector", "mg_strerror", "mg_last_hip_error",
@@ -44,6 +45,10 @@ def lib() -> ctypes.CDLL:
         vp, ci, cf, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
         L.mg_gridmaker_create.restype = ci
         L.mg_gridmaker_create.argtypes = [ctypes.POINTER(vp), cf, cf, ci, ci, cf, cf]
+        L.mg_gridmaker_create_subgrids.restype = ci
+        L.mg_gridmaker_create_subgrids.argtypes = [ctypes.POINTER(vp), cf, cf, ci, ci, ci, cf, cf]
+        L.mg_gridmaker_subgrids_per_side.restype = ci
+        L.mg_gridmaker_subgrids_per_side.argtypes = [vp, ctypes.POINTER(ci)]
         L.mg_gridmaker_destroy.restype = None
         L.mg_gridmaker_destroy.argtypes = [vp]
         L.mg_gridmaker_points_per_side.restype = ci
@@ -159,14 +164,22 @@ class GridMaker:
     """Handle over ``mg_gridmaker`` (GridMaker constructor listing of the paper)."""
 
     def __init__(self, resolution=0.5, dimension=23.5, binary=False, radius_type_indexed=False,
-                 radius_scale=1.0, gaussian_radius_multiple=1.0):
+                 radius_scale=1.0, gaussian_radius_multiple=1.0, subgrids_per_side=1):
         self._h = ctypes.c_void_p()
-        rc = lib().mg_gridmaker_create(ctypes.byref(self._h), resolution, dimension, int(binary),
-                                       int(radius_type_indexed), radius_scale,
-                                       gaussian_radius_multiple)
+        if subgrids_per_side == 1:
+            rc = lib().mg_gridmaker_create(ctypes.byref(self._h), resolution, dimension,
+                                           int(binary), int(radius_type_indexed), radius_scale,
+                                           gaussian_radius_multiple)
+        else:
+            rc = lib().mg_gridmaker_create_subgrids(
+                ctypes.byref(self._h), resolution, dimension, int(subgrids_per_side), int(binary),
+                int(radius_type_indexed), radius_scale, gaussian_radius_multiple)
         if rc != MG_OK:
             self._h = ctypes.c_void_p()
             raise MolgridError(rc, "mg_gridmaker_create")
+        sps = ctypes.c_int()
+        lib().mg_gridmaker_subgrids_per_side(self._h, ctypes.byref(sps))
+        self.S = sps.value
         d = ctypes.c_int()
         lib().mg_gridmaker_points_per_side(self._h, ctypes.byref(d))
         self.D = d.value
@@ -186,6 +199,11 @@ class GridMaker:
         if rc != MG_OK:
             raise MolgridError(rc, "mg_workspace_bytes")
         return n.value
+
+    def grid_shape(self, B: int, T: int):
+        """[B,T,D,D,D], or [B,S,S,S,T,D,D,D] for a GridMaker with S > 1 subgrids per side."""
+        D, S = self.D, self.S
+        return (B, T, D, D, D) if S == 1 else (B, S, S, S, T, D, D, D)
 
     def _workspace(self, B, N, T, device, workspace):
         need = self.workspace_bytes(B, N, T)
@@ -208,13 +226,13 @@ class GridMaker:
         B, N, pc, pn, pce, pq, pt = self._common(coords, natoms, centers, quats, translations)
         D = self.D
         if out is None:
-            out = torch.empty((B, T, D, D, D), dtype=torch.float32, device=coords.device)
+            out = torch.empty(self.grid_shape(B, T), dtype=torch.float32, device=coords.device)
         ws, wsb = self._workspace(B, N, T, coords.device, workspace)
         rshape = (T,) if self.radius_type_indexed else (B, N)
         rc = lib().mg_forward_index(
             self._h, B, N, T, pc, _ptr(types, torch.int32, "types", (B, N)),
             _ptr(radii, torch.float32, "radii", rshape), pn, pce, pq, pt,
-            _ptr(out, torch.float32, "out", (B, T, D, D, D)), ctypes.c_void_p(ws.data_ptr()), wsb,
+            _ptr(out, torch.float32, "out", self.grid_shape(B, T)), ctypes.c_void_p(ws.data_ptr()), wsb,
             _stream())
         if rc != MG_OK:
             raise MolgridError(rc, "mg_forward_index")
@@ -226,12 +244,12 @@ class GridMaker:
         T = weights.shape[2]
         D = self.D
         if out is None:
-            out = torch.empty((B, T, D, D, D), dtype=torch.float32, device=coords.device)
+            out = torch.empty(self.grid_shape(B, T), dtype=torch.float32, device=coords.device)
         ws, wsb = self._workspace(B, N, T, coords.device, workspace)
         rc = lib().mg_forward_vector(
             self._h, B, N, T, pc, _ptr(weights, torch.float32, "weights", (B, N, T)),
             _ptr(radii, torch.float32, "radii", (T,)), pn, pce, pq, pt,
-            _ptr(out, torch.float32, "out", (B, T, D, D, D)), ctypes.c_void_p(ws.data_ptr()), wsb,
+            _ptr(out, torch.float32, "out", self.grid_shape(B, T)), ctypes.c_void_p(ws.data_ptr()), wsb,
             _stream())
         if rc != MG_OK:
             raise MolgridError(rc, "mg_forward_vector")
@@ -248,7 +266,7 @@ class GridMaker:
         rc = lib().mg_backward_index(
             self._h, B, N, T, pc, _ptr(types, torch.int32, "types", (B, N)),
             _ptr(radii, torch.float32, "radii", rshape), pn, pce, pq, pt,
-            _ptr(grad_out, torch.float32, "grad_out", (B, T, D, D, D)),
+            _ptr(grad_out, torch.float32, "grad_out", self.grid_shape(B, T)),
             _ptr(grad_coords, torch.float32, "grad_coords", (B, N, 3)),
             ctypes.c_void_p(ws.data_ptr()), wsb, _stream())
         if rc != MG_OK:
@@ -269,7 +287,7 @@ class GridMaker:
         rc = lib().mg_backward_vector(
             self._h, B, N, T, pc, _ptr(weights, torch.float32, "weights", (B, N, T)),
             _ptr(radii, torch.float32, "radii", (T,)), pn, pce, pq, pt,
-            _ptr(grad_out, torch.float32, "grad_out", (B, T, D, D, D)),
+            _ptr(grad_out, torch.float32, "grad_out", self.grid_shape(B, T)),
             _ptr(grad_coords, torch.float32, "grad_coords", (B, N, 3)),
             _ptr(grad_weights, torch.float32, "grad_weights", (B, N, T)),
             ctypes.c_void_p(ws.data_ptr()), wsb, _stream())

@@ -80,8 +80,25 @@ def test_calls_reject_bad_arguments_before_any_launch(L):
     assert rc == 0
     n = sz()
     assert L.mg_workspace_bytes(h, 50, 2040, 28, ctypes.byref(n)) == 0
-    assert 50 * 2040 * 20 <= n.value <= 50 * 2040 * 20 + 50 * 28 * (16 + 48 * 8) + 50 * 48 + 64
+    assert 50 * 2040 * 20 <= n.value <= 50 * 2040 * 20 + 50 * 28 * (16 + 48 * 8) + 50 * 64 + 64
     assert L.mg_workspace_bytes(h, 0, 2040, 28, ctypes.byref(n)) == -2
+    # a subgrid decomposition: S^3 virtual examples per example, plus the gradient staging
+    L.mg_gridmaker_create_subgrids.argtypes = [ctypes.POINTER(vp), ctypes.c_float, ctypes.c_float,
+                                               ci, ci, ci, ctypes.c_float, ctypes.c_float]
+    hs = vp()
+    assert L.mg_gridmaker_create_subgrids(ctypes.byref(hs), 0.5, 11.5, 2, 0, 1, 1.0, 1.0) == 0
+    m = sz()
+    assert L.mg_workspace_bytes(hs, 50, 2040, 28, ctypes.byref(m)) == 0
+    assert m.value >= 8 * 50 * 2040 * (20 + 12 + 28 * 4)
+    s_ = ci()
+    L.mg_gridmaker_subgrids_per_side.argtypes = [vp, ctypes.POINTER(ci)]
+    assert L.mg_gridmaker_subgrids_per_side(hs, ctypes.byref(s_)) == 0 and s_.value == 2
+    assert L.mg_gridmaker_subgrids_per_side(h, ctypes.byref(s_)) == 0 and s_.value == 1
+    assert L.mg_workspace_bytes(hs, 9000, 10, 4, ctypes.byref(m)) == -2      # 72000 virtual examples
+    for bad in (0, -3, 17):
+        assert L.mg_gridmaker_create_subgrids(ctypes.byref(vp()), 0.5, 11.5, bad, 0, 1, 1.0, 1.0) == -2
+    L.mg_gridmaker_destroy.argtypes = [vp]
+    L.mg_gridmaker_destroy(hs)
     assert L.mg_workspace_bytes(h, 50, 2040, 28, None) == -1
     assert L.mg_workspace_bytes(None, 50, 2040, 28, ctypes.byref(n)) == -1
     fake = vp(0x1000)       # never dereferenced: validation fails first

@@ -9,15 +9,23 @@
 // d = 0 contribute exactly 0 through u = 0).  The gradient with respect to the
 // caller's coordinates is R^T times that sum.
 //
-// One wavefront per atom record (four records per workgroup, no barrier): the
-// 64 lanes spread over the atom's cutoff box (x-planes x rows x 4-voxel
-// z-segments), read the upstream gradient with 16-byte loads, and the three
-// partial sums are reduced with wavefront shuffles in a fixed order.  Records
-// are grouped by channel (and, within a channel, by x-plane), so neighbouring
-// wavefronts read the same part of the same channel volume.
+// One wavefront per atom record (four records per workgroup, no barrier).  The
+// work items are "slots": 4-voxel z-segments of the grid rows (x-plane, y) of
+// the atom's cutoff box, read with one 16-byte load each.  Only the slots that
+// meet the cutoff sphere are visited (about 45 % of the box's): per group of 128
+// rows every lane works out the segment span of its two rows, a prefix sum over
+// the lanes numbers the live slots, and slot s finds its row through a byte
+// array in LDS (the first slot of each lane's rows is marked with the lane, a
+// running maximum over the slots gives the owner) and one register exchange.
+// The kernel is bound by vector arithmetic (two transcendentals per voxel), so
+// the time goes with the number of voxels evaluated.  The three partial sums
+// are reduced with wavefront shuffles in a fixed order.  Records are grouped by
+// channel (and, within a channel, by x-plane), so neighbouring wavefronts read
+// the same part of the same channel volume.
 #include <cmath>
 
 #include "mg_common.h"
+#include "mg_wave.h"
 
 namespace mg {
 
@@ -37,7 +45,7 @@ struct BwdParams {
     float *grad_coords;
     float *grad_weights;
     int subgrids, N, T;
-    float sk, g2k;          // sqrt(k), g^2 k with k = 2 log2(e)
+    float sk, g2k, c2k;     // sqrt(k), g^2 k, c^2 k with k = 2 log2(e)
     float A2, cAk2;         // 2A, 2A c sqrt(k)
     float sAk, cA;          // sqrt(A/k), c sqrt(A)
 };
@@ -52,7 +60,11 @@ __device__ inline float wave_sum(float v)
 struct Box {
     int ilo, jlo, seg0;
     int np, nr, ns;
+    int klo, khi;
 };
+
+constexpr int kSlotCap = 1024;      // live slots of a group of 128 rows: at most 8 per row
+constexpr int kMaxCulledSegs = 8;   // boxes with more z-segments per row take the plain loop
 
 // grid points within `reach` of the atom along each axis, padded by 1e-3 steps
 __device__ inline bool atom_box(const GridSpec &gs, float reach, const float4 &a, float ox, float oy,
@@ -65,7 +77,7 @@ __device__ inline bool atom_box(const GridSpec &gs, float reach, const float4 &a
     const int ilo = max(0, (int)ceilf(fx - hv)), ihi = min(D - 1, (int)floorf(fx + hv));
     const int jlo = max(0, (int)ceilf(fy - hv)), jhi = min(D - 1, (int)floorf(fy + hv));
     const int klo = max(0, (int)ceilf(fz - hv)), khi = min(D - 1, (int)floorf(fz + hv));
-    bx.ilo = ilo; bx.jlo = jlo; bx.seg0 = klo >> 2;
+    bx.ilo = ilo; bx.jlo = jlo; bx.seg0 = klo >> 2; bx.klo = klo; bx.khi = khi;
     bx.np = ihi - ilo + 1; bx.nr = jhi - jlo + 1; bx.ns = (khi >> 2) - (klo >> 2) + 1;
     return bx.np > 0 && bx.nr > 0 && bx.ns > 0 && khi >= klo;
 }
@@ -74,13 +86,56 @@ __device__ inline bool atom_box(const GridSpec &gs, float reach, const float4 &a
 // k = 2 log2(e) (then exp(-2x^2) = exp2(-x'^2)):  (sx, sy, sz) += sum G f u',  sv += sum G rho.
 //   f = -4 exp2(-x'^2)                   x'^2 <= g^2 k
 //     = min(2A - 2A c sqrt(k) / x', 0)   beyond (zero from the cutoff on)
+// One slot: the four voxels k4 .. k4+3 of row (i, j).
 template <bool ALIGNED, bool WANT_VALUE>
-__device__ inline void reduce_channel(const BwdParams &p, const float *Gc, const float4 &a, float r,
-                                      const Box &bx, float ox, float oy, float oz, float &sx,
-                                      float &sy, float &sz, float &sv)
+__device__ inline void reduce_slot(const BwdParams &p, const float *Gc, const float4 &a, float s,
+                                   float step, float azs, int i, int j, int k4, float ox, float oy,
+                                   float &sx, float &sy, float &sz, float &sv)
 {
     const GridSpec &gs = p.gs;
     const int D = gs.D;
+    const float *src = Gc + ((size_t)i * D + j) * D + k4;
+    float gv[4];
+    if (ALIGNED) {
+        const float4 g4 = *reinterpret_cast<const float4 *>(src);
+        gv[0] = g4.x; gv[1] = g4.y; gv[2] = g4.z; gv[3] = g4.w;
+    } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) gv[u] = (k4 + u < D) ? src[u] : 0.0f;
+    }
+    const float ux = (a.x - (ox + (float)i * gs.res)) * s;
+    const float uy = (a.y - (oy + (float)j * gs.res)) * s;
+    const float b2 = ux * ux + uy * uy;
+    const float uz0 = azs - (float)k4 * step;
+    float fsum = 0.0f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const float uz = uz0 - (float)u * step;
+        const float x2 = fmaf(uz, uz, b2);
+        const float e = __builtin_amdgcn_exp2f(-x2);
+        const float rs = __builtin_amdgcn_rsqf(x2);
+        const float ft = fminf(fmaf(-p.cAk2, rs, p.A2), 0.0f);
+        const float f = x2 <= p.g2k ? -4.0f * e : ft;
+        const float gf = gv[u] * f;
+        fsum += gf;
+        sz = fmaf(gf, uz, sz);
+        if (WANT_VALUE) {
+            const float tl = fminf(fmaf(x2 * rs, p.sAk, -p.cA), 0.0f);     // sqrt(A) (x - c)
+            const float rho = x2 <= p.g2k ? e : tl * tl;
+            sv = fmaf(gv[u], rho, sv);
+        }
+    }
+    sx = fmaf(fsum, ux, sx);
+    sy = fmaf(fsum, uy, sy);
+}
+
+// Every slot of the box (boxes with very many segments per row).
+template <bool ALIGNED, bool WANT_VALUE>
+__device__ inline void reduce_channel_box(const BwdParams &p, const float *Gc, const float4 &a,
+                                          float r, const Box &bx, float ox, float oy, float oz,
+                                          float &sx, float &sy, float &sz, float &sv)
+{
+    const GridSpec &gs = p.gs;
     const int per_plane = bx.nr * bx.ns;
     const int slots = bx.np * per_plane;
     const float inv_pp = 1.0f / (float)per_plane, inv_ns = 1.0f / (float)bx.ns;
@@ -91,40 +146,87 @@ __device__ inline void reduce_channel(const BwdParams &p, const float *Gc, const
         const int rem = sl - pi * per_plane;
         const int row = (int)(((float)rem + 0.5f) * inv_ns);
         const int seg = rem - row * bx.ns;
-        const int i = bx.ilo + pi, j = bx.jlo + row, k4 = (bx.seg0 + seg) << 2;
-        const float *src = Gc + ((size_t)i * D + j) * D + k4;
-        float gv[4];
-        if (ALIGNED) {
-            const float4 g4 = *reinterpret_cast<const float4 *>(src);
-            gv[0] = g4.x; gv[1] = g4.y; gv[2] = g4.z; gv[3] = g4.w;
-        } else {
+        reduce_slot<ALIGNED, WANT_VALUE>(p, Gc, a, s, step, azs, bx.ilo + pi, bx.jlo + row,
+                                         (bx.seg0 + seg) << 2, ox, oy, sx, sy, sz, sv);
+    }
+}
+
+// Only the slots that meet the cutoff sphere.  `marks` is this wavefront's kSlotCap bytes of
+// LDS, all zero on entry and on return.
+template <bool ALIGNED, bool WANT_VALUE>
+__device__ inline void reduce_channel(const BwdParams &p, const float *Gc, const float4 &a, float r,
+                                      const Box &bx, float ox, float oy, float oz,
+                                      unsigned char *marks, float &sx, float &sy, float &sz,
+                                      float &sv)
+{
+    if (bx.ns > kMaxCulledSegs) {
+        reduce_channel_box<ALIGNED, WANT_VALUE>(p, Gc, a, r, bx, ox, oy, oz, sx, sy, sz, sv);
+        return;
+    }
+    const GridSpec &gs = p.gs;
+    const int lane = (int)(threadIdx.x & 63u);
+    const int rows = bx.np * bx.nr;
+    const float inv_nr = 1.0f / (float)bx.nr;
+    const float s = p.sk / r, step = gs.res * s;
+    const float inv_step = 1.0f / step;
+    const float azs = (a.z - oz) * s;
+    const float fz = (a.z - oz) * gs.inv_res;           // the atom's z in grid steps
+    for (int row0 = 0; row0 < rows; row0 += 128) {
+        // this lane's two rows of the group: which segments meet the sphere
+        int cnt[2] = {0, 0}, slo[2] = {0, 0};
 #pragma unroll
-            for (int u = 0; u < 4; ++u) gv[u] = (k4 + u < D) ? src[u] : 0.0f;
-        }
-        const float ux = (a.x - (ox + (float)i * gs.res)) * s;
-        const float uy = (a.y - (oy + (float)j * gs.res)) * s;
-        const float b2 = ux * ux + uy * uy;
-        const float uz0 = azs - (float)k4 * step;
-        float fsum = 0.0f;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const float uz = uz0 - (float)u * step;
-            const float x2 = fmaf(uz, uz, b2);
-            const float e = __builtin_amdgcn_exp2f(-x2);
-            const float rs = __builtin_amdgcn_rsqf(x2);
-            const float ft = fminf(fmaf(-p.cAk2, rs, p.A2), 0.0f);
-            const float f = x2 <= p.g2k ? -4.0f * e : ft;
-            const float gf = gv[u] * f;
-            fsum += gf;
-            sz = fmaf(gf, uz, sz);
-            if (WANT_VALUE) {
-                const float tl = fminf(fmaf(x2 * rs, p.sAk, -p.cA), 0.0f);     // sqrt(A) (x - c)
-                const float rho = x2 <= p.g2k ? e : tl * tl;
-                sv = fmaf(gv[u], rho, sv);
+        for (int q = 0; q < 2; ++q) {
+            const int row = row0 + 2 * lane + q;
+            if (row < rows) {
+                const int pi = (int)(((float)row + 0.5f) * inv_nr);
+                const int jr = row - pi * bx.nr;
+                const float ux = (a.x - (ox + (float)(bx.ilo + pi) * gs.res)) * s;
+                const float uy = (a.y - (oy + (float)(bx.jlo + jr) * gs.res)) * s;
+                const float h2 = p.c2k - (ux * ux + uy * uy);
+                if (h2 > 0.0f) {
+                    // half chord in grid steps; the pad only adds voxels that contribute 0
+                    const float hv = __builtin_amdgcn_sqrtf(h2) * inv_step + 1.0e-3f;
+                    const int klo = max(bx.klo, (int)ceilf(fz - hv));
+                    const int khi = min(bx.khi, (int)floorf(fz + hv));
+                    if (khi >= klo) {
+                        slo[q] = klo >> 2;
+                        cnt[q] = (khi >> 2) - slo[q] + 1;
+                    }
+                }
             }
         }
-        sx = fmaf(fsum, ux, sx);
-        sy = fmaf(fsum, uy, sy);
+        const int mine = cnt[0] + cnt[1];
+        const int incl = wave_inclusive_scan(mine);
+        const int total = bcast(incl, 63);
+        const int excl = incl - mine;
+        if (mine > 0) marks[excl] = (unsigned char)(lane + 1);
+        // what a slot needs of its owner: first slot (11 bits), slots of row 0 (4), first
+        // segment of row 0 and of row 1 (8 each)
+        const int word = excl | (cnt[0] << 11) | (slo[0] << 15) | (slo[1] << 23);
+        lds_sync();
+        int carry = 0;
+        for (int base = 0; base < total; base += 64) {
+            const int sidx = base + lane;
+            int v = sidx < total ? (int)marks[sidx] : 0;
+            v = max(wave_inclusive_max(v), carry);      // owner of slot 0 is marked: v >= 1
+            carry = bcast(v, 63);
+            const int owner = v - 1;
+            const int w = __builtin_amdgcn_ds_bpermute(owner << 2, word);
+            if (sidx < total) {
+                const int o = sidx - (w & 0x7ff);
+                const int c0 = (w >> 11) & 15;
+                const int q = o >= c0 ? 1 : 0;
+                const int seg = q ? (o - c0) + ((w >> 23) & 255) : o + ((w >> 15) & 255);
+                const int row = row0 + 2 * owner + q;
+                const int pi = (int)(((float)row + 0.5f) * inv_nr);
+                const int jr = row - pi * bx.nr;
+                reduce_slot<ALIGNED, WANT_VALUE>(p, Gc, a, s, step, azs, bx.ilo + pi, bx.jlo + jr,
+                                                 seg << 2, ox, oy, sx, sy, sz, sv);
+            }
+        }
+        lds_sync();
+        if (mine > 0) marks[excl] = 0;
+        lds_sync();
     }
 }
 
@@ -135,6 +237,10 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
     const int b = blockIdx.y, slot = (int)(blockIdx.x * 4u + (threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63u);
     const int N = p.N, T = p.T, D = gs.D;
+    __shared__ __attribute__((aligned(16))) unsigned char s_marks[4][kSlotCap];
+    unsigned char *marks = s_marks[threadIdx.x >> 6];
+    for (int k = lane; k < kSlotCap / 4; k += 64) reinterpret_cast<int *>(marks)[k] = 0;
+    lds_sync();
     const int4 last = p.meta[(size_t)b * T + (VECTOR ? 0 : T - 1)];
     if (slot >= last.x + last.z) return;            // past the last group's slots (per wavefront)
     const float4 a = p.rec[(size_t)b * N + slot];
@@ -154,7 +260,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
         float sx = 0.0f, sy = 0.0f, sz = 0.0f, sv = 0.0f;
         if (atom_box(gs, r * gs.c, a, ox, oy, oz, bx))
             reduce_channel<ALIGNED, false>(p, p.G + ((size_t)b * T + t) * D3, a, r, bx, ox,
-                                           oy, oz, sx, sy, sz, sv);
+                                           oy, oz, marks, sx, sy, sz, sv);
         const float inv_r2 = 1.0f / (r * p.sk);         // 1/r^2 times r/sqrt(k): the sums are in scaled units
         tx = wave_sum(sx) * inv_r2;
         ty = wave_sum(sy) * inv_r2;
@@ -167,7 +273,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
             Box bx;
             if (r > 0.0f && atom_box(gs, r * gs.c, a, ox, oy, oz, bx))
                 reduce_channel<ALIGNED, true>(p, p.G + ((size_t)b * T + t) * D3, a, r, bx,
-                                              ox, oy, oz, sx, sy, sz, sv);
+                                              ox, oy, oz, marks, sx, sy, sz, sv);
             const float inv_r2 = r > 0.0f ? 1.0f / (r * p.sk) : 0.0f;   // sums are in scaled units
             if (p.grad_coords) {
                 tx = fmaf(w * inv_r2, wave_sum(sx), tx);
@@ -226,6 +332,7 @@ hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace 
         const double k = 2.8853900817779268;    // 2 / ln 2
         p.sk = (float)std::sqrt(k);
         p.g2k = (float)((double)gs.g2 * k);
+        p.c2k = (float)((double)gs.c * (double)gs.c * k);
         p.A2 = (float)(2.0 * (double)gs.A);
         p.cAk2 = (float)(2.0 * (double)gs.A * (double)gs.c * std::sqrt(k));
         p.sAk = (float)std::sqrt((double)gs.A / k);

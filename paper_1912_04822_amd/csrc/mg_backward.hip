@@ -50,11 +50,25 @@ struct BwdParams {
     float sAk, cA;          // sqrt(A/k), c sqrt(A)
 };
 
+// v + (v of the lane the DPP control selects, 0 where there is none or the row is masked out)
+template <int CTRL, int ROW_MASK>
+__device__ inline float add_dpp(float v)
+{
+    return v + __int_as_float(
+                   __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+
+// Sum over the 64 lanes in a fixed order (an inclusive scan by DPP row shifts and row
+// broadcasts, whose last lane holds the total); returned in every lane.
 __device__ inline float wave_sum(float v)
 {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-    return v;
+    v = add_dpp<0x111, 0xf>(v);     // row_shr:1
+    v = add_dpp<0x112, 0xf>(v);     // row_shr:2
+    v = add_dpp<0x114, 0xf>(v);     // row_shr:4
+    v = add_dpp<0x118, 0xf>(v);     // row_shr:8
+    v = add_dpp<0x142, 0xa>(v);     // row_bcast:15 -> rows 1, 3
+    v = add_dpp<0x143, 0xc>(v);     // row_bcast:31 -> rows 2, 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 struct Box {
@@ -86,27 +100,38 @@ __device__ inline bool atom_box(const GridSpec &gs, float reach, const float4 &a
 // k = 2 log2(e) (then exp(-2x^2) = exp2(-x'^2)):  (sx, sy, sz) += sum G f u',  sv += sum G rho.
 //   f = -4 exp2(-x'^2)                   x'^2 <= g^2 k
 //     = min(2A - 2A c sqrt(k) / x', 0)   beyond (zero from the cutoff on)
-// One slot: the four voxels k4 .. k4+3 of row (i, j).
-template <bool ALIGNED, bool WANT_VALUE>
-__device__ inline void reduce_slot(const BwdParams &p, const float *Gc, const float4 &a, float s,
-                                   float step, float azs, int i, int j, int k4, float ox, float oy,
-                                   float &sx, float &sy, float &sz, float &sv)
+// One slot: the four voxels k4 .. k4+3 of the grid row at float offset `row_off` of the
+// channel (a channel has at most 2^30 floats); ux, uy: the row's scaled x and y distance.
+struct SlotData {
+    float gv[4];        // upstream gradient of the four voxels
+    float ux, uy;
+    int k4;
+};
+
+template <bool ALIGNED>
+__device__ inline void load_slot(const BwdParams &p, const float *Gc, unsigned row_off, int k4,
+                                 float ux, float uy, SlotData &d)
 {
-    const GridSpec &gs = p.gs;
-    const int D = gs.D;
-    const float *src = Gc + ((size_t)i * D + j) * D + k4;
-    float gv[4];
+    const float *src = Gc + (row_off + (unsigned)k4);
     if (ALIGNED) {
         const float4 g4 = *reinterpret_cast<const float4 *>(src);
-        gv[0] = g4.x; gv[1] = g4.y; gv[2] = g4.z; gv[3] = g4.w;
+        d.gv[0] = g4.x; d.gv[1] = g4.y; d.gv[2] = g4.z; d.gv[3] = g4.w;
     } else {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) gv[u] = (k4 + u < D) ? src[u] : 0.0f;
+        for (int u = 0; u < 4; ++u) d.gv[u] = (k4 + u < p.gs.D) ? src[u] : 0.0f;
     }
-    const float ux = (a.x - (ox + (float)i * gs.res)) * s;
-    const float uy = (a.y - (oy + (float)j * gs.res)) * s;
+    d.ux = ux; d.uy = uy; d.k4 = k4;
+}
+
+template <bool WANT_VALUE>
+__device__ inline void reduce_slot(const BwdParams &p, float step, float azs, const SlotData &d,
+                                   float &sx, float &sy, float &sz, float &sv)
+{
+    const float ux = d.ux, uy = d.uy;
+    const int k4 = d.k4;
+    const float *gv = d.gv;
     const float b2 = ux * ux + uy * uy;
-    const float uz0 = azs - (float)k4 * step;
+    const float uz0 = fmaf(-(float)k4, step, azs);
     float fsum = 0.0f;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -141,36 +166,52 @@ __device__ inline void reduce_channel_box(const BwdParams &p, const float *Gc, c
     const float inv_pp = 1.0f / (float)per_plane, inv_ns = 1.0f / (float)bx.ns;
     const float s = p.sk / r, step = gs.res * s;
     const float azs = (a.z - oz) * s;
+    // scaled distance of the box's first row; rows step by `step`
+    const float ux0 = (a.x - (ox + (float)bx.ilo * gs.res)) * s;
+    const float uy0 = (a.y - (oy + (float)bx.jlo * gs.res)) * s;
     for (int sl = (int)(threadIdx.x & 63u); sl < slots; sl += 64) {
         const int pi = (int)(((float)sl + 0.5f) * inv_pp);
         const int rem = sl - pi * per_plane;
         const int row = (int)(((float)rem + 0.5f) * inv_ns);
         const int seg = rem - row * bx.ns;
-        reduce_slot<ALIGNED, WANT_VALUE>(p, Gc, a, s, step, azs, bx.ilo + pi, bx.jlo + row,
-                                         (bx.seg0 + seg) << 2, ox, oy, sx, sy, sz, sv);
+        const float ux = fmaf(-(float)pi, step, ux0), uy = fmaf(-(float)row, step, uy0);
+        SlotData d;
+        load_slot<ALIGNED>(p, Gc, (unsigned)((bx.ilo + pi) * gs.D + bx.jlo + row) * (unsigned)gs.D,
+                           (bx.seg0 + seg) << 2, ux, uy, d);
+        reduce_slot<WANT_VALUE>(p, step, azs, d, sx, sy, sz, sv);
     }
 }
 
 // Only the slots that meet the cutoff sphere.  `marks` is this wavefront's kSlotCap bytes of
 // LDS, all zero on entry and on return.
+// The channel is G + t * D3; t may still be on its way from memory (index types read it
+// from the types array) and is not touched before the first slot is read.
 template <bool ALIGNED, bool WANT_VALUE>
-__device__ inline void reduce_channel(const BwdParams &p, const float *Gc, const float4 &a, float r,
-                                      const Box &bx, float ox, float oy, float oz,
-                                      unsigned char *marks, float &sx, float &sy, float &sz,
-                                      float &sv)
+__device__ inline void reduce_channel(const BwdParams &p, const float *G, int t, size_t D3,
+                                      const float4 &a, float r, const Box &bx, float ox, float oy,
+                                      float oz, unsigned char *marks, float &sx, float &sy,
+                                      float &sz, float &sv)
 {
     if (bx.ns > kMaxCulledSegs) {
-        reduce_channel_box<ALIGNED, WANT_VALUE>(p, Gc, a, r, bx, ox, oy, oz, sx, sy, sz, sv);
+        reduce_channel_box<ALIGNED, WANT_VALUE>(p, G + (size_t)t * D3, a, r, bx, ox, oy, oz, sx, sy,
+                                                sz, sv);
         return;
     }
     const GridSpec &gs = p.gs;
     const int lane = (int)(threadIdx.x & 63u);
     const int rows = bx.np * bx.nr;
-    const float inv_nr = 1.0f / (float)bx.nr;
-    const float s = p.sk / r, step = gs.res * s;
-    const float inv_step = 1.0f / step;
+    // reciprocals by the hardware approximation (1 ulp): the row split below has a margin of
+    // 0.5/nr and the scale enters the result with a relative error of 1e-7
+    const float inv_nr = __builtin_amdgcn_rcpf((float)bx.nr);
+    const float s = p.sk * __builtin_amdgcn_rcpf(r), step = gs.res * s;
+    const float inv_step = __builtin_amdgcn_rcpf(step);
     const float azs = (a.z - oz) * s;
     const float fz = (a.z - oz) * gs.inv_res;           // the atom's z in grid steps
+    // scaled distance of the box's first row; rows step by `step`
+    const float ux0 = (a.x - (ox + (float)bx.ilo * gs.res)) * s;
+    const float uy0 = (a.y - (oy + (float)bx.jlo * gs.res)) * s;
+    const unsigned D = (unsigned)gs.D;
+    const unsigned off0 = ((unsigned)bx.ilo * D + (unsigned)bx.jlo) * D;   // the box's first row
     for (int row0 = 0; row0 < rows; row0 += 128) {
         // this lane's two rows of the group: which segments meet the sphere
         int cnt[2] = {0, 0}, slo[2] = {0, 0};
@@ -180,8 +221,7 @@ __device__ inline void reduce_channel(const BwdParams &p, const float *Gc, const
             if (row < rows) {
                 const int pi = (int)(((float)row + 0.5f) * inv_nr);
                 const int jr = row - pi * bx.nr;
-                const float ux = (a.x - (ox + (float)(bx.ilo + pi) * gs.res)) * s;
-                const float uy = (a.y - (oy + (float)(bx.jlo + jr) * gs.res)) * s;
+                const float ux = fmaf(-(float)pi, step, ux0), uy = fmaf(-(float)jr, step, uy0);
                 const float h2 = p.c2k - (ux * ux + uy * uy);
                 if (h2 > 0.0f) {
                     // half chord in grid steps; the pad only adds voxels that contribute 0
@@ -204,6 +244,11 @@ __device__ inline void reduce_channel(const BwdParams &p, const float *Gc, const
         // segment of row 0 and of row 1 (8 each)
         const int word = excl | (cnt[0] << 11) | (slo[0] << 15) | (slo[1] << 23);
         lds_sync();
+        asm volatile("" : "+v"(t));     // nothing above waits for t
+        const float *Gc = G + (size_t)t * D3;
+        // Round k works on slots 64k .. 64k+63, one per lane.  (Issuing the read of round k+1
+        // before the arithmetic of round k was measured slower: the kernel is bound by
+        // instruction issue, and other wavefronts cover the wait.)
         int carry = 0;
         for (int base = 0; base < total; base += 64) {
             const int sidx = base + lane;
@@ -220,8 +265,11 @@ __device__ inline void reduce_channel(const BwdParams &p, const float *Gc, const
                 const int row = row0 + 2 * owner + q;
                 const int pi = (int)(((float)row + 0.5f) * inv_nr);
                 const int jr = row - pi * bx.nr;
-                reduce_slot<ALIGNED, WANT_VALUE>(p, Gc, a, s, step, azs, bx.ilo + pi, bx.jlo + jr,
-                                                 seg << 2, ox, oy, sx, sy, sz, sv);
+                const float ux = fmaf(-(float)pi, step, ux0), uy = fmaf(-(float)jr, step, uy0);
+                SlotData d;
+                load_slot<ALIGNED>(p, Gc, off0 + ((unsigned)pi * D + (unsigned)jr) * D, seg << 2, ux,
+                                   uy, d);
+                reduce_slot<WANT_VALUE>(p, step, azs, d, sx, sy, sz, sv);
             }
         }
         lds_sync();
@@ -234,23 +282,45 @@ template <bool VECTOR, bool ALIGNED>
 __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
 {
     const GridSpec &gs = p.gs;
-    const int b = blockIdx.y, slot = (int)(blockIdx.x * 4u + (threadIdx.x >> 6));
+    // The kernel arguments the first loads need are fetched together (they are inputs of an
+    // asm statement whose result, zero, enters the example index) instead of in several
+    // dependent trips to the scalar cache.
+    unsigned zero;
+    asm("s_mov_b32 %0, 0"
+        : "=s"(zero)
+        : "s"((unsigned long long)p.meta), "s"((unsigned long long)p.rec),
+          "s"((unsigned long long)p.idx), "s"((unsigned long long)p.gcen),
+          "s"((unsigned long long)p.rot), "s"(p.N), "s"(p.T));
+    const int b = (int)(blockIdx.y + zero), slot = (int)(blockIdx.x * 4u + (threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63u);
     const int N = p.N, T = p.T, D = gs.D;
     __shared__ __attribute__((aligned(16))) unsigned char s_marks[4][kSlotCap];
     unsigned char *marks = s_marks[threadIdx.x >> 6];
-    for (int k = lane; k < kSlotCap / 4; k += 64) reinterpret_cast<int *>(marks)[k] = 0;
+    static_assert(kSlotCap == 64 * 16, "one 16-byte store per lane clears the marks");
+    reinterpret_cast<int4 *>(marks)[lane] = make_int4(0, 0, 0, 0);
     lds_sync();
+    // Everything the wavefront needs first is requested in one go (one trip to memory, not
+    // four in a row): the group table's last entry, the record and its atom index (slot
+    // clamped into the array; whether the slot is live is decided afterwards), the grid
+    // centre and the rotation.
+    const int cslot = min(slot, N - 1);
     const int4 last = p.meta[(size_t)b * T + (VECTOR ? 0 : T - 1)];
+    const float4 a = p.rec[(size_t)b * N + cslot];
+    const int ai = p.idx[(size_t)b * N + cslot];
+    const float4 gc = *reinterpret_cast<const float4 *>(p.gcen + 4 * b);
+    const float *Rp = p.rot + b * 12;
+    const float4 Ra = *reinterpret_cast<const float4 *>(Rp);
+    const float4 Rb = *reinterpret_cast<const float4 *>(Rp + 4);
+    const float Rc = Rp[8];
+    asm volatile("" ::"s"(last.x), "s"(last.z), "s"(gc.x), "s"(gc.y), "s"(gc.z), "s"(Ra.x), "s"(Ra.y),
+                 "s"(Ra.z), "s"(Ra.w), "s"(Rb.x), "s"(Rb.y), "s"(Rb.z), "s"(Rb.w), "s"(Rc));
     if (slot >= last.x + last.z) return;            // past the last group's slots (per wavefront)
-    const float4 a = p.rec[(size_t)b * N + slot];
     if (!(a.w > 0.0f)) return;                      // dead record: the prep kernel wrote its zeros
-    const int ai = p.idx[(size_t)b * N + slot];
     const size_t D3 = (size_t)D * D * D;
     const int bs = source_example(p.subgrids, b);          // types and weights are the source example's
-    const float ox = p.gcen[4 * b + 0] - gs.half;
-    const float oy = p.gcen[4 * b + 1] - gs.half;
-    const float oz = p.gcen[4 * b + 2] - gs.half;
+    const float ox = gc.x - gs.half;
+    const float oy = gc.y - gs.half;
+    const float oz = gc.z - gs.half;
 
     float tx = 0.0f, ty = 0.0f, tz = 0.0f;          // gradient in the transformed frame
     if (!VECTOR) {
@@ -259,9 +329,9 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
         Box bx;
         float sx = 0.0f, sy = 0.0f, sz = 0.0f, sv = 0.0f;
         if (atom_box(gs, r * gs.c, a, ox, oy, oz, bx))
-            reduce_channel<ALIGNED, false>(p, p.G + ((size_t)b * T + t) * D3, a, r, bx, ox,
-                                           oy, oz, marks, sx, sy, sz, sv);
-        const float inv_r2 = 1.0f / (r * p.sk);         // 1/r^2 times r/sqrt(k): the sums are in scaled units
+            reduce_channel<ALIGNED, false>(p, p.G + (size_t)b * T * D3, t, D3, a, r, bx, ox, oy, oz,
+                                           marks, sx, sy, sz, sv);
+        const float inv_r2 = __builtin_amdgcn_rcpf(r * p.sk);    // 1/r^2 times r/sqrt(k): the sums are in scaled units
         tx = wave_sum(sx) * inv_r2;
         ty = wave_sum(sy) * inv_r2;
         tz = wave_sum(sz) * inv_r2;
@@ -272,9 +342,9 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
             float sx = 0.0f, sy = 0.0f, sz = 0.0f, sv = 0.0f;
             Box bx;
             if (r > 0.0f && atom_box(gs, r * gs.c, a, ox, oy, oz, bx))
-                reduce_channel<ALIGNED, true>(p, p.G + ((size_t)b * T + t) * D3, a, r, bx,
-                                              ox, oy, oz, marks, sx, sy, sz, sv);
-            const float inv_r2 = r > 0.0f ? 1.0f / (r * p.sk) : 0.0f;   // sums are in scaled units
+                reduce_channel<ALIGNED, true>(p, p.G + (size_t)b * T * D3, t, D3, a, r, bx, ox, oy,
+                                              oz, marks, sx, sy, sz, sv);
+            const float inv_r2 = r > 0.0f ? __builtin_amdgcn_rcpf(r * p.sk) : 0.0f;    // sums are in scaled units
             if (p.grad_coords) {
                 tx = fmaf(w * inv_r2, wave_sum(sx), tx);
                 ty = fmaf(w * inv_r2, wave_sum(sy), ty);
@@ -287,11 +357,10 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
         }
     }
     if (lane == 0 && p.grad_coords) {
-        const float *R = p.rot + b * 12;
         float *o = p.grad_coords + ((size_t)b * N + ai) * 3;
-        o[0] = (R[0] * tx + R[3] * ty) + R[6] * tz;
-        o[1] = (R[1] * tx + R[4] * ty) + R[7] * tz;
-        o[2] = (R[2] * tx + R[5] * ty) + R[8] * tz;
+        o[0] = (Ra.x * tx + Ra.w * ty) + Rb.z * tz;         // R^T: column m of R
+        o[1] = (Ra.y * tx + Rb.x * ty) + Rb.w * tz;
+        o[2] = (Ra.z * tx + Rb.y * ty) + Rc * tz;
     }
 }
 

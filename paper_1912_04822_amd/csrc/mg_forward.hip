@@ -399,46 +399,37 @@ __device__ inline void store_tile(const TileCtx &cx, float *dst, bool touched, b
     }
 }
 
-template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS, int NW>
-__global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
-{
-    extern __shared__ __attribute__((aligned(16))) float lds[];   // tile | marks per wave | shared
+// Where a tile lies: floats [f0, f1) of the channel = rows [R0, R1) of its D*D rows, which
+// belong to x-planes i_lo .. i_hi.
+struct TileGeom {
+    int f0, f1, R0, R1, i_lo, i_hi;
+};
 
-    // One workgroup per tile.  Workgroup ids go round the 8 XCDs (id % 8), each with its
-    // own L2: runs of consecutive tiles, which read the same atom records, can be given
-    // to one XCD.
+template <int ITERS>
+__device__ inline TileGeom tile_geom(const FwdParams &p, int D, unsigned tile_in_chan)
+{
+    TileGeom g;
+    const int total = D * D * D;
+    g.f0 = (int)tile_in_chan * (ITERS * 512);
+    g.f1 = min(total, g.f0 + ITERS * 512);
+    g.R0 = div_by_d(g.f0, p.div_magic);
+    g.R1 = div_by_d(g.f1 - 1, p.div_magic) + 1;
+    g.i_lo = div_by_d(g.R0, p.div_magic);
+    g.i_hi = div_by_d(g.R1 - 1, p.div_magic);
+    return g;
+}
+
+// One tile of channel (b, t): the records [r0, r1) of the example can reach it; cen is the
+// grid centre.
+template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS, int NW>
+__device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b, int t,
+                                          const TileGeom &tg, int r0, int r1, const float4 &cen)
+{
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const GridSpec &gs = p.gs;
     const int D = gs.D, T = p.T, N = p.N;
-    // Every kernel argument the preamble needs is fetched now, in one go, instead of in five
-    // dependent trips to the scalar cache spread over the preamble: they are inputs of an
-    // asm statement whose result (zero) enters the very first computation.  (Not `asm
-    // volatile`: after one, the compiler no longer uses scalar loads for the spans.)
-    unsigned zero;
-    asm("s_mov_b32 %0, 0"
-        : "=s"(zero)
-        : "s"((unsigned long long)p.range), "s"((unsigned long long)p.rec),
-          "s"((unsigned long long)p.gcen), "s"((unsigned long long)p.out), "s"(p.tiles_magic),
-          "s"(p.t_magic), "s"(p.div_magic), "s"(p.tiles), "s"(p.xcd_shift), "s"(p.n_remap), "s"(D),
-          "s"(T), "s"(N), "s"(p.debug), "s"(gs.half));
-    unsigned u = blockIdx.x + zero;
-    if (p.xcd_shift >= 0 && u < p.n_remap) {
-        const unsigned xcd = u & 7u, slot = u >> 3, sh = (unsigned)p.xcd_shift;
-        u = ((slot >> sh) << (sh + 3)) + (xcd << sh) + (slot & ((1u << sh) - 1u));
-    }
-    const unsigned chan = div_u32(u, p.tiles_magic);
-    const unsigned tile_in_chan = u - chan * p.tiles;
-    const int b = (int)div_u32(chan, p.t_magic);
-    const int t = (int)chan - b * T;
-
-    // the tile: floats [f0, f1) of the channel = rows [R0, R1) of its D*D rows, the first
-    // from column c0 on, the last up to column c1
     const int total = D * D * D;
-    const int f0 = (int)tile_in_chan * (ITERS * 512);
-    const int f1 = min(total, f0 + ITERS * 512);
-    const int R0 = div_by_d(f0, p.div_magic), R1 = div_by_d(f1 - 1, p.div_magic) + 1;
-    const int i_lo = div_by_d(R0, p.div_magic), i_hi = div_by_d(R1 - 1, p.div_magic);
-
+    const int f0 = tg.f0, f1 = tg.f1, R0 = tg.R0, R1 = tg.R1, i_lo = tg.i_lo, i_hi = tg.i_hi;
     TileCtx cx;
     cx.tile = lds;
     cx.marks = reinterpret_cast<unsigned char *>(lds + ITERS * 512) + wave * kTaskCap;
@@ -458,31 +449,13 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     cx.debug = p.debug;
 
     float *dst = p.out + ((size_t)b * T + t) * (size_t)total + f0;
-    if (p.debug == 3) {         // timing aid: nothing but the zero stores
-        store_tile<ALIGNED, ITERS, NW>(cx, dst, false, false);
-        return;
-    }
-    const size_t group = (size_t)b * T + (VECTOR ? 0 : t);
-    // One 32-byte entry written by the prep kernel holds what the tile needs first (one
-    // scalar load, one trip to L2, which is slow while the chip streams stores): the span
-    // of records that can reach the tile's planes and the grid origin.
-    // All the scalar loads of the preamble are issued together (one trip to L2, which is
-    // slow while the chip streams stores): the span of records that can reach planes
-    // i_lo .. i_hi (counted from the example's first record) and the grid centre.
-    const int2 *span = p.range + group * D;
-    const float4 cen = *reinterpret_cast<const float4 *>(p.gcen + 4 * b);   // one 16-byte load
-    const int r0 = span[i_lo].x;
-    int r1 = span[i_hi].y;
-    const float cen_x = cen.x, cen_y = cen.y, cen_z = cen.z;
-    asm volatile("" ::"s"(r0), "s"(r1), "s"(cen_x), "s"(cen_y), "s"(cen_z));  // all in flight before the first wait
-    cx.cen_x = cen_x;
-    cx.cen_y = cen_y;
-    cx.cen_z = cen_z;
+    cx.cen_x = cen.x;
+    cx.cen_y = cen.y;
+    cx.cen_z = cen.z;
     cx.hD = 0.5f * (float)(D - 1);
     const float ox = cx.cen_x - gs.half;
     cx.oy = cx.cen_y - gs.half;
     cx.oz = cx.cen_z - gs.half;
-    if (p.debug == 2) r1 = r0;
     const float r_chan = VECTOR ? gs.radius_scale * p.radii[t] : 0.0f;
 
     const float4 *rec = p.rec + (size_t)b * N + r0;
@@ -616,6 +589,54 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     store_tile<ALIGNED, ITERS, NW>(cx, dst, any, fixed);
 }
 
+
+// One workgroup per tile.
+template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS, int NW>
+__global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];   // tile | marks per wave | shared
+
+    // Workgroup ids go round the 8 XCDs (id % 8), each with its own L2: runs of consecutive
+    // tiles, which read the same atom records, can be given to one XCD.
+    const GridSpec &gs = p.gs;
+    const int D = gs.D, T = p.T, N = p.N;
+    // Every kernel argument the preamble needs is fetched now, in one go, instead of in five
+    // dependent trips to the scalar cache spread over the preamble: they are inputs of an
+    // asm statement whose result (zero) enters the very first computation.  (Not `asm
+    // volatile`: after one, the compiler no longer uses scalar loads for the spans.)
+    unsigned zero;
+    asm("s_mov_b32 %0, 0"
+        : "=s"(zero)
+        : "s"((unsigned long long)p.range), "s"((unsigned long long)p.rec),
+          "s"((unsigned long long)p.gcen), "s"((unsigned long long)p.out), "s"(p.tiles_magic),
+          "s"(p.t_magic), "s"(p.div_magic), "s"(p.tiles), "s"(p.xcd_shift), "s"(p.n_remap), "s"(D),
+          "s"(T), "s"(N), "s"(p.debug), "s"(gs.half));
+    unsigned u = blockIdx.x + zero;
+    if (p.xcd_shift >= 0 && u < p.n_remap) {
+        const unsigned xcd = u & 7u, slot = u >> 3, sh = (unsigned)p.xcd_shift;
+        u = ((slot >> sh) << (sh + 3)) + (xcd << sh) + (slot & ((1u << sh) - 1u));
+    }
+    const unsigned chan = div_u32(u, p.tiles_magic);
+    const unsigned tile_in_chan = u - chan * p.tiles;
+    const int b = (int)div_u32(chan, p.t_magic);
+    const int t = (int)chan - b * T;
+    const size_t group = (size_t)b * T + (VECTOR ? 0 : t);
+    // All the scalar loads of the preamble are issued together (one trip to L2, which is
+    // slow while the chip streams stores): the span of records that can reach the planes
+    // of the tile (counted from the example's first record) and the grid centre.
+    const int2 *span = p.range + group * D;
+    const float4 cen = *reinterpret_cast<const float4 *>(p.gcen + 4 * b);   // one 16-byte load
+    const TileGeom tg = tile_geom<ITERS>(p, D, tile_in_chan);
+    int r0 = 0, r1 = 0;
+    if (p.debug != 3) {         // debug 3, a timing aid: nothing but the zero stores
+        r0 = span[tg.i_lo].x;
+        r1 = span[tg.i_hi].y;
+    }
+    asm volatile("" ::"s"(r0), "s"(r1), "s"(cen.x), "s"(cen.y), "s"(cen.z));  // all in flight before the first wait
+    if (p.debug == 2) r1 = r0;
+    tile_body<VECTOR, BINARY, ALIGNED, ITERS, NW>(p, lds, b, t, tg, r0, r1, cen);
+}
+
 }  // namespace
 
 ForwardGeometry forward_geometry(int D, int tile_floats)
@@ -654,6 +675,8 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     p.subgrids = bt.sub.count; p.N = bt.N; p.T = bt.T;
     p.tile_floats = fg.tile_floats;
     p.div_magic = ((1ULL << 40) + (unsigned long long)gs.D - 1ULL) / (unsigned long long)gs.D;
+    const int iters = tile_floats / 512;
+    const int nw = waves_per_tile < iters ? waves_per_tile : iters;
     p.tiles = (unsigned)fg.tiles;
     p.tiles_magic = magic64((unsigned)fg.tiles);
     p.t_magic = magic64((unsigned)bt.T);
@@ -674,8 +697,6 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     p.c2k = (float)((double)gs.c * (double)gs.c * k);
     p.sA = (float)std::sqrt((double)gs.A / k);
     p.cA = (float)((double)gs.c * std::sqrt((double)gs.A));
-    const int iters = tile_floats / 512;
-    const int nw = waves_per_tile < iters ? waves_per_tile : iters;
     // tile | marks of each wavefront | shared words; lds_floor raises the request to cap how
     // many tiles are resident on a CU (the store pattern wants about 12 tiles of 8 KB)
     size_t lds_bytes = (size_t)tile_floats * sizeof(float) + (size_t)nw * kTaskCap + 16;

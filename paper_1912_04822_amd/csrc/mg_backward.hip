@@ -19,7 +19,7 @@
 // running maximum over the slots gives the owner) and one register exchange.
 // The kernel is bound by vector arithmetic (two transcendentals per voxel), so
 // the time goes with the number of voxels evaluated.  The three partial sums
-// are reduced with wavefront shuffles in a fixed order.  Records are grouped by
+// are reduced across the wavefront by DPP adds in a fixed order.  Records are grouped by
 // channel (and, within a channel, by x-plane), so neighbouring wavefronts read
 // the same part of the same channel volume.
 #include <cmath>

@@ -104,3 +104,37 @@ def test_subgrid_gridmaker_rejects_bad_counts(mg):
     gm = mg.GridMaker(0.5, 11.5, radius_type_indexed=True, subgrids_per_side=16)
     with pytest.raises(mg.MolgridError):
         gm.workspace_bytes(16, 10, 4)          # 16 * 4096 virtual examples > 65535
+
+
+@pytest.mark.parametrize("N,single_type", [(9000, False), (9000, True)])
+def test_subgrids_with_the_per_group_prep_kernel_and_per_atom_radii(mg, N, single_type):
+    """N = 9000 takes the slower prep kernel (one wavefront per example and type; with a single
+    type the group is not binned at all); radii given per atom; natoms ragged."""
+    w = workloads.ragged_small(seed=12, B=2, N=N, T=3, D=8, resolution=0.5)
+    if single_type:
+        w.types[:] = 2
+    S = 2
+    nat = np.array([N, N - 411], np.int32)
+    per_atom = w.radii[np.clip(w.types, 0, w.T - 1)]
+    gm = mg.GridMaker(w.resolution, w.dimension, radius_type_indexed=False, subgrids_per_side=S)
+    out = gm.mg_forward_index(dev(w.coords), dev(w.types), dev(per_atom), w.T, natoms=dev(nat),
+                              **dposes(w)).cpu().numpy()
+    ref = oracle.forward_subgrids(w.coords, per_atom, S, w.resolution, w.dimension, T=w.T,
+                                  types=w.types, natoms=nat, radius_type_indexed=False, **poses(w))
+    assert np.abs(out - ref).max() <= GRID_TOL + 2e-6 * ref.max()
+    gmb = mg.GridMaker(w.resolution, w.dimension, binary=True, radius_type_indexed=False,
+                       subgrids_per_side=S)
+    outb = gmb.mg_forward_index(dev(w.coords), dev(w.types), dev(per_atom), w.T, natoms=dev(nat),
+                                **dposes(w)).cpu().numpy()
+    refb = oracle.forward_subgrids(w.coords, per_atom, S, w.resolution, w.dimension, T=w.T,
+                                   types=w.types, natoms=nat, binary=True,
+                                   radius_type_indexed=False, **poses(w))
+    assert np.array_equal(outb.view(np.uint32), refb.view(np.uint32))
+    rng = np.random.default_rng(3)
+    G = rng.standard_normal(ref.shape).astype(np.float32)
+    g = gm.mg_backward_index(dev(w.coords), dev(w.types), dev(per_atom), w.T, dev(G),
+                             natoms=dev(nat), **dposes(w)).cpu().numpy()
+    rg = oracle.backward_subgrids(w.coords, per_atom, S, w.resolution, w.dimension, G, T=w.T,
+                                  types=w.types, natoms=nat, radius_type_indexed=False, **poses(w))
+    for b in range(w.B):
+        assert np.abs(g[b] - rg[b]).max() <= GRAD_RTOL * np.abs(rg[b]).max()

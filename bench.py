@@ -225,6 +225,23 @@ def main():
         add("backward_vector", lambda: gm.mg_backward_vector(
             coords, weights, radii, G, centers=centers, quats=quats, translations=trans,
             grad_coords=gc, grad_weights=gw, workspace=ws), w.out_bytes, k)
+        # one 16-example chunk of the large / high-resolution configuration (96^3 at 0.25 A,
+        # 8000 atoms per example); freed first: the chunk's grid is 1.6 GB
+        del out, ws, gw, G, weights
+        torch.cuda.empty_cache()
+        wc = workloads.large_chunk(0)
+        gmc = molgrid.GridMaker(wc.resolution, wc.dimension, radius_type_indexed=True)
+        outc = torch.empty(wc.out_shape, dtype=torch.float32, device="cuda")
+        wsc = torch.empty(gmc.workspace_bytes(wc.B, wc.N, wc.T), dtype=torch.uint8, device="cuda")
+        cc, tc, rc = dev(wc.coords), dev(wc.types), dev(wc.radii)
+        cec, qc, trc = dev(wc.centers), dev(wc.quats), dev(wc.translations)
+        ms, mk, _ = time_call(torch, molgrid, lambda: gmc.mg_forward_index(
+            cc, tc, rc, wc.T, centers=cec, quats=qc, translations=trc, out=outc, workspace=wsc),
+            max(20, args.steps // 4), 20)
+        rows["forward_large_chunk"] = {
+            "ms_per_call": ms, "kernel_ms_avg": mk, "grids_per_s": wc.B / (ms * 1e-3),
+            "algorithmic_GBs": wc.out_bytes / (mk * 1e-3) / 1e9,
+            "workload": "configs[4], one chunk: B=16, N=8000, T=28, 96^3 @0.25A"}
         result["rows"] = rows
 
     if not args.no_cpu:

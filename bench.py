@@ -215,6 +215,11 @@ def main():
                                 translations=ta, out=out, workspace=ws)
 
         add("forward_augmented", augmented, w.out_bytes, args.steps)
+        out64 = torch.empty(w.out_shape, dtype=torch.float64, device="cuda")
+        add("forward_index_f64", lambda: gm.mg_forward_index(
+            coords, types, radii, w.T, centers=centers, quats=quats, translations=trans, out=out64,
+            workspace=ws), 2 * w.out_bytes, max(20, args.steps // 4))
+        del out64
         add("forward_vector", lambda: gm.mg_forward_vector(
             coords, weights, radii, centers=centers, quats=quats, translations=trans, out=out,
             workspace=ws), w.out_bytes, k)

@@ -48,7 +48,7 @@ enum {
     MG_EWORKSPACE = -4,  /* workspace NULL, misaligned or too small             */
     MG_EHIP = -5,        /* the HIP runtime refused a launch (see mg_last_hip_error) */
     MG_EMODE = -6,       /* call not defined for this GridMaker (e.g. backward in binary mode) */
-    MG_EALIGN = -7       /* a float / int array is not 4-byte aligned            */
+    MG_EALIGN = -7       /* a float / int array is not 4-byte (double: 8-byte) aligned */
 };
 
 #define MG_MAX_POINTS 1024      /* largest supported D (points per side) */
@@ -201,6 +201,37 @@ int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T,
                        const float *translations, const float *grad_out,
                        float *grad_coords, float *grad_weights,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The same four calls with the grid held in doubles (the paper's grids come
+ * in float and double flavours, e.g. a 5-dimensional double grid on the
+ * device): out / grad_out are [B][T][D][D][D] double (8-byte aligned); all
+ * other arrays, the arithmetic and the results' accuracy are as above (the
+ * path computes in float; a double grid holds the same values widened, and
+ * a double gradient is narrowed to float as it is read).
+ */
+int mg_forward_index_f64(const mg_gridmaker *gm, int B, int N, int T,
+                         const float *coords, const int32_t *types, const float *radii,
+                         const int32_t *natoms, const float *centers, const float *quats,
+                         const float *translations, double *out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+int mg_forward_vector_f64(const mg_gridmaker *gm, int B, int N, int T,
+                          const float *coords, const float *weights, const float *radii,
+                          const int32_t *natoms, const float *centers, const float *quats,
+                          const float *translations, double *out,
+                          void *workspace, size_t workspace_bytes, void *stream);
+int mg_backward_index_f64(const mg_gridmaker *gm, int B, int N, int T,
+                          const float *coords, const int32_t *types, const float *radii,
+                          const int32_t *natoms, const float *centers, const float *quats,
+                          const float *translations, const double *grad_out,
+                          float *grad_coords,
+                          void *workspace, size_t workspace_bytes, void *stream);
+int mg_backward_vector_f64(const mg_gridmaker *gm, int B, int N, int T,
+                           const float *coords, const float *weights, const float *radii,
+                           const int32_t *natoms, const float *centers, const float *quats,
+                           const float *translations, const double *grad_out,
+                           float *grad_coords, float *grad_weights,
+                           void *workspace, size_t workspace_bytes, void *stream);
 
 /* Text for an MG_* code (static storage). */
 const char *mg_strerror(int code);

@@ -191,28 +191,51 @@ int mg_draw_transforms(uint64_t seed, uint64_t draw, int B, int random_rotation,
                                                  (hipStream_t)stream));
 }
 
+// Forward with either kind of types (types or weights is NULL) into a float or double grid.
+static int forward_call(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
+                        const int32_t *types, const float *weights, const float *radii,
+                        const int32_t *natoms, const float *centers, const float *quats,
+                        const float *translations, void *out, bool out_is_double, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    if (!gm || !coords || (!types && !weights) || !radii || !out) return MG_ENULL;
+    if (weights && !gm->gs.radius_type_indexed) return MG_EMODE;    // vector types need radii per type
+    int rc = check_shape(gm, B, N, T);
+    if (rc != MG_OK) return rc;
+    if (misaligned4(coords) || misaligned4(types) || misaligned4(weights) || misaligned4(radii) ||
+        misaligned4(natoms) || misaligned4(centers) || misaligned4(quats) ||
+        misaligned4(translations) || ((uintptr_t)out & (out_is_double ? 7u : 3u)) != 0)
+        return MG_EALIGN;
+    rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
+    if (rc != MG_OK) return rc;
+    const mg::Batch bt = make_batch(gm, B, N, T, coords, types, weights, radii, natoms, centers,
+                                    quats, translations);
+    const mg::Workspace ws = mg::carve_workspace(gm->gs, gm->sub.count, workspace, bt.B, N, T);
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
+    if (rc != MG_OK) return rc;
+    return hip_status(mg::launch_forward(gm->gs, bt, ws, out, out_is_double, g_tile_floats,
+                                         g_waves_per_tile, g_xcd_run, g_lds_floor, g_debug,
+                                         take_events(), (hipStream_t)stream));
+}
+
 int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
                      const int32_t *types, const float *radii, const int32_t *natoms,
                      const float *centers, const float *quats, const float *translations,
                      float *out, void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!gm || !coords || !types || !radii || !out) return MG_ENULL;
-    int rc = check_shape(gm, B, N, T);
-    if (rc != MG_OK) return rc;
-    if (misaligned4(coords) || misaligned4(types) || misaligned4(radii) || misaligned4(out) ||
-        misaligned4(natoms) || misaligned4(centers) || misaligned4(quats) ||
-        misaligned4(translations))
-        return MG_EALIGN;
-    rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
-    if (rc != MG_OK) return rc;
-    const mg::Batch bt = make_batch(gm, B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
-                                    translations);
-    const mg::Workspace ws = mg::carve_workspace(gm->gs, gm->sub.count, workspace, bt.B, N, T);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
-    if (rc != MG_OK) return rc;
-    return hip_status(mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_waves_per_tile,
-                                         g_xcd_run, g_lds_floor, g_debug, take_events(),
-                                         (hipStream_t)stream));
+    if (!types) return MG_ENULL;
+    return forward_call(gm, B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
+                        translations, out, false, workspace, workspace_bytes, stream);
+}
+
+int mg_forward_index_f64(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
+                         const int32_t *types, const float *radii, const int32_t *natoms,
+                         const float *centers, const float *quats, const float *translations,
+                         double *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!types) return MG_ENULL;
+    return forward_call(gm, B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
+                        translations, out, true, workspace, workspace_bytes, stream);
 }
 
 int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
@@ -220,84 +243,53 @@ int mg_forward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *
                       const float *centers, const float *quats, const float *translations,
                       float *out, void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!gm || !coords || !weights || !radii || !out) return MG_ENULL;
-    if (!gm->gs.radius_type_indexed) return MG_EMODE;     // vector types need radii per type
-    int rc = check_shape(gm, B, N, T);
-    if (rc != MG_OK) return rc;
-    if (misaligned4(coords) || misaligned4(weights) || misaligned4(radii) || misaligned4(out) ||
-        misaligned4(natoms) || misaligned4(centers) || misaligned4(quats) ||
-        misaligned4(translations))
-        return MG_EALIGN;
-    rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
-    if (rc != MG_OK) return rc;
-    const mg::Batch bt = make_batch(gm, B, N, T, coords, nullptr, weights, radii, natoms, centers,
-                                    quats, translations);
-    const mg::Workspace ws = mg::carve_workspace(gm->gs, gm->sub.count, workspace, bt.B, N, T);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
-    if (rc != MG_OK) return rc;
-    return hip_status(mg::launch_forward(gm->gs, bt, ws, out, g_tile_floats, g_waves_per_tile,
-                                         g_xcd_run, g_lds_floor, g_debug, take_events(),
-                                         (hipStream_t)stream));
+    if (!weights) return MG_ENULL;
+    return forward_call(gm, B, N, T, coords, nullptr, weights, radii, natoms, centers, quats,
+                        translations, out, false, workspace, workspace_bytes, stream);
 }
 
-int mg_backward_index(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
-                      const int32_t *types, const float *radii, const int32_t *natoms,
-                      const float *centers, const float *quats, const float *translations,
-                      const float *grad_out, float *grad_coords, void *workspace,
-                      size_t workspace_bytes, void *stream)
+int mg_forward_vector_f64(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
+                          const float *weights, const float *radii, const int32_t *natoms,
+                          const float *centers, const float *quats, const float *translations,
+                          double *out, void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!gm || !coords || !types || !radii || !grad_out || !grad_coords) return MG_ENULL;
-    if (gm->gs.binary) return MG_EMODE;
+    if (!weights) return MG_ENULL;
+    return forward_call(gm, B, N, T, coords, nullptr, weights, radii, natoms, centers, quats,
+                        translations, out, true, workspace, workspace_bytes, stream);
+}
+
+// Backward with either kind of types from a float or double gradient grid.
+static int backward_call(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
+                         const int32_t *types, const float *weights, const float *radii,
+                         const int32_t *natoms, const float *centers, const float *quats,
+                         const float *translations, const void *grad_out, bool grad_is_double,
+                         float *grad_coords, float *grad_weights, void *workspace,
+                         size_t workspace_bytes, void *stream)
+{
+    if (!gm || !coords || (!types && !weights) || !radii || !grad_out) return MG_ENULL;
+    if (!grad_coords && !grad_weights) return MG_ENULL;
+    if (types && !grad_coords) return MG_ENULL;
+    if (gm->gs.binary || (weights && !gm->gs.radius_type_indexed)) return MG_EMODE;
     int rc = check_shape(gm, B, N, T);
     if (rc != MG_OK) return rc;
-    if (misaligned4(coords) || misaligned4(types) || misaligned4(radii) || misaligned4(grad_out) ||
-        misaligned4(grad_coords) || misaligned4(natoms) || misaligned4(centers) ||
-        misaligned4(quats) || misaligned4(translations))
+    if (misaligned4(coords) || misaligned4(types) || misaligned4(weights) || misaligned4(radii) ||
+        misaligned4(grad_coords) || misaligned4(grad_weights) || misaligned4(natoms) ||
+        misaligned4(centers) || misaligned4(quats) || misaligned4(translations) ||
+        ((uintptr_t)grad_out & (grad_is_double ? 7u : 3u)) != 0)
         return MG_EALIGN;
     rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
     if (rc != MG_OK) return rc;
-    const mg::Batch bt = make_batch(gm, B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
-                                    translations);
+    const mg::Batch bt = make_batch(gm, B, N, T, coords, types, weights, radii, natoms, centers,
+                                    quats, translations);
     const mg::Workspace ws = mg::carve_workspace(gm->gs, gm->sub.count, workspace, bt.B, N, T);
     // with subgrids each virtual example's gradient goes to the workspace and they are summed
-    float *gc = gm->sub.count > 1 ? ws.gtmp : grad_coords;
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, gc, nullptr, (hipStream_t)stream));
-    if (rc != MG_OK) return rc;
-    rc = hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, gc, nullptr, take_events(),
-                                        (hipStream_t)stream));
-    if (rc != MG_OK || gm->sub.count == 1) return rc;
-    return hip_status(mg::launch_sum_subgrids(gm->sub.count, B, (size_t)N * 3, gc, grad_coords,
-                                              (hipStream_t)stream));
-}
-
-int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
-                       const float *weights, const float *radii, const int32_t *natoms,
-                       const float *centers, const float *quats, const float *translations,
-                       const float *grad_out, float *grad_coords, float *grad_weights,
-                       void *workspace, size_t workspace_bytes, void *stream)
-{
-    if (!gm || !coords || !weights || !radii || !grad_out) return MG_ENULL;
-    if (!grad_coords && !grad_weights) return MG_ENULL;
-    if (gm->gs.binary || !gm->gs.radius_type_indexed) return MG_EMODE;
-    int rc = check_shape(gm, B, N, T);
-    if (rc != MG_OK) return rc;
-    if (misaligned4(coords) || misaligned4(weights) || misaligned4(radii) ||
-        misaligned4(grad_out) || misaligned4(grad_coords) || misaligned4(grad_weights) ||
-        misaligned4(natoms) || misaligned4(centers) || misaligned4(quats) ||
-        misaligned4(translations))
-        return MG_EALIGN;
-    rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
-    if (rc != MG_OK) return rc;
-    const mg::Batch bt = make_batch(gm, B, N, T, coords, nullptr, weights, radii, natoms, centers,
-                                    quats, translations);
-    const mg::Workspace ws = mg::carve_workspace(gm->gs, gm->sub.count, workspace, bt.B, N, T);
     const bool sub = gm->sub.count > 1;
     float *gc = (sub && grad_coords) ? ws.gtmp : grad_coords;
     float *gw = (sub && grad_weights) ? ws.wtmp : grad_weights;
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, gc, gw, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
-    rc = hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, gc, gw, take_events(),
-                                        (hipStream_t)stream));
+    rc = hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, grad_is_double, gc, gw,
+                                        take_events(), (hipStream_t)stream));
     if (rc != MG_OK || !sub) return rc;
     if (grad_coords)
         rc = hip_status(mg::launch_sum_subgrids(gm->sub.count, B, (size_t)N * 3, gc, grad_coords,
@@ -306,6 +298,54 @@ int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T, const float 
         rc = hip_status(mg::launch_sum_subgrids(gm->sub.count, B, (size_t)N * T, gw, grad_weights,
                                                 (hipStream_t)stream));
     return rc;
+}
+
+int mg_backward_index(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
+                      const int32_t *types, const float *radii, const int32_t *natoms,
+                      const float *centers, const float *quats, const float *translations,
+                      const float *grad_out, float *grad_coords, void *workspace,
+                      size_t workspace_bytes, void *stream)
+{
+    if (!types) return MG_ENULL;
+    return backward_call(gm, B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
+                         translations, grad_out, false, grad_coords, nullptr, workspace,
+                         workspace_bytes, stream);
+}
+
+int mg_backward_index_f64(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
+                          const int32_t *types, const float *radii, const int32_t *natoms,
+                          const float *centers, const float *quats, const float *translations,
+                          const double *grad_out, float *grad_coords, void *workspace,
+                          size_t workspace_bytes, void *stream)
+{
+    if (!types) return MG_ENULL;
+    return backward_call(gm, B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
+                         translations, grad_out, true, grad_coords, nullptr, workspace,
+                         workspace_bytes, stream);
+}
+
+int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
+                       const float *weights, const float *radii, const int32_t *natoms,
+                       const float *centers, const float *quats, const float *translations,
+                       const float *grad_out, float *grad_coords, float *grad_weights,
+                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!weights) return MG_ENULL;
+    return backward_call(gm, B, N, T, coords, nullptr, weights, radii, natoms, centers, quats,
+                         translations, grad_out, false, grad_coords, grad_weights, workspace,
+                         workspace_bytes, stream);
+}
+
+int mg_backward_vector_f64(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
+                           const float *weights, const float *radii, const int32_t *natoms,
+                           const float *centers, const float *quats, const float *translations,
+                           const double *grad_out, float *grad_coords, float *grad_weights,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!weights) return MG_ENULL;
+    return backward_call(gm, B, N, T, coords, nullptr, weights, radii, natoms, centers, quats,
+                         translations, grad_out, true, grad_coords, grad_weights, workspace,
+                         workspace_bytes, stream);
 }
 
 const char *mg_strerror(int code)

@@ -41,7 +41,7 @@ struct BwdParams {
     const float *weights;
     const float *radii;
     const float *gcen;
-    const float *G;
+    const void *G;          // upstream gradient grid, float or double
     float *grad_coords;
     float *grad_weights;
     int subgrids, N, T;
@@ -108,17 +108,23 @@ struct SlotData {
     int k4;
 };
 
-template <bool ALIGNED>
-__device__ inline void load_slot(const BwdParams &p, const float *Gc, unsigned row_off, int k4,
+template <bool ALIGNED, typename GT>
+__device__ inline void load_slot(const BwdParams &p, const GT *Gc, unsigned row_off, int k4,
                                  float ux, float uy, SlotData &d)
 {
-    const float *src = Gc + (row_off + (unsigned)k4);
+    const GT *src = Gc + (row_off + (unsigned)k4);
     if (ALIGNED) {
-        const float4 g4 = *reinterpret_cast<const float4 *>(src);
-        d.gv[0] = g4.x; d.gv[1] = g4.y; d.gv[2] = g4.z; d.gv[3] = g4.w;
+        if (sizeof(GT) == 8) {      // a grid of doubles: two 16-byte loads, narrowed
+            const double2 lo = reinterpret_cast<const double2 *>(src)[0];
+            const double2 hi = reinterpret_cast<const double2 *>(src)[1];
+            d.gv[0] = (float)lo.x; d.gv[1] = (float)lo.y; d.gv[2] = (float)hi.x; d.gv[3] = (float)hi.y;
+        } else {
+            const float4 g4 = *reinterpret_cast<const float4 *>(src);
+            d.gv[0] = g4.x; d.gv[1] = g4.y; d.gv[2] = g4.z; d.gv[3] = g4.w;
+        }
     } else {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) d.gv[u] = (k4 + u < p.gs.D) ? src[u] : 0.0f;
+        for (int u = 0; u < 4; ++u) d.gv[u] = (k4 + u < p.gs.D) ? (float)src[u] : 0.0f;
     }
     d.ux = ux; d.uy = uy; d.k4 = k4;
 }
@@ -155,8 +161,8 @@ __device__ inline void reduce_slot(const BwdParams &p, float step, float azs, co
 }
 
 // Every slot of the box (boxes with very many segments per row).
-template <bool ALIGNED, bool WANT_VALUE>
-__device__ inline void reduce_channel_box(const BwdParams &p, const float *Gc, const float4 &a,
+template <bool ALIGNED, bool WANT_VALUE, typename GT>
+__device__ inline void reduce_channel_box(const BwdParams &p, const GT *Gc, const float4 &a,
                                           float r, const Box &bx, float ox, float oy, float oz,
                                           float &sx, float &sy, float &sz, float &sv)
 {
@@ -186,8 +192,8 @@ __device__ inline void reduce_channel_box(const BwdParams &p, const float *Gc, c
 // LDS, all zero on entry and on return.
 // The channel is G + t * D3; t may still be on its way from memory (index types read it
 // from the types array) and is not touched before the first slot is read.
-template <bool ALIGNED, bool WANT_VALUE>
-__device__ inline void reduce_channel(const BwdParams &p, const float *G, int t, size_t D3,
+template <bool ALIGNED, bool WANT_VALUE, typename GT>
+__device__ inline void reduce_channel(const BwdParams &p, const GT *G, int t, size_t D3,
                                       const float4 &a, float r, const Box &bx, float ox, float oy,
                                       float oz, unsigned char *marks, float &sx, float &sy,
                                       float &sz, float &sv)
@@ -245,7 +251,7 @@ __device__ inline void reduce_channel(const BwdParams &p, const float *G, int t,
         const int word = excl | (cnt[0] << 11) | (slo[0] << 15) | (slo[1] << 23);
         lds_sync();
         asm volatile("" : "+v"(t));     // nothing above waits for t
-        const float *Gc = G + (size_t)t * D3;
+        const GT *Gc = G + (size_t)t * D3;
         // Round k works on slots 64k .. 64k+63, one per lane.  (Issuing the read of round k+1
         // before the arithmetic of round k was measured slower: the kernel is bound by
         // instruction issue, and other wavefronts cover the wait.)
@@ -278,7 +284,7 @@ __device__ inline void reduce_channel(const BwdParams &p, const float *G, int t,
     }
 }
 
-template <bool VECTOR, bool ALIGNED>
+template <bool VECTOR, bool ALIGNED, typename GT>
 __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
 {
     const GridSpec &gs = p.gs;
@@ -329,7 +335,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
         Box bx;
         float sx = 0.0f, sy = 0.0f, sz = 0.0f, sv = 0.0f;
         if (atom_box(gs, r * gs.c, a, ox, oy, oz, bx))
-            reduce_channel<ALIGNED, false>(p, p.G + (size_t)b * T * D3, t, D3, a, r, bx, ox, oy, oz,
+            reduce_channel<ALIGNED, false>(p, reinterpret_cast<const GT *>(p.G) + (size_t)b * T * D3, t, D3, a, r, bx, ox, oy, oz,
                                            marks, sx, sy, sz, sv);
         const float inv_r2 = __builtin_amdgcn_rcpf(r * p.sk);    // 1/r^2 times r/sqrt(k): the sums are in scaled units
         tx = wave_sum(sx) * inv_r2;
@@ -342,7 +348,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
             float sx = 0.0f, sy = 0.0f, sz = 0.0f, sv = 0.0f;
             Box bx;
             if (r > 0.0f && atom_box(gs, r * gs.c, a, ox, oy, oz, bx))
-                reduce_channel<ALIGNED, true>(p, p.G + (size_t)b * T * D3, t, D3, a, r, bx, ox, oy,
+                reduce_channel<ALIGNED, true>(p, reinterpret_cast<const GT *>(p.G) + (size_t)b * T * D3, t, D3, a, r, bx, ox, oy,
                                               oz, marks, sx, sy, sz, sv);
             const float inv_r2 = r > 0.0f ? __builtin_amdgcn_rcpf(r * p.sk) : 0.0f;    // sums are in scaled units
             if (p.grad_coords) {
@@ -388,8 +394,8 @@ hipError_t launch_sum_subgrids(int subgrid_count, int B_source, size_t per_examp
 }
 
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
-                           const float *grad_out, float *grad_coords, float *grad_weights,
-                           KernelEvents ev, hipStream_t stream)
+                           const void *grad_out, bool grad_is_double, float *grad_coords,
+                           float *grad_weights, KernelEvents ev, hipStream_t stream)
 {
     BwdParams p;
     p.gs = gs;
@@ -409,13 +415,19 @@ hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace 
     }
     const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)grad_out & 15u) == 0);
     const dim3 grd((bt.N + 3) / 4, bt.B), blk(256);
-    if (bt.weights) {
-        if (aligned) hipExtLaunchKernelGGL((backward_kernel<true, true>), grd, blk, 0, stream, ev.start, ev.stop, 0, p);
-        else hipExtLaunchKernelGGL((backward_kernel<true, false>), grd, blk, 0, stream, ev.start, ev.stop, 0, p);
-    } else {
-        if (aligned) hipExtLaunchKernelGGL((backward_kernel<false, true>), grd, blk, 0, stream, ev.start, ev.stop, 0, p);
-        else hipExtLaunchKernelGGL((backward_kernel<false, false>), grd, blk, 0, stream, ev.start, ev.stop, 0, p);
+#define MG_BWD(V, Al, Gt) \
+    hipExtLaunchKernelGGL((backward_kernel<V, Al, Gt>), grd, blk, 0, stream, ev.start, ev.stop, 0, p)
+#define MG_BWD_TYPE(Gt)                                      \
+    if (bt.weights) {                                        \
+        if (aligned) MG_BWD(true, true, Gt);                 \
+        else MG_BWD(true, false, Gt);                        \
+    } else {                                                 \
+        if (aligned) MG_BWD(false, true, Gt);                \
+        else MG_BWD(false, false, Gt);                       \
     }
+    if (grad_is_double) { MG_BWD_TYPE(double) } else { MG_BWD_TYPE(float) }
+#undef MG_BWD_TYPE
+#undef MG_BWD
     return hipGetLastError();
 }
 

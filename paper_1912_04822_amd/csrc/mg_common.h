@@ -141,11 +141,12 @@ hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                        float *grad_coords_to_clear, float *grad_weights_to_clear,
                        hipStream_t stream);
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
-                          float *out, int tile_floats, int waves_per_tile, int xcd_run,
-                          int lds_floor, int debug, KernelEvents ev, hipStream_t stream);
+                          void *out, bool out_is_double, int tile_floats, int waves_per_tile,
+                          int xcd_run, int lds_floor, int debug, KernelEvents ev,
+                          hipStream_t stream);
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
-                           const float *grad_out, float *grad_coords, float *grad_weights,
-                           KernelEvents ev, hipStream_t stream);
+                           const void *grad_out, bool grad_is_double, float *grad_coords,
+                           float *grad_weights, KernelEvents ev, hipStream_t stream);
 // grad[b] = sum over the sub3 virtual examples of b, in order (subgrids only)
 hipError_t launch_sum_subgrids(int subgrid_count, int B_source, size_t per_example,
                                const float *tmp, float *grad, hipStream_t stream);

@@ -74,7 +74,7 @@ struct FwdParams {
     const float *weights;
     const float *radii;
     const float *gcen;          // [B][4] grid centres, written by the prep kernel
-    float *out;
+    void *out;                      // float or double grid
     int subgrids, N, T;             // subgrids: virtual examples per example (weights are per example)
     int tile_floats;                // floats per tile (a multiple of 512)
     unsigned tiles;                 // tiles per channel
@@ -348,13 +348,42 @@ __device__ inline bool pair_run(const TileCtx &cx, PairHit &h, bool fixed)
 
 // Stream the finished tile to HBM (zeros if no atom touched it).  ITERS = tile_floats / 512
 // chunks of 2 KB; wavefront w of NW takes chunks w, w + NW, ...
-template <bool ALIGNED, int ITERS, int NW>
-__device__ inline void store_tile(const TileCtx &cx, float *dst, bool touched, bool fixed)
+template <bool ALIGNED, int ITERS, int NW, typename OUT>
+__device__ inline void store_tile(const TileCtx &cx, OUT *dst, bool touched, bool fixed)
 {
-    if (ALIGNED) {
+    constexpr bool kWide = sizeof(OUT) == 8;        // a grid of doubles: the same values, widened
+    if (ALIGNED && kWide) {
+        // Doubles: every store instruction writes 1 KB in one piece (lane l its 16 bytes at
+        // 16 l), four per 512-voxel chunk.
+        constexpr int MINE = ITERS / NW;
+        const int n2 = cx.n >> 1;
+        double2 *dst2 = reinterpret_cast<double2 *>(dst);
+        const float2 *src2 = reinterpret_cast<const float2 *>(cx.tile);
+        const bool convert = touched && fixed;
+#pragma unroll
+        for (int it = 0; it < MINE; ++it) {
+            float2 v[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int o = ((it * NW + cx.wave) * 4 + k) * 64 + cx.lane;
+                v[k] = touched ? src2[o] : make_float2(0.0f, 0.0f);
+                if (convert) {
+                    const float sc = 1.0f / kFixedOne;
+                    v[k] = make_float2((float)__float_as_int(v[k].x) * sc,
+                                       (float)__float_as_int(v[k].y) * sc);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int o = ((it * NW + cx.wave) * 4 + k) * 64 + cx.lane;
+                if (o < n2) dst2[o] = make_double2((double)v[k].x, (double)v[k].y);
+            }
+        }
+    } else if (ALIGNED) {
         constexpr int MINE = ITERS / NW;            // chunks per wavefront
         const int n4 = cx.n >> 2;                   // even: D^3 and the tile size are multiples of 8
-        float4 *dst4 = reinterpret_cast<float4 *>(dst);
+        float4 *dst4 = reinterpret_cast<float4 *>(dst);         // float grids
+        double2 *dst2 = reinterpret_cast<double2 *>(dst);       // double grids
         const float4 *src4 = reinterpret_cast<const float4 *>(cx.tile);
         // Constant trip count, fully unrolled; the tile comes from LDS into registers
         // under a uniform branch (zeros otherwise), so that the stores below are one
@@ -384,8 +413,15 @@ __device__ inline void store_tile(const TileCtx &cx, float *dst, bool touched, b
             }
             const int o = (it * NW + cx.wave) * 128 + cx.lane * 2;
             if (o < n4) {
-                dst4[o] = a;
-                dst4[o + 1] = b;
+                if (kWide) {        // the lane's 8 values are 64 contiguous bytes: four 16-byte stores
+                    dst2[2 * o] = make_double2((double)a.x, (double)a.y);
+                    dst2[2 * o + 1] = make_double2((double)a.z, (double)a.w);
+                    dst2[2 * o + 2] = make_double2((double)b.x, (double)b.y);
+                    dst2[2 * o + 3] = make_double2((double)b.z, (double)b.w);
+                } else {
+                    dst4[o] = a;
+                    dst4[o + 1] = b;
+                }
             }
         }
     } else {
@@ -394,7 +430,7 @@ __device__ inline void store_tile(const TileCtx &cx, float *dst, bool touched, b
             if (touched)
                 v = fixed ? (float)reinterpret_cast<const int *>(cx.tile)[o] * (1.0f / kFixedOne)
                           : cx.tile[o];
-            dst[o] = v;
+            dst[o] = (OUT)v;
         }
     }
 }
@@ -421,7 +457,7 @@ __device__ inline TileGeom tile_geom(const FwdParams &p, int D, unsigned tile_in
 
 // One tile of channel (b, t): the records [r0, r1) of the example can reach it; cen is the
 // grid centre.
-template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS, int NW>
+template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS, int NW, typename OUT>
 __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b, int t,
                                           const TileGeom &tg, int r0, int r1, const float4 &cen)
 {
@@ -448,7 +484,7 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
     cx.g2k = p.g2k; cx.c2k = p.c2k; cx.sA = p.sA; cx.cA = p.cA;
     cx.debug = p.debug;
 
-    float *dst = p.out + ((size_t)b * T + t) * (size_t)total + f0;
+    OUT *dst = reinterpret_cast<OUT *>(p.out) + ((size_t)b * T + t) * (size_t)total + f0;
     cx.cen_x = cen.x;
     cx.cen_y = cen.y;
     cx.cen_z = cen.z;
@@ -462,7 +498,7 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
     const int *idx = p.idx + (size_t)b * N + r0;
     const int count = r1 - r0;
     if (count <= 0) {           // uniform: nothing can reach this tile
-        store_tile<ALIGNED, ITERS, NW>(cx, dst, false, false);
+        store_tile<ALIGNED, ITERS, NW, OUT>(cx, dst, false, false);
         return;
     }
 
@@ -586,12 +622,12 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
             any = cx.shared[1] != 0;
         }
     }
-    store_tile<ALIGNED, ITERS, NW>(cx, dst, any, fixed);
+    store_tile<ALIGNED, ITERS, NW, OUT>(cx, dst, any, fixed);
 }
 
 
-// One workgroup per tile.
-template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS, int NW>
+// One workgroup per tile.  OUT: float, or double for a grid of doubles.
+template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS, int NW, typename OUT>
 __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];   // tile | marks per wave | shared
@@ -634,7 +670,7 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     }
     asm volatile("" ::"s"(r0), "s"(r1), "s"(cen.x), "s"(cen.y), "s"(cen.z));  // all in flight before the first wait
     if (p.debug == 2) r1 = r0;
-    tile_body<VECTOR, BINARY, ALIGNED, ITERS, NW>(p, lds, b, t, tg, r0, r1, cen);
+    tile_body<VECTOR, BINARY, ALIGNED, ITERS, NW, OUT>(p, lds, b, t, tg, r0, r1, cen);
 }
 
 }  // namespace
@@ -658,10 +694,14 @@ unsigned long long magic64(unsigned d)      // ceil(2^64 / d); 0 stands for d ==
 }
 }  // namespace
 
-hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws, float *out,
-                          int tile_floats, int waves_per_tile, int xcd_run, int lds_floor,
-                          int debug, KernelEvents ev, hipStream_t stream)
+hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws, void *out,
+                          bool out_is_double, int tile_floats, int waves_per_tile, int xcd_run,
+                          int lds_floor, int debug, KernelEvents ev, hipStream_t stream)
 {
+    if (out_is_double) {        // 512 voxels = 4 KB of doubles per one-wavefront workgroup
+        tile_floats = 512;
+        waves_per_tile = 1;
+    }
     const ForwardGeometry fg = forward_geometry(gs.D, tile_floats);
     FwdParams p;
     p.gs = gs;
@@ -706,10 +746,13 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     const bool vec = bt.weights != nullptr;
     const dim3 blk(64 * nw), grd((unsigned)groups);
 #define MG_LAUNCH5(V, Bn, Al, It, Nw) \
-    hipExtLaunchKernelGGL((forward_kernel<V, Bn, Al, It, Nw>), grd, blk, (uint32_t)lds_bytes, stream, \
-                          ev.start, ev.stop, 0, p)
+    hipExtLaunchKernelGGL((forward_kernel<V, Bn, Al, It, Nw, float>), grd, blk, (uint32_t)lds_bytes, \
+                          stream, ev.start, ev.stop, 0, p)
 #define MG_LAUNCH(V, Bn, Al)                                                    \
-    switch (iters * 8 + nw) {                                                   \
+    if (out_is_double) {                                                        \
+        hipExtLaunchKernelGGL((forward_kernel<V, Bn, Al, 1, 1, double>), grd, blk,                 \
+                              (uint32_t)lds_bytes, stream, ev.start, ev.stop, 0, p);               \
+    } else switch (iters * 8 + nw) {                                            \
     case 2 * 8 + 1: MG_LAUNCH5(V, Bn, Al, 2, 1); break;                         \
     case 2 * 8 + 2: MG_LAUNCH5(V, Bn, Al, 2, 2); break;                         \
     case 4 * 8 + 1: MG_LAUNCH5(V, Bn, Al, 4, 1); break;                         \

@@ -20,7 +20,8 @@ EXPORTS = [
     "mg_gridmaker_create", "mg_gridmaker_create_subgrids", "mg_gridmaker_subgrids_per_side",
     "mg_gridmaker_destroy", "mg_gridmaker_points_per_side",
     "mg_workspace_bytes", "mg_transform_forward", "mg_transform_backward", "mg_draw_transforms",
-    "mg_forward_index", "mg_forward_vector",
+    "mg_forward_index", "mg_forward_vector", "mg_forward_index_f64", "mg_forward_vector_f64",
+    "mg_backward_index_f64", "mg_backward_vector_f64",
     "mg_backward_index", "mg_backward_vector", "mg_strerror", "mg_last_hip_error",
     "mg_set_option", "mg_time_next_kernel",
 ]
@@ -65,6 +66,14 @@ def lib() -> ctypes.CDLL:
         L.mg_forward_index.argtypes = [vp, ci, ci, ci] + [vp] * 8 + [vp, sz, vp]
         L.mg_forward_vector.restype = ci
         L.mg_forward_vector.argtypes = [vp, ci, ci, ci] + [vp] * 8 + [vp, sz, vp]
+        for name, src in (("mg_forward_index_f64", "mg_forward_index"),
+                          ("mg_forward_vector_f64", "mg_forward_vector")):
+            getattr(L, name).restype = ci
+            getattr(L, name).argtypes = [vp, ci, ci, ci] + [vp] * 8 + [vp, sz, vp]
+        L.mg_backward_index_f64.restype = ci
+        L.mg_backward_index_f64.argtypes = [vp, ci, ci, ci] + [vp] * 9 + [vp, sz, vp]
+        L.mg_backward_vector_f64.restype = ci
+        L.mg_backward_vector_f64.argtypes = [vp, ci, ci, ci] + [vp] * 10 + [vp, sz, vp]
         L.mg_backward_index.restype = ci
         L.mg_backward_index.argtypes = [vp, ci, ci, ci] + [vp] * 9 + [vp, sz, vp]
         L.mg_backward_vector.restype = ci
@@ -222,34 +231,37 @@ class GridMaker:
                 _ptr(translations, torch.float32, "translations", (B, 3)))
 
     def mg_forward_index(self, coords, types, radii, T, natoms=None, centers=None, quats=None,
-                         translations=None, out=None, workspace=None):
+                         translations=None, out=None, workspace=None, dtype=torch.float32):
+        """``dtype`` (or ``out.dtype``) torch.float64 calls ``mg_forward_index_f64``."""
         B, N, pc, pn, pce, pq, pt = self._common(coords, natoms, centers, quats, translations)
         D = self.D
         if out is None:
-            out = torch.empty(self.grid_shape(B, T), dtype=torch.float32, device=coords.device)
+            out = torch.empty(self.grid_shape(B, T), dtype=dtype, device=coords.device)
         ws, wsb = self._workspace(B, N, T, coords.device, workspace)
         rshape = (T,) if self.radius_type_indexed else (B, N)
-        rc = lib().mg_forward_index(
+        fn = lib().mg_forward_index_f64 if out.dtype == torch.float64 else lib().mg_forward_index
+        rc = fn(
             self._h, B, N, T, pc, _ptr(types, torch.int32, "types", (B, N)),
             _ptr(radii, torch.float32, "radii", rshape), pn, pce, pq, pt,
-            _ptr(out, torch.float32, "out", self.grid_shape(B, T)), ctypes.c_void_p(ws.data_ptr()), wsb,
+            _ptr(out, out.dtype, "out", self.grid_shape(B, T)), ctypes.c_void_p(ws.data_ptr()), wsb,
             _stream())
         if rc != MG_OK:
             raise MolgridError(rc, "mg_forward_index")
         return out
 
     def mg_forward_vector(self, coords, weights, radii, natoms=None, centers=None, quats=None,
-                          translations=None, out=None, workspace=None):
+                          translations=None, out=None, workspace=None, dtype=torch.float32):
         B, N, pc, pn, pce, pq, pt = self._common(coords, natoms, centers, quats, translations)
         T = weights.shape[2]
         D = self.D
         if out is None:
-            out = torch.empty(self.grid_shape(B, T), dtype=torch.float32, device=coords.device)
+            out = torch.empty(self.grid_shape(B, T), dtype=dtype, device=coords.device)
         ws, wsb = self._workspace(B, N, T, coords.device, workspace)
-        rc = lib().mg_forward_vector(
+        fn = lib().mg_forward_vector_f64 if out.dtype == torch.float64 else lib().mg_forward_vector
+        rc = fn(
             self._h, B, N, T, pc, _ptr(weights, torch.float32, "weights", (B, N, T)),
             _ptr(radii, torch.float32, "radii", (T,)), pn, pce, pq, pt,
-            _ptr(out, torch.float32, "out", self.grid_shape(B, T)), ctypes.c_void_p(ws.data_ptr()), wsb,
+            _ptr(out, out.dtype, "out", self.grid_shape(B, T)), ctypes.c_void_p(ws.data_ptr()), wsb,
             _stream())
         if rc != MG_OK:
             raise MolgridError(rc, "mg_forward_vector")
@@ -263,10 +275,12 @@ class GridMaker:
             grad_coords = torch.empty((B, N, 3), dtype=torch.float32, device=coords.device)
         ws, wsb = self._workspace(B, N, T, coords.device, workspace)
         rshape = (T,) if self.radius_type_indexed else (B, N)
-        rc = lib().mg_backward_index(
+        fn = (lib().mg_backward_index_f64 if grad_out.dtype == torch.float64
+              else lib().mg_backward_index)
+        rc = fn(
             self._h, B, N, T, pc, _ptr(types, torch.int32, "types", (B, N)),
             _ptr(radii, torch.float32, "radii", rshape), pn, pce, pq, pt,
-            _ptr(grad_out, torch.float32, "grad_out", self.grid_shape(B, T)),
+            _ptr(grad_out, grad_out.dtype, "grad_out", self.grid_shape(B, T)),
             _ptr(grad_coords, torch.float32, "grad_coords", (B, N, 3)),
             ctypes.c_void_p(ws.data_ptr()), wsb, _stream())
         if rc != MG_OK:
@@ -284,10 +298,12 @@ class GridMaker:
         if grad_weights is None and want_weights:
             grad_weights = torch.empty((B, N, T), dtype=torch.float32, device=coords.device)
         ws, wsb = self._workspace(B, N, T, coords.device, workspace)
-        rc = lib().mg_backward_vector(
+        fn = (lib().mg_backward_vector_f64 if grad_out.dtype == torch.float64
+              else lib().mg_backward_vector)
+        rc = fn(
             self._h, B, N, T, pc, _ptr(weights, torch.float32, "weights", (B, N, T)),
             _ptr(radii, torch.float32, "radii", (T,)), pn, pce, pq, pt,
-            _ptr(grad_out, torch.float32, "grad_out", self.grid_shape(B, T)),
+            _ptr(grad_out, grad_out.dtype, "grad_out", self.grid_shape(B, T)),
             _ptr(grad_coords, torch.float32, "grad_coords", (B, N, 3)),
             _ptr(grad_weights, torch.float32, "grad_weights", (B, N, T)),
             ctypes.c_void_p(ws.data_ptr()), wsb, _stream())

@@ -45,6 +45,9 @@ struct BwdParams {
     float *grad_coords;
     float *grad_weights;
     int subgrids, N, T;
+    unsigned wgs_per_example;       // workgroups (of four records) per example
+    unsigned units, share;          // workgroups in all; per XCD (ceil(units / 8))
+    unsigned long long wg_magic;    // ceil(2^64 / wgs_per_example), 0 if that is 1
     float sk, g2k, c2k;     // sqrt(k), g^2 k, c^2 k with k = 2 log2(e)
     float A2, cAk2;         // 2A, 2A c sqrt(k)
     float sAk, cA;          // sqrt(A/k), c sqrt(A)
@@ -296,8 +299,16 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
         : "=s"(zero)
         : "s"((unsigned long long)p.meta), "s"((unsigned long long)p.rec),
           "s"((unsigned long long)p.idx), "s"((unsigned long long)p.gcen),
-          "s"((unsigned long long)p.rot), "s"(p.N), "s"(p.T));
-    const int b = (int)(blockIdx.y + zero), slot = (int)(blockIdx.x * 4u + (threadIdx.x >> 6));
+          "s"((unsigned long long)p.rot), "s"(p.N), "s"(p.T), "s"(p.share), "s"(p.units),
+          "s"(p.wgs_per_example), "s"(p.wg_magic));
+    // Workgroup ids go round the 8 XCDs (id % 8), each with its own L2.  XCD k takes the k-th
+    // eighth of the (example, record) list, so the gradient volume of an example -- and the
+    // lines of it that neighbouring records share -- is read through one L2 only.
+    const unsigned lin = blockIdx.x + zero;
+    const unsigned v = (lin & 7u) * p.share + (lin >> 3);
+    if (v >= p.units || (lin >> 3) >= p.share) return;
+    const unsigned bu = p.wg_magic == 0ull ? v : (unsigned)__umul64hi((unsigned long long)v, p.wg_magic);
+    const int b = (int)bu, slot = (int)((v - bu * p.wgs_per_example) * 4u + (threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63u);
     const int N = p.N, T = p.T, D = gs.D;
     __shared__ __attribute__((aligned(16))) unsigned char s_marks[4][kSlotCap];
@@ -414,7 +425,11 @@ hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace 
         p.cA = (float)((double)gs.c * std::sqrt((double)gs.A));
     }
     const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)grad_out & 15u) == 0);
-    const dim3 grd((bt.N + 3) / 4, bt.B), blk(256);
+    p.wgs_per_example = (unsigned)((bt.N + 3) / 4);
+    p.units = p.wgs_per_example * (unsigned)bt.B;
+    p.share = (p.units + 7u) / 8u;
+    p.wg_magic = p.wgs_per_example <= 1u ? 0ull : (~0ull / p.wgs_per_example) + 1ull;
+    const dim3 grd(p.share * 8u), blk(256);
 #define MG_BWD(V, Al, Gt) \
     hipExtLaunchKernelGGL((backward_kernel<V, Al, Gt>), grd, blk, 0, stream, ev.start, ev.stop, 0, p)
 #define MG_BWD_TYPE(Gt)                                      \

@@ -362,16 +362,21 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
                 reduce_channel<ALIGNED, true>(p, reinterpret_cast<const GT *>(p.G) + (size_t)b * T * D3, t, D3, a, r, bx, ox, oy,
                                               oz, marks, sx, sy, sz, sv);
             const float inv_r2 = r > 0.0f ? __builtin_amdgcn_rcpf(r * p.sk) : 0.0f;    // sums are in scaled units
-            if (p.grad_coords) {
-                tx = fmaf(w * inv_r2, wave_sum(sx), tx);
-                ty = fmaf(w * inv_r2, wave_sum(sy), ty);
-                tz = fmaf(w * inv_r2, wave_sum(sz), tz);
+            if (p.grad_coords) {        // per lane; summed over the wavefront once, after the last channel
+                tx = fmaf(w * inv_r2, sx, tx);
+                ty = fmaf(w * inv_r2, sy, ty);
+                tz = fmaf(w * inv_r2, sz, tz);
             }
             if (p.grad_weights) {
                 const float val = wave_sum(sv);
                 if (lane == 0) p.grad_weights[((size_t)b * N + ai) * T + t] = val;
             }
         }
+    }
+    if (VECTOR && p.grad_coords) {
+        tx = wave_sum(tx);
+        ty = wave_sum(ty);
+        tz = wave_sum(tz);
     }
     if (lane == 0 && p.grad_coords) {
         float *o = p.grad_coords + ((size_t)b * N + ai) * 3;

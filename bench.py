@@ -43,15 +43,15 @@ class Events:
 
     def __init__(self, n):
         self.hip = hip_runtime()
-        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventCreateWithFlags.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint]
         self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p,
                                                  ctypes.c_void_p]
         self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
         self.pairs = []
         for _ in range(n):
             a, b = ctypes.c_void_p(), ctypes.c_void_p()
-            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0
-            assert self.hip.hipEventCreate(ctypes.byref(b)) == 0
+            assert self.hip.hipEventCreateWithFlags(ctypes.byref(a), EVENT_FLAGS) == 0
+            assert self.hip.hipEventCreateWithFlags(ctypes.byref(b), EVENT_FLAGS) == 0
             self.pairs.append((a, b))
 
     def elapsed_ms(self):
@@ -78,7 +78,11 @@ def stored_traffic(kernel_tag):
     return float(m.group(1)) if m else None
 
 
-EVENT_EVERY = 5     # a step in five carries kernel timing events (each pair costs the step ~4.5 us)
+# hipEventDisableSystemFence: the events only time a kernel, so they need no system-scope fence
+# (cache write-back and invalidation) when they complete; with the default flags that fence is
+# charged to the timed kernel (+1.4 us) and to the step that carries the pair.
+EVENT_FLAGS = 0x20000000
+EVENT_EVERY = 5     # a step in five carries kernel timing events (a pair costs its step a few us)
 
 
 def time_call(torch, molgrid, fn, steps, warmup):

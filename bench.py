@@ -271,8 +271,16 @@ def main():
                                               translations=w.translations, return_threads=True)
             times.append(time.perf_counter() - t0)
         best = min(times)
+        one = []
+        for _ in range(2):          # the same batch on one thread, about 1.5 s each
+            t0 = time.perf_counter()
+            oracle.forward_index(w.coords, w.types, w.radii, w.T, w.resolution, w.dimension,
+                                 centers=w.centers, quats=w.quats, translations=w.translations,
+                                 threads=1)
+            one.append(time.perf_counter() - t0)
         result["cpu_baseline"] = {
             "value": w.B / best, "unit": "grids/s", "cores": int(threads), "kind": "oracle",
+            "one_core_value": w.B / min(one),
             "sample": "all 50 examples of the same batch, cutoff-box variant, OpenMP over "
                       "examples, best of 10 runs (%.2f s each, median %.2f s)"
                       % (best, float(np.median(times)))}

@@ -57,21 +57,40 @@ class _VectorGrid(torch.autograd.Function):
 
 class GridLayer(torch.nn.Module):
     """A GridMaker as a differentiable layer: ``layer(coords, types=... | weights=..., ...)``
-    returns the ``[B,T,D,D,D]`` grid; gradients flow to ``coords`` (and ``weights``)."""
+    returns the ``[B,T,D,D,D]`` grid (``[B,S,S,S,T,D,D,D]`` with ``subgrids_per_side`` = S > 1);
+    gradients flow to ``coords`` (and ``weights``).
+
+    ``random_rotation`` / ``random_translation`` (GridMaker.forward's optional augmentation): a
+    fresh per-example rotation and a translation of at most that many Angstrom per axis are
+    drawn on the device for every call (``mg_draw_transforms``, counter-based: ``seed`` and the
+    number of the call fix them) and kept in ``last_quats`` / ``last_translations``, so the
+    applied transformation can be retained; gradients come back in the caller's frame."""
 
     def __init__(self, resolution=0.5, dimension=23.5, binary=False, radius_type_indexed=True,
-                 radius_scale=1.0, gaussian_radius_multiple=1.0):
+                 radius_scale=1.0, gaussian_radius_multiple=1.0, subgrids_per_side=1):
         super().__init__()
         self.gm = molgrid.GridMaker(resolution, dimension, binary=binary,
                                     radius_type_indexed=radius_type_indexed,
                                     radius_scale=radius_scale,
-                                    gaussian_radius_multiple=gaussian_radius_multiple)
+                                    gaussian_radius_multiple=gaussian_radius_multiple,
+                                    subgrids_per_side=subgrids_per_side)
+        self.seed, self.draws = 0, 0
+        self.last_quats = self.last_translations = None
 
     def forward(self, coords, radii, *, types: Optional[torch.Tensor] = None,
                 weights: Optional[torch.Tensor] = None, T: Optional[int] = None, natoms=None,
-                centers=None, quats=None, translations=None):
+                centers=None, quats=None, translations=None, random_rotation=False,
+                random_translation=0.0):
         if (types is None) == (weights is None):
             raise ValueError("give exactly one of types (index) or weights (vector)")
+        if random_rotation or random_translation > 0.0:
+            if quats is not None or translations is not None:
+                raise ValueError("give explicit transforms or ask for random ones, not both")
+            quats, translations = molgrid.mg_draw_transforms(
+                self.seed, self.draws, coords.shape[0], random_rotation=bool(random_rotation),
+                max_translation=float(random_translation), device=coords.device)
+            self.draws += 1
+            self.last_quats, self.last_translations = quats, translations
         if types is not None:
             if T is None:
                 raise ValueError("index types need the number of channels T")

@@ -83,6 +83,68 @@ def test_gradient_descent_on_coordinates_lowers_the_loss(mg):
     assert losses[1] < losses[0]            # the first step goes downhill
 
 
+def test_subgrid_layer_gradient(mg):
+    """A 2x2x2 sequence of subgrids as a layer: the gradient of a weighted sum over all subgrids
+    equals the oracle's subgrid backward (contributions of the subgrids added up per atom)."""
+    from paper_1912_04822_amd.autograd import GridLayer
+    w = workloads.ragged_small(seed=5, B=2, N=120, T=3, D=10, resolution=0.5)
+    S = 2
+    layer = GridLayer(w.resolution, w.dimension, subgrids_per_side=S)
+    coords = dev(w.coords).requires_grad_(True)
+    grid = layer(coords, dev(w.radii), types=dev(w.types), T=w.T, centers=dev(w.centers),
+                 quats=dev(w.quats), translations=dev(w.translations))
+    assert tuple(grid.shape) == (w.B, S, S, S, w.T, w.D, w.D, w.D)
+    rng = np.random.default_rng(12)
+    G = rng.standard_normal(tuple(grid.shape)).astype(np.float32)
+    (grid * dev(G)).sum().backward()
+    ref_grid = oracle.forward_subgrids(w.coords, w.radii, S, w.resolution, w.dimension, T=w.T,
+                                       types=w.types, centers=w.centers, quats=w.quats,
+                                       translations=w.translations)
+    assert np.abs(grid.detach().cpu().numpy() - ref_grid).max() <= GRID_TOL
+    ref = oracle.backward_subgrids(w.coords, w.radii, S, w.resolution, w.dimension, G, T=w.T,
+                                   types=w.types, centers=w.centers, quats=w.quats,
+                                   translations=w.translations)
+    got = coords.grad.cpu().numpy()
+    for b in range(w.B):
+        assert np.abs(got[b] - ref[b]).max() <= GRAD_RTOL * np.abs(ref[b]).max()
+
+
+def test_layer_with_random_augmentation_keeps_the_applied_transforms(mg):
+    """Random rotation + translation drawn per call: the grid and the gradient equal the oracle's
+    for the transforms the layer kept; the next call draws different ones; the same seed and call
+    number draw the same."""
+    from paper_1912_04822_amd.autograd import GridLayer
+    w = workloads.ragged_small(seed=6, B=3, N=90, T=3, D=12, resolution=0.5)
+    layer = GridLayer(w.resolution, w.dimension)
+    layer.seed = 77
+    coords = dev(w.coords).requires_grad_(True)
+    rng = np.random.default_rng(13)
+    G = rng.standard_normal(w.out_shape).astype(np.float32)
+    grid = layer(coords, dev(w.radii), types=dev(w.types), T=w.T, centers=dev(w.centers),
+                 random_rotation=True, random_translation=1.5)
+    (grid * dev(G)).sum().backward()
+    q, t = layer.last_quats.cpu().numpy(), layer.last_translations.cpu().numpy()
+    rq, rt = oracle.draw_transforms(77, 0, w.B, True, 1.5)
+    assert np.abs(q - rq).max() <= 1.2e-7 and np.abs(t - rt).max() <= 2.4e-7   # one float ulp
+    assert np.abs(t).max() <= 1.5 and np.allclose((q.astype(np.float64) ** 2).sum(1), 1.0, atol=1e-6)
+    ref_grid = oracle.forward_index(w.coords, w.types, w.radii, w.T, w.resolution, w.dimension,
+                                    centers=w.centers, quats=q, translations=t)
+    assert np.abs(grid.detach().cpu().numpy() - ref_grid).max() <= GRID_TOL
+    ref = oracle.backward_index(w.coords, w.types, w.radii, w.T, w.resolution, w.dimension, G,
+                                centers=w.centers, quats=q, translations=t)
+    got = coords.grad.cpu().numpy()
+    for b in range(w.B):
+        assert np.abs(got[b] - ref[b]).max() <= GRAD_RTOL * np.abs(ref[b]).max()
+    layer(dev(w.coords), dev(w.radii), types=dev(w.types), T=w.T, random_rotation=True)
+    assert not np.array_equal(layer.last_quats.cpu().numpy(), q)
+    assert float(layer.last_translations.abs().max()) == 0.0
+    again = GridLayer(w.resolution, w.dimension)
+    again.seed = 77
+    again(dev(w.coords), dev(w.radii), types=dev(w.types), T=w.T, random_rotation=True,
+          random_translation=1.5)
+    assert np.array_equal(again.last_quats.cpu().numpy(), q)
+
+
 def test_binary_grid_refuses_a_gradient(mg):
     from paper_1912_04822_amd.autograd import GridLayer
     w = workloads.tiny()

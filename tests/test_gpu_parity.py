@@ -128,6 +128,24 @@ def test_forward_backward_many_atoms_per_example(mg, N, single_type):
     assert grad_err(gb, rb) <= GRAD_RTOL
 
 
+def test_forward_backward_many_channels(mg):
+    """T * (D + 3) = 300 * 27 (type, x-bin) pairs are more than the one-workgroup-per-example prep
+    kernel keeps in LDS: the per-group kernel runs instead."""
+    w = workloads.ragged_small(seed=23, B=2, N=400, T=300, D=24, resolution=0.5)
+    got = run_forward_index(mg, w)
+    ref = oracle_forward_index(w)
+    assert np.abs(got - ref).max() <= GRID_TOL
+    assert (ref.reshape(2, 300, -1).max(axis=2) > 0).sum() > 100     # many channels hold atoms
+    gotb = run_forward_index(mg, w, binary=True)
+    refb = oracle_forward_index(w, binary=True)
+    assert np.array_equal(gotb.view(np.uint32), refb.astype(np.float32).view(np.uint32))
+    gb = run_backward_index(mg, w)
+    rb = oracle.backward_index(w.coords, w.types, w.radii, w.T, w.resolution, w.dimension,
+                               w.grad_out, centers=w.centers, quats=w.quats,
+                               translations=w.translations)
+    assert grad_err(gb, rb) <= GRAD_RTOL
+
+
 @pytest.mark.parametrize("D,res", [(1, 1.0), (4, 0.5), (7, 0.3), (50, 0.5), (130, 0.125)])
 def test_forward_odd_grid_sizes(mg, D, res):
     w = workloads.ragged_small(seed=D, B=2, N=50, T=3, D=D, resolution=res)

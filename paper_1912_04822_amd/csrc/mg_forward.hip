@@ -205,6 +205,7 @@ __device__ inline void run_tasks(const TileCtx &cx, const Cand &cd, int ntasks)
             float cA = cx.cA;
             asm volatile("" : "+v"(cA));        // keep it in a VGPR across the loop
             float fi = 0.0f;
+            const float wK = w * kFixedOne;     // a power of two: exact
             for (int i = 0; i < nz; ++i) {
                 const float zs = fmaf(fi, stepk, z0);
                 fi += 1.0f;
@@ -213,7 +214,7 @@ __device__ inline void run_tasks(const TileCtx &cx, const Cand &cd, int ntasks)
                 const float u = fminf(fmaf(__builtin_amdgcn_sqrtf(x2), cx.sA, -cA), 0.0f);
                 const float rho = x2 <= cx.g2k ? e : u * u;                 // 0 beyond the cutoff
                 if (FIXED) {
-                    const int q = VECTOR ? (int)rintf(w * rho * kFixedOne)
+                    const int q = VECTOR ? (int)rintf(wK * rho)
                                          : (int)fmaf(rho, kFixedOne, 0.5f);
                     __hip_atomic_fetch_add(reinterpret_cast<int *>(rowp) + klo + i, q,
                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);

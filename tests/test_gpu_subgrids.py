@@ -35,6 +35,29 @@ def test_forward_index_subgrids_small_ragged(mg, S):
     assert ref.max() > 0.5
 
 
+def test_sixteen_subgrids_per_side(mg):
+    """The largest decomposition the ABI takes: 16^3 = 4096 subgrids per example (3 points per
+    side each, a 48^3 lattice in all), forward and backward."""
+    S, D, res = 16, 3, 0.5
+    w = workloads.ragged_small(seed=17, B=2, N=300, T=3, D=D, resolution=res)
+    rng = np.random.default_rng(18)
+    w.coords[:] = (w.centers[:, None, :] + rng.uniform(-12.5, 12.5, w.coords.shape)).astype(np.float32)
+    gm = mg.GridMaker(res, w.dimension, radius_type_indexed=True, subgrids_per_side=S)
+    out = gm.mg_forward_index(dev(w.coords), dev(w.types), dev(w.radii), w.T, **dposes(w)).cpu().numpy()
+    ref = oracle.forward_subgrids(w.coords, w.radii, S, res, w.dimension, T=w.T, types=w.types,
+                                  **poses(w))
+    assert out.shape == ref.shape == (2, S, S, S, w.T, D, D, D)
+    assert np.abs(out - ref).max() <= GRID_TOL
+    assert (ref.reshape(2, S ** 3, -1).max(axis=2) > 0).mean() > 0.5       # most subgrids hold density
+    G = rng.standard_normal(ref.shape).astype(np.float32)
+    g = gm.mg_backward_index(dev(w.coords), dev(w.types), dev(w.radii), w.T, dev(G),
+                             **dposes(w)).cpu().numpy()
+    rg = oracle.backward_subgrids(w.coords, w.radii, S, res, w.dimension, G, T=w.T, types=w.types,
+                                  **poses(w))
+    for b in range(2):
+        assert np.abs(g[b] - rg[b]).max() <= GRAD_RTOL * np.abs(rg[b]).max()
+
+
 def test_forward_subgrids_protein_ligand_real_binary_vector(mg):
     """Two examples of the protein-ligand recipe in 2^3 subgrids of 24^3 points each (the 48^3
     region of the plain GridMaker cut in eight)."""

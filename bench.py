@@ -255,6 +255,40 @@ def main():
         ms, mk, _ = time_call(torch, molgrid, lambda: gmc.mg_forward_index(
             cc, tc, rc, wc.T, centers=cec, quats=qc, translations=trc, out=outc, workspace=wsc),
             max(20, args.steps // 4), 20)
+        # the tiny configuration (configs[0]: one example, 100 atoms, 24^3): launch-bound, so a
+        # latency in microseconds rather than a bandwidth -- called eagerly, and replayed from a
+        # HIP graph that holds the call's two kernel launches
+        wt = workloads.tiny()
+        gmt = molgrid.GridMaker(wt.resolution, wt.dimension, radius_type_indexed=True)
+        outt = torch.empty(wt.out_shape, dtype=torch.float32, device="cuda")
+        wst = torch.empty(gmt.workspace_bytes(wt.B, wt.N, wt.T), dtype=torch.uint8, device="cuda")
+        ct, tt, rt = dev(wt.coords), dev(wt.types), dev(wt.radii)
+
+        def tiny_call():
+            gmt.mg_forward_index(ct, tt, rt, wt.T, out=outt, workspace=wst)
+
+        ms_eager, mk_tiny, _ = time_call(torch, molgrid, tiny_call, 2000, 200)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            tiny_call()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            tiny_call()
+        for _ in range(200):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(2000):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_graph = (time.perf_counter() - t0) * 1e3 / 2000
+        rows["forward_tiny"] = {
+            "latency_us_eager": ms_eager * 1e3, "latency_us_graph": ms_graph * 1e3,
+            "kernel_us": mk_tiny * 1e3,
+            "workload": "configs[0]: B=1, N=100, T=4, 24^3 @0.5A (221 KB out): calls back to back"}
         rows["forward_large_chunk"] = {
             "ms_per_call": ms, "kernel_ms_avg": mk, "grids_per_s": wc.B / (ms * 1e-3),
             "algorithmic_GBs": wc.out_bytes / (mk * 1e-3) / 1e9,

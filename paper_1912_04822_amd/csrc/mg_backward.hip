@@ -48,7 +48,7 @@ struct BwdParams {
     unsigned wgs_per_example;       // workgroups (of four records) per example
     unsigned units, share;          // workgroups in all; per XCD (ceil(units / 8))
     unsigned long long wg_magic;    // ceil(2^64 / wgs_per_example), 0 if that is 1
-    float sk, g2k, c2k;     // sqrt(k), g^2 k, c^2 k with k = 2 log2(e)
+    float sk, inv_sk, g2k, c2k;     // sqrt(k), 1/sqrt(k), g^2 k, c^2 k with k = 2 log2(e)
     float A2, cAk2;         // 2A, 2A c sqrt(k)
     float sAk, cA;          // sqrt(A/k), c sqrt(A)
 };
@@ -287,6 +287,154 @@ __device__ inline void reduce_channel(const BwdParams &p, const GT *G, int t, si
     }
 }
 
+// ---------------------------------------------------------------------------
+// Vector types: kChanGroup channels of one atom in one pass.  The channels differ only in
+// radius, so the slots are listed once, for the widest sphere of the group (radius rmax),
+// and every voxel's x'^2 (in units of rmax/sqrt(k)) is rescaled per channel:
+//   x'^2_q = x'^2 (rmax/r_q)^2.   Beyond channel q's own cutoff f and rho are 0 by their
+// formulas, so the voxels the narrower spheres do not reach add nothing.
+// ---------------------------------------------------------------------------
+constexpr int kChanGroup = 4;
+
+struct GroupCoef {
+    float ratio2[kChanGroup];       // (rmax / r_q)^2
+    float cq[kChanGroup];           // w_q rmax / (sqrt(k) r_q^2): channel q's share of the coordinate sums
+    bool live[kChanGroup];          // r_q > 0 and t0 + q < T (uniform over the wavefront)
+};
+
+// body(row_off, k4, ux, uy) for every slot of the box that meets the sphere of radius r:
+// the slot is the four voxels k4 .. k4+3 of the row at float offset row_off of a channel;
+// ux, uy are the row's distances in units of r/sqrt(k).  The same enumeration as
+// reduce_channel (marks: this wavefront's kSlotCap bytes of LDS, zero on entry and return).
+template <typename Body>
+__device__ inline void for_each_slot(const BwdParams &p, const float4 &a, float r, const Box &bx,
+                                     float ox, float oy, float oz, unsigned char *marks,
+                                     Body body)
+{
+    const GridSpec &gs = p.gs;
+    const int lane = (int)(threadIdx.x & 63u);
+    const unsigned D = (unsigned)gs.D;
+    const float s = p.sk * __builtin_amdgcn_rcpf(r), step = gs.res * s;
+    const float ux0 = (a.x - (ox + (float)bx.ilo * gs.res)) * s;
+    const float uy0 = (a.y - (oy + (float)bx.jlo * gs.res)) * s;
+    const unsigned off0 = ((unsigned)bx.ilo * D + (unsigned)bx.jlo) * D;   // the box's first row
+    if (bx.ns > kMaxCulledSegs) {       // very many segments per row: every slot of the box
+        const int per_plane = bx.nr * bx.ns;
+        const int slots = bx.np * per_plane;
+        const float inv_pp = 1.0f / (float)per_plane, inv_ns = 1.0f / (float)bx.ns;
+        for (int sl = lane; sl < slots; sl += 64) {
+            const int pi = (int)(((float)sl + 0.5f) * inv_pp);
+            const int rem = sl - pi * per_plane;
+            const int row = (int)(((float)rem + 0.5f) * inv_ns);
+            const int seg = rem - row * bx.ns;
+            body(off0 + ((unsigned)pi * D + (unsigned)row) * D, (bx.seg0 + seg) << 2,
+                 fmaf(-(float)pi, step, ux0), fmaf(-(float)row, step, uy0));
+        }
+        return;
+    }
+    const int rows = bx.np * bx.nr;
+    const float inv_nr = __builtin_amdgcn_rcpf((float)bx.nr);
+    const float inv_step = __builtin_amdgcn_rcpf(step);
+    const float fz = (a.z - oz) * gs.inv_res;           // the atom's z in grid steps
+    for (int row0 = 0; row0 < rows; row0 += 128) {
+        int cnt[2] = {0, 0}, slo[2] = {0, 0};
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int row = row0 + 2 * lane + q;
+            if (row < rows) {
+                const int pi = (int)(((float)row + 0.5f) * inv_nr);
+                const int jr = row - pi * bx.nr;
+                const float ux = fmaf(-(float)pi, step, ux0), uy = fmaf(-(float)jr, step, uy0);
+                const float h2 = p.c2k - (ux * ux + uy * uy);
+                if (h2 > 0.0f) {
+                    const float hv = __builtin_amdgcn_sqrtf(h2) * inv_step + 1.0e-3f;
+                    const int klo = max(bx.klo, (int)ceilf(fz - hv));
+                    const int khi = min(bx.khi, (int)floorf(fz + hv));
+                    if (khi >= klo) {
+                        slo[q] = klo >> 2;
+                        cnt[q] = (khi >> 2) - slo[q] + 1;
+                    }
+                }
+            }
+        }
+        const int mine = cnt[0] + cnt[1];
+        const int incl = wave_inclusive_scan(mine);
+        const int total = bcast(incl, 63);
+        const int excl = incl - mine;
+        if (mine > 0) marks[excl] = (unsigned char)(lane + 1);
+        const int word = excl | (cnt[0] << 11) | (slo[0] << 15) | (slo[1] << 23);
+        lds_sync();
+        int carry = 0;
+        for (int base = 0; base < total; base += 64) {
+            const int sidx = base + lane;
+            int v = sidx < total ? (int)marks[sidx] : 0;
+            v = max(wave_inclusive_max(v), carry);
+            carry = bcast(v, 63);
+            const int owner = v - 1;
+            const int w = __builtin_amdgcn_ds_bpermute(owner << 2, word);
+            if (sidx < total) {
+                const int o = sidx - (w & 0x7ff);
+                const int c0 = (w >> 11) & 15;
+                const int q = o >= c0 ? 1 : 0;
+                const int seg = q ? (o - c0) + ((w >> 23) & 255) : o + ((w >> 15) & 255);
+                const int row = row0 + 2 * owner + q;
+                const int pi = (int)(((float)row + 0.5f) * inv_nr);
+                const int jr = row - pi * bx.nr;
+                body(off0 + ((unsigned)pi * D + (unsigned)jr) * D, seg << 2,
+                     fmaf(-(float)pi, step, ux0), fmaf(-(float)jr, step, uy0));
+            }
+        }
+        lds_sync();
+        if (mine > 0) marks[excl] = 0;
+        lds_sync();
+    }
+}
+
+// One atom against the channels t0 .. t0 + kChanGroup - 1 (G0: the volume of channel t0).
+//   (sx, sy, sz) += sum_q cq sum G_q f_q u   (u in units of rmax/sqrt(k)),  sv[q] += sum G_q rho_q
+template <bool ALIGNED, typename GT>
+__device__ inline void reduce_group(const BwdParams &p, const GT *G0, size_t D3, const float4 &a,
+                                    float rmax, const Box &bx, float ox, float oy, float oz,
+                                    unsigned char *marks, const GroupCoef &gc, float &sx,
+                                    float &sy, float &sz, float (&sv)[kChanGroup])
+{
+    const float s = p.sk * __builtin_amdgcn_rcpf(rmax), step = p.gs.res * s;
+    const float azs = (a.z - oz) * s;
+    for_each_slot(p, a, rmax, bx, ox, oy, oz, marks,
+                  [&](unsigned row_off, int k4, float ux, float uy) {
+        SlotData d[kChanGroup];
+#pragma unroll
+        for (int q = 0; q < kChanGroup; ++q)
+            if (gc.live[q]) load_slot<ALIGNED>(p, G0 + (size_t)q * D3, row_off, k4, ux, uy, d[q]);
+        const float b2 = ux * ux + uy * uy;
+        const float uz0 = fmaf(-(float)k4, step, azs);
+        float fsum = 0.0f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float uz = uz0 - (float)u * step;
+            const float x2m = fmaf(uz, uz, b2);
+            float F = 0.0f;
+#pragma unroll
+            for (int q = 0; q < kChanGroup; ++q) {
+                if (!gc.live[q]) continue;
+                const float x2 = x2m * gc.ratio2[q];
+                const float e = __builtin_amdgcn_exp2f(-x2);
+                const float rs = __builtin_amdgcn_rsqf(x2);
+                const float ft = fminf(fmaf(-p.cAk2, rs, p.A2), 0.0f);
+                const float f = x2 <= p.g2k ? -4.0f * e : ft;
+                F = fmaf(gc.cq[q], d[q].gv[u] * f, F);
+                const float tl = fminf(fmaf(x2 * rs, p.sAk, -p.cA), 0.0f);     // sqrt(A) (x - c)
+                const float rho = x2 <= p.g2k ? e : tl * tl;
+                sv[q] = fmaf(d[q].gv[u], rho, sv[q]);
+            }
+            fsum += F;
+            sz = fmaf(F, uz, sz);
+        }
+        sx = fmaf(fsum, ux, sx);
+        sy = fmaf(fsum, uy, sy);
+    });
+}
+
 template <bool VECTOR, bool ALIGNED, typename GT>
 __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
 {
@@ -353,23 +501,42 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
         ty = wave_sum(sy) * inv_r2;
         tz = wave_sum(sz) * inv_r2;
     } else {
-        for (int t = 0; t < T; ++t) {
-            const float r = gs.radius_scale * p.radii[t];
-            const float w = p.weights[((size_t)bs * N + ai) * T + t];
-            float sx = 0.0f, sy = 0.0f, sz = 0.0f, sv = 0.0f;
-            Box bx;
-            if (r > 0.0f && atom_box(gs, r * gs.c, a, ox, oy, oz, bx))
-                reduce_channel<ALIGNED, true>(p, reinterpret_cast<const GT *>(p.G) + (size_t)b * T * D3, t, D3, a, r, bx, ox, oy,
-                                              oz, marks, sx, sy, sz, sv);
-            const float inv_r2 = r > 0.0f ? __builtin_amdgcn_rcpf(r * p.sk) : 0.0f;    // sums are in scaled units
-            if (p.grad_coords) {        // per lane; summed over the wavefront once, after the last channel
-                tx = fmaf(w * inv_r2, sx, tx);
-                ty = fmaf(w * inv_r2, sy, ty);
-                tz = fmaf(w * inv_r2, sz, tz);
+        const size_t arow = ((size_t)bs * N + ai) * T;
+        for (int t0 = 0; t0 < T; t0 += kChanGroup) {
+            float rq[kChanGroup], wq[kChanGroup];
+            GroupCoef gc;
+            float rmax = 0.0f;
+#pragma unroll
+            for (int q = 0; q < kChanGroup; ++q) {
+                const int t = min(t0 + q, T - 1);
+                rq[q] = gs.radius_scale * p.radii[t];
+                wq[q] = p.weights[arow + t];
+                gc.live[q] = t0 + q < T && rq[q] > 0.0f;
+                if (gc.live[q]) rmax = fmaxf(rmax, rq[q]);
             }
+            float sx = 0.0f, sy = 0.0f, sz = 0.0f, sv[kChanGroup];
+#pragma unroll
+            for (int q = 0; q < kChanGroup; ++q) {
+                const float inv = gc.live[q] ? __builtin_amdgcn_rcpf(rq[q]) : 0.0f;
+                const float ratio = rmax * inv;
+                gc.ratio2[q] = ratio * ratio;
+                gc.cq[q] = wq[q] * ratio * inv * p.inv_sk;
+                sv[q] = 0.0f;
+            }
+            Box bx;
+            if (rmax > 0.0f && atom_box(gs, rmax * gs.c, a, ox, oy, oz, bx))
+                reduce_group<ALIGNED>(p, reinterpret_cast<const GT *>(p.G) + ((size_t)b * T + t0) * D3, D3, a, rmax, bx, ox,
+                                      oy, oz, marks, gc, sx, sy, sz, sv);
+            tx += sx;       // per lane; summed over the wavefront once, after the last group
+            ty += sy;
+            tz += sz;
             if (p.grad_weights) {
-                const float val = wave_sum(sv);
-                if (lane == 0) p.grad_weights[((size_t)b * N + ai) * T + t] = val;
+#pragma unroll
+                for (int q = 0; q < kChanGroup; ++q) {
+                    if (t0 + q >= T) break;
+                    const float val = wave_sum(sv[q]);
+                    if (lane == 0) p.grad_weights[((size_t)b * N + ai) * T + t0 + q] = val;
+                }
             }
         }
     }
@@ -422,6 +589,7 @@ hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace 
     {
         const double k = 2.8853900817779268;    // 2 / ln 2
         p.sk = (float)std::sqrt(k);
+        p.inv_sk = (float)(1.0 / std::sqrt(k));
         p.g2k = (float)((double)gs.g2 * k);
         p.c2k = (float)((double)gs.c * (double)gs.c * k);
         p.A2 = (float)(2.0 * (double)gs.A);

@@ -390,12 +390,12 @@ __device__ inline void for_each_slot(const BwdParams &p, const float4 &a, float 
     }
 }
 
-// One atom against the channels t0 .. t0 + kChanGroup - 1 (G0: the volume of channel t0).
+// One atom against kChanGroup channels (Gq[q]: the volume of the q-th of them).
 //   (sx, sy, sz) += sum_q cq sum G_q f_q u   (u in units of rmax/sqrt(k)),  sv[q] += sum G_q rho_q
 template <bool ALIGNED, typename GT>
-__device__ inline void reduce_group(const BwdParams &p, const GT *G0, size_t D3, const float4 &a,
-                                    float rmax, const Box &bx, float ox, float oy, float oz,
-                                    unsigned char *marks, const GroupCoef &gc, float &sx,
+__device__ inline void reduce_group(const BwdParams &p, const GT *const (&Gq)[kChanGroup],
+                                    const float4 &a, float rmax, const Box &bx, float ox, float oy,
+                                    float oz, unsigned char *marks, const GroupCoef &gc, float &sx,
                                     float &sy, float &sz, float (&sv)[kChanGroup])
 {
     const float s = p.sk * __builtin_amdgcn_rcpf(rmax), step = p.gs.res * s;
@@ -405,7 +405,7 @@ __device__ inline void reduce_group(const BwdParams &p, const GT *G0, size_t D3,
         SlotData d[kChanGroup];
 #pragma unroll
         for (int q = 0; q < kChanGroup; ++q)
-            if (gc.live[q]) load_slot<ALIGNED>(p, G0 + (size_t)q * D3, row_off, k4, ux, uy, d[q]);
+            if (gc.live[q]) load_slot<ALIGNED>(p, Gq[q], row_off, k4, ux, uy, d[q]);
         const float b2 = ux * ux + uy * uy;
         const float uz0 = fmaf(-(float)k4, step, azs);
         float fsum = 0.0f;
@@ -502,15 +502,36 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
         tz = wave_sum(sz) * inv_r2;
     } else {
         const size_t arow = ((size_t)bs * N + ai) * T;
+        // The channels are taken in order of radius (T <= 64: lane l ranks channel l among the
+        // others; more channels are taken as they come), so that the spheres of a group are
+        // nearly the same size and few voxels of the widest lie outside the others.
+        __shared__ unsigned char s_perm[4][64];
+        unsigned char *perm = s_perm[threadIdx.x >> 6];
+        const bool sorted = T <= 64;
+        if (sorted) {
+            float mine = lane < T ? p.radii[lane] : 0.0f;
+            mine = mine > 0.0f ? mine : 0.0f;       // NaN and negative radii rank as 0: still a permutation
+            int rank = 0;
+            for (int m = 0; m < T; ++m) {
+                const float other = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mine), m));
+                rank += (other < mine || (other == mine && m < lane)) ? 1 : 0;
+            }
+            if (lane < T) perm[rank] = (unsigned char)lane;
+            lds_sync();
+        }
         for (int t0 = 0; t0 < T; t0 += kChanGroup) {
             float rq[kChanGroup], wq[kChanGroup];
+            int tq[kChanGroup];
+            const GT *Gq[kChanGroup];
             GroupCoef gc;
             float rmax = 0.0f;
 #pragma unroll
             for (int q = 0; q < kChanGroup; ++q) {
-                const int t = min(t0 + q, T - 1);
-                rq[q] = gs.radius_scale * p.radii[t];
-                wq[q] = p.weights[arow + t];
+                const int pos = min(t0 + q, T - 1);
+                tq[q] = sorted ? min(__builtin_amdgcn_readfirstlane((int)perm[pos]), T - 1) : pos;
+                rq[q] = gs.radius_scale * p.radii[tq[q]];
+                wq[q] = p.weights[arow + tq[q]];
+                Gq[q] = reinterpret_cast<const GT *>(p.G) + ((size_t)b * T + tq[q]) * D3;
                 gc.live[q] = t0 + q < T && rq[q] > 0.0f;
                 if (gc.live[q]) rmax = fmaxf(rmax, rq[q]);
             }
@@ -525,8 +546,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
             }
             Box bx;
             if (rmax > 0.0f && atom_box(gs, rmax * gs.c, a, ox, oy, oz, bx))
-                reduce_group<ALIGNED>(p, reinterpret_cast<const GT *>(p.G) + ((size_t)b * T + t0) * D3, D3, a, rmax, bx, ox,
-                                      oy, oz, marks, gc, sx, sy, sz, sv);
+                reduce_group<ALIGNED>(p, Gq, a, rmax, bx, ox, oy, oz, marks, gc, sx, sy, sz, sv);
             tx += sx;       // per lane; summed over the wavefront once, after the last group
             ty += sy;
             tz += sz;
@@ -535,7 +555,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
                 for (int q = 0; q < kChanGroup; ++q) {
                     if (t0 + q >= T) break;
                     const float val = wave_sum(sv[q]);
-                    if (lane == 0) p.grad_weights[((size_t)b * N + ai) * T + t0 + q] = val;
+                    if (lane == 0) p.grad_weights[((size_t)b * N + ai) * T + tq[q]] = val;
                 }
             }
         }

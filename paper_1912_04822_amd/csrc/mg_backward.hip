@@ -10,10 +10,13 @@
 // caller's coordinates is R^T times that sum.
 //
 // One wavefront per atom record (four records per workgroup, no barrier).  The
-// work items are "slots": 4-voxel z-segments of the grid rows (x-plane, y) of
-// the atom's cutoff box, read with one 16-byte load each.  Only the slots that
-// meet the cutoff sphere are visited (about 45 % of the box's): per group of 128
-// rows every lane works out the segment span of its two rows, a prefix sum over
+// work items are "slots": runs of four voxels along z in the grid rows (x-plane,
+// y) of the atom's cutoff box, read with one 16-byte load each.  Only the rows
+// that meet the cutoff sphere are visited, and a row's slots start at the first
+// voxel of its chord (so a chord of L voxels takes ceil(L/4) slots, wherever it
+// lies; the last slot is pulled back into the row if need be -- voxels outside the
+// sphere add exactly 0): per group of 128
+// rows every lane works out the chord of its two rows, a prefix sum over
 // the lanes numbers the live slots, and slot s finds its row through a byte
 // array in LDS (the first slot of each lane's rows is marked with the lane, a
 // running maximum over the slots gives the owner) and one register exchange.
@@ -111,18 +114,22 @@ struct SlotData {
     int k4;
 };
 
+// 16-byte vectors that are only aligned like their elements (one wide load all the same)
+typedef float Float4E __attribute__((ext_vector_type(4), aligned(4)));
+typedef double Double2E __attribute__((ext_vector_type(2), aligned(8)));
+
 template <bool ALIGNED, typename GT>
 __device__ inline void load_slot(const BwdParams &p, const GT *Gc, unsigned row_off, int k4,
                                  float ux, float uy, SlotData &d)
 {
     const GT *src = Gc + (row_off + (unsigned)k4);
-    if (ALIGNED) {
+    if (ALIGNED) {      // the four voxels lie in the row; k4 need not be a multiple of 4
         if (sizeof(GT) == 8) {      // a grid of doubles: two 16-byte loads, narrowed
-            const double2 lo = reinterpret_cast<const double2 *>(src)[0];
-            const double2 hi = reinterpret_cast<const double2 *>(src)[1];
+            const Double2E lo = reinterpret_cast<const Double2E *>(src)[0];
+            const Double2E hi = reinterpret_cast<const Double2E *>(src)[1];
             d.gv[0] = (float)lo.x; d.gv[1] = (float)lo.y; d.gv[2] = (float)hi.x; d.gv[3] = (float)hi.y;
         } else {
-            const float4 g4 = *reinterpret_cast<const float4 *>(src);
+            const Float4E g4 = *reinterpret_cast<const Float4E *>(src);
             d.gv[0] = g4.x; d.gv[1] = g4.y; d.gv[2] = g4.z; d.gv[3] = g4.w;
         }
     } else {
@@ -237,9 +244,9 @@ __device__ inline void reduce_channel(const BwdParams &p, const GT *G, int t, si
                     const float hv = __builtin_amdgcn_sqrtf(h2) * inv_step + 1.0e-3f;
                     const int klo = max(bx.klo, (int)ceilf(fz - hv));
                     const int khi = min(bx.khi, (int)floorf(fz + hv));
-                    if (khi >= klo) {
-                        slo[q] = klo >> 2;
-                        cnt[q] = (khi >> 2) - slo[q] + 1;
+                    if (khi >= klo) {       // 4-voxel slots from the chord's first voxel, kept inside the row
+                        cnt[q] = (khi - klo + 4) >> 2;
+                        slo[q] = ALIGNED ? min(klo, gs.D - 4 * cnt[q]) : klo;
                     }
                 }
             }
@@ -249,9 +256,9 @@ __device__ inline void reduce_channel(const BwdParams &p, const GT *G, int t, si
         const int total = bcast(incl, 63);
         const int excl = incl - mine;
         if (mine > 0) marks[excl] = (unsigned char)(lane + 1);
-        // what a slot needs of its owner: first slot (11 bits), slots of row 0 (4), first
-        // segment of row 0 and of row 1 (8 each)
-        const int word = excl | (cnt[0] << 11) | (slo[0] << 15) | (slo[1] << 23);
+        // what a slot needs of its owner: first slot (11 bits) and slots of row 0 in one word,
+        // the first voxel of row 0 and of row 1 (16 bits each) in another
+        const int word = excl | (cnt[0] << 11), starts = slo[0] | (slo[1] << 16);
         lds_sync();
         asm volatile("" : "+v"(t));     // nothing above waits for t
         const GT *Gc = G + (size_t)t * D3;
@@ -266,17 +273,18 @@ __device__ inline void reduce_channel(const BwdParams &p, const GT *G, int t, si
             carry = bcast(v, 63);
             const int owner = v - 1;
             const int w = __builtin_amdgcn_ds_bpermute(owner << 2, word);
+            const int st = __builtin_amdgcn_ds_bpermute(owner << 2, starts);
             if (sidx < total) {
                 const int o = sidx - (w & 0x7ff);
-                const int c0 = (w >> 11) & 15;
+                const int c0 = w >> 11;
                 const int q = o >= c0 ? 1 : 0;
-                const int seg = q ? (o - c0) + ((w >> 23) & 255) : o + ((w >> 15) & 255);
+                const int k4 = q ? (st >> 16) + 4 * (o - c0) : (st & 0xffff) + 4 * o;
                 const int row = row0 + 2 * owner + q;
                 const int pi = (int)(((float)row + 0.5f) * inv_nr);
                 const int jr = row - pi * bx.nr;
                 const float ux = fmaf(-(float)pi, step, ux0), uy = fmaf(-(float)jr, step, uy0);
                 SlotData d;
-                load_slot<ALIGNED>(p, Gc, off0 + ((unsigned)pi * D + (unsigned)jr) * D, seg << 2, ux,
+                load_slot<ALIGNED>(p, Gc, off0 + ((unsigned)pi * D + (unsigned)jr) * D, k4, ux,
                                    uy, d);
                 reduce_slot<WANT_VALUE>(p, step, azs, d, sx, sy, sz, sv);
             }
@@ -306,7 +314,7 @@ struct GroupCoef {
 // the slot is the four voxels k4 .. k4+3 of the row at float offset row_off of a channel;
 // ux, uy are the row's distances in units of r/sqrt(k).  The same enumeration as
 // reduce_channel (marks: this wavefront's kSlotCap bytes of LDS, zero on entry and return).
-template <typename Body>
+template <bool ALIGNED, typename Body>
 __device__ inline void for_each_slot(const BwdParams &p, const float4 &a, float r, const Box &bx,
                                      float ox, float oy, float oz, unsigned char *marks,
                                      Body body)
@@ -350,9 +358,9 @@ __device__ inline void for_each_slot(const BwdParams &p, const float4 &a, float 
                     const float hv = __builtin_amdgcn_sqrtf(h2) * inv_step + 1.0e-3f;
                     const int klo = max(bx.klo, (int)ceilf(fz - hv));
                     const int khi = min(bx.khi, (int)floorf(fz + hv));
-                    if (khi >= klo) {
-                        slo[q] = klo >> 2;
-                        cnt[q] = (khi >> 2) - slo[q] + 1;
+                    if (khi >= klo) {       // 4-voxel slots from the chord's first voxel, kept inside the row
+                        cnt[q] = (khi - klo + 4) >> 2;
+                        slo[q] = ALIGNED ? min(klo, gs.D - 4 * cnt[q]) : klo;
                     }
                 }
             }
@@ -362,7 +370,7 @@ __device__ inline void for_each_slot(const BwdParams &p, const float4 &a, float 
         const int total = bcast(incl, 63);
         const int excl = incl - mine;
         if (mine > 0) marks[excl] = (unsigned char)(lane + 1);
-        const int word = excl | (cnt[0] << 11) | (slo[0] << 15) | (slo[1] << 23);
+        const int word = excl | (cnt[0] << 11), starts = slo[0] | (slo[1] << 16);
         lds_sync();
         int carry = 0;
         for (int base = 0; base < total; base += 64) {
@@ -372,15 +380,16 @@ __device__ inline void for_each_slot(const BwdParams &p, const float4 &a, float 
             carry = bcast(v, 63);
             const int owner = v - 1;
             const int w = __builtin_amdgcn_ds_bpermute(owner << 2, word);
+            const int st = __builtin_amdgcn_ds_bpermute(owner << 2, starts);
             if (sidx < total) {
                 const int o = sidx - (w & 0x7ff);
-                const int c0 = (w >> 11) & 15;
+                const int c0 = w >> 11;
                 const int q = o >= c0 ? 1 : 0;
-                const int seg = q ? (o - c0) + ((w >> 23) & 255) : o + ((w >> 15) & 255);
+                const int k4 = q ? (st >> 16) + 4 * (o - c0) : (st & 0xffff) + 4 * o;
                 const int row = row0 + 2 * owner + q;
                 const int pi = (int)(((float)row + 0.5f) * inv_nr);
                 const int jr = row - pi * bx.nr;
-                body(off0 + ((unsigned)pi * D + (unsigned)jr) * D, seg << 2,
+                body(off0 + ((unsigned)pi * D + (unsigned)jr) * D, k4,
                      fmaf(-(float)pi, step, ux0), fmaf(-(float)jr, step, uy0));
             }
         }
@@ -400,7 +409,7 @@ __device__ inline void reduce_group(const BwdParams &p, const GT *const (&Gq)[kC
 {
     const float s = p.sk * __builtin_amdgcn_rcpf(rmax), step = p.gs.res * s;
     const float azs = (a.z - oz) * s;
-    for_each_slot(p, a, rmax, bx, ox, oy, oz, marks,
+    for_each_slot<ALIGNED>(p, a, rmax, bx, ox, oy, oz, marks,
                   [&](unsigned row_off, int k4, float ux, float uy) {
         SlotData d[kChanGroup];
 #pragma unroll

@@ -399,6 +399,32 @@ def test_backward_vector(mg):
     assert none is None and torch.equal(gc2, gc)
 
 
+@pytest.mark.parametrize("T", [6, 64, 70])
+def test_backward_vector_channel_groups(mg, T):
+    """Vector-typed backward takes an atom's channels four at a time, in order of radius when
+    there are at most 64 of them: a last group that is not full (T = 6, 70), equal radii, a
+    channel without radius, exactly 64 channels, and more than 64 (taken as they come)."""
+    w = workloads.ragged_small(seed=40 + T, B=2, N=60, T=T, D=12, resolution=0.5)
+    rng = np.random.default_rng(T)
+    radii = rng.uniform(0.6, 2.2, T).astype(np.float32)
+    radii[1] = radii[4]                     # a tie
+    radii[2] = 0.0                          # takes no atoms: zero gradient
+    wts = rng.dirichlet(0.4 * np.ones(T), (w.B, w.N)).astype(np.float32)
+    wts[rng.random(wts.shape) < 0.2] = 0.0
+    G = rng.standard_normal((w.B, T, w.D, w.D, w.D)).astype(np.float32)
+    gm = mg.GridMaker(w.resolution, w.dimension, radius_type_indexed=True)
+    gc, gw = gm.mg_backward_vector(dev(w.coords), dev(wts), dev(radii), dev(G),
+                                   centers=dev(w.centers), quats=dev(w.quats),
+                                   translations=dev(w.translations))
+    rc, rw = oracle.backward_vector(w.coords, wts, radii, w.resolution, w.dimension, G,
+                                    centers=w.centers, quats=w.quats, translations=w.translations)
+    gc, gw = gc.cpu().numpy(), gw.cpu().numpy()
+    for b in range(w.B):
+        assert np.abs(gc[b] - rc[b]).max() <= GRAD_RTOL * np.abs(rc[b]).max()
+        assert np.abs(gw[b] - rw[b]).max() <= GRAD_RTOL * np.abs(rw[b]).max()
+    assert (gw[:, :, 2] == 0).all() and np.abs(rw[:, :, 2]).max() == 0
+
+
 def test_backward_rejects_binary_mode(mg):
     w = workloads.tiny()
     gm = mg.GridMaker(w.resolution, w.dimension, binary=True, radius_type_indexed=True)

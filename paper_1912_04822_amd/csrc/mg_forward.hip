@@ -205,22 +205,38 @@ __device__ inline void run_tasks(const TileCtx &cx, const Cand &cd, int ntasks)
             float cA = cx.cA;
             asm volatile("" : "+v"(cA));        // keep it in a VGPR across the loop
             float fi = 0.0f;
-            const float wK = w * kFixedOne;     // a power of two: exact
-            for (int i = 0; i < nz; ++i) {
-                const float zs = fmaf(fi, stepk, z0);
-                fi += 1.0f;
-                const float x2 = fmaf(zs, zs, x2b);
-                const float e = __builtin_amdgcn_exp2f(-x2);
-                const float u = fminf(fmaf(__builtin_amdgcn_sqrtf(x2), cx.sA, -cA), 0.0f);
-                const float rho = x2 <= cx.g2k ? e : u * u;                 // 0 beyond the cutoff
-                if (FIXED) {
-                    const int q = VECTOR ? (int)rintf(wK * rho)
-                                         : (int)fmaf(rho, kFixedOne, 0.5f);
-                    __hip_atomic_fetch_add(reinterpret_cast<int *>(rowp) + klo + i, q,
-                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                } else {
-                    __hip_atomic_fetch_add(rowp + klo + i, VECTOR ? w * rho : rho, __ATOMIC_RELAXED,
+            if (VECTOR && FIXED) {
+                // weight in fixed-point units (a power of two: exact); the product has the
+                // weight's sign, so adding half a unit of that sign and truncating rounds to
+                // nearest.  The voxel count is kept as a float: one counter less in the loop.
+                const float wK = w * kFixedOne, half = copysignf(0.5f, w);
+                const float fnz = (float)nz;
+                int *q = reinterpret_cast<int *>(rowp) + klo;
+                for (; fi < fnz; fi += 1.0f, ++q) {
+                    const float zs = fmaf(fi, stepk, z0);
+                    const float x2 = fmaf(zs, zs, x2b);
+                    const float e = __builtin_amdgcn_exp2f(-x2);
+                    const float u = fminf(fmaf(__builtin_amdgcn_sqrtf(x2), cx.sA, -cA), 0.0f);
+                    const float rho = x2 <= cx.g2k ? e : u * u;             // 0 beyond the cutoff
+                    __hip_atomic_fetch_add(q, (int)fmaf(rho, wK, half), __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+            } else {
+                for (int i = 0; i < nz; ++i) {
+                    const float zs = fmaf(fi, stepk, z0);
+                    fi += 1.0f;
+                    const float x2 = fmaf(zs, zs, x2b);
+                    const float e = __builtin_amdgcn_exp2f(-x2);
+                    const float u = fminf(fmaf(__builtin_amdgcn_sqrtf(x2), cx.sA, -cA), 0.0f);
+                    const float rho = x2 <= cx.g2k ? e : u * u;             // 0 beyond the cutoff
+                    if (FIXED) {
+                        __hip_atomic_fetch_add(reinterpret_cast<int *>(rowp) + klo + i,
+                                               (int)fmaf(rho, kFixedOne, 0.5f), __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_WORKGROUP);
+                    } else {
+                        __hip_atomic_fetch_add(rowp + klo + i, VECTOR ? w * rho : rho, __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_WORKGROUP);
+                    }
                 }
             }
         }

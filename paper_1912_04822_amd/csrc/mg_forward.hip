@@ -571,7 +571,59 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
     const bool single = count <= 64 * nsplit && pA1 - pA0 <= 1;    // one round, one pair of planes
     const int limit = (int)(kFixedLimit * 256.0f);
     bool any = false, fixed = !BINARY;
-    if (NW == 1 && !single) {
+    if (VECTOR && NW == 1 && !single) {
+        // Vector types, one wavefront, several rounds.  As the single pass below, but the loads
+        // run two stages ahead: a weight is gathered through the atom's index, so asking for
+        // the records of the next round and their weights in one go would make every round
+        // wait for a trip to memory between the two.  Records and indices are requested two
+        // rounds ahead, the weights one round ahead, each from values that arrived a round ago.
+        struct Raw {
+            float4 a;
+            int ai;
+        };
+        auto load_raw = [&](int base) {
+            Raw r;
+            r.a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            r.ai = 0;
+            if (base + lane < count) {
+                r.a = rec[base + lane];
+                r.ai = idx[base + lane];
+            }
+            return r;
+        };
+        auto gather = [&](const Raw &r) { return r.a.w > 0.0f ? wcol[(size_t)r.ai * T] : 1.0f; };
+        auto make_atom = [&](const Raw &r, float w) {
+            Atom at;
+            at.a = r.a;
+            at.w = w;
+            at.valid = (r.a.w > 0.0f) && (r_chan > 0.0f) && (BINARY ? (w > 0.0f) : (w != 0.0f));
+            at.a.w = r_chan;
+            return at;
+        };
+        Raw rn = load_raw(64);
+        float wn = gather(rn);
+        int bound = 0;
+        Atom at = at0;
+        for (int base = 0; base < count; base += 64) {
+            const Raw rnn = load_raw(base + 128);
+            for (int iA = pA0; iA <= pA1; iA += 2) {
+                PairHit h = test_pair(at, iA);
+                if (!BINARY && fixed) {
+                    bound += min(pair_bound<VECTOR>(h, at), 1 << 24);
+                    if (bound > limit) {
+                        fixed = false;
+                        for (int o = lane; o < ITERS * 512; o += 64)
+                            cx.tile[o] = (float)reinterpret_cast<int *>(cx.tile)[o] * (1.0f / kFixedOne);
+                        lds_sync();
+                    }
+                }
+                any = pair_run<VECTOR, BINARY>(cx, h, fixed) || any;
+            }
+            at = make_atom(rn, wn);
+            rn = rnn;
+            wn = gather(rn);
+        }
+    } else if (NW == 1 && !single) {
         // One wavefront, several rounds: a single pass.  The tile starts in fixed point and
         // the bound on what can reach one voxel is kept up round by round; the moment it
         // passes the limit, the tile is turned into floats and stays so.  The records of

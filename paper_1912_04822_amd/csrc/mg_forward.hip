@@ -323,11 +323,9 @@ template <bool VECTOR>
 __device__ inline int pair_bound(const PairHit &h, const Atom &at)
 {
     const bool hit = h.nA + h.nB > 0;
-    if (VECTOR) {
-        float s = hit ? fminf(fabsf(at.w), 4096.0f) : 0.0f;
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
-        return (int)ceilf(s * 256.0f);
+    if (VECTOR) {       // each weight rounded up to 1/256, summed exactly by DPP adds (no LDS traffic)
+        const int mine = hit ? (int)ceilf(fminf(fabsf(at.w), 4096.0f) * 256.0f) : 0;
+        return bcast(wave_inclusive_scan(mine), 63);
     }
     return 256 * (int)__builtin_popcountll(__ballot(hit));
 }

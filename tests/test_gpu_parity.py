@@ -432,3 +432,63 @@ def test_backward_rejects_binary_mode(mg):
         gm.mg_backward_index(dev(w.coords), dev(w.types), dev(w.radii), w.T,
                              torch.zeros(w.out_shape, device="cuda"))
     assert e.value.code == -6
+
+
+def _poisoned():
+    """ragged_small with data errors planted: non-finite and huge coordinates, a NaN and a
+    negative radius, types outside [0,T), natoms outside [0,N], a NaN quaternion, an infinite
+    translation (the documented rule: such atoms contribute nothing and get zero gradient)."""
+    w = workloads.ragged_small(seed=77, B=4, N=80, T=4, D=12, resolution=0.5)
+    w.coords[0, 3, 1] = np.nan
+    w.coords[0, 4, 0] = np.inf
+    w.coords[0, 5, 2] = -np.inf
+    w.coords[1, 6] = [1e30, -1e30, 3e38]
+    w.types[0, 7] = w.T
+    w.types[1, 8] = -5
+    w.types[2, 9] = 2 ** 31 - 1
+    radii = w.radii.copy()
+    radii[1] = np.nan
+    radii[2] = -1.0
+    quats = w.quats.copy()
+    quats[2] = [np.nan, 0.0, 1.0, 0.0]          # not a rotation: taken as the identity
+    trans = w.translations.copy()
+    trans[3, 1] = np.inf                         # every atom of example 3 becomes non-finite
+    nat = np.array([w.N + 50, -3, w.N, w.N], np.int32)
+    return w, radii, quats, trans, nat
+
+
+def test_data_errors_are_skipped_not_reported(mg):
+    w, radii, quats, trans, nat = _poisoned()
+    gm = mg.GridMaker(w.resolution, w.dimension, radius_type_indexed=True)
+    kw = dict(natoms=dev(nat), centers=dev(w.centers), quats=dev(quats), translations=dev(trans))
+    okw = dict(natoms=nat, centers=w.centers, quats=quats, translations=trans)
+    out = gm.mg_forward_index(dev(w.coords), dev(w.types), dev(radii), w.T, **kw).cpu().numpy()
+    ref = oracle.forward_index(w.coords, w.types, radii, w.T, w.resolution, w.dimension, **okw)
+    assert np.isfinite(out).all() and np.isfinite(ref).all()
+    assert np.abs(out - ref).max() <= GRID_TOL
+    assert out[0].max() > 0.5 and out[1].max() == 0 and out[3].max() == 0    # natoms -3; all atoms non-finite
+    assert out[:, 1].max() == 0 and out[:, 2].max() == 0                     # NaN and negative radius
+    gmb = mg.GridMaker(w.resolution, w.dimension, binary=True, radius_type_indexed=True)
+    outb = gmb.mg_forward_index(dev(w.coords), dev(w.types), dev(radii), w.T, **kw).cpu().numpy()
+    refb = oracle.forward_binary(w.coords, radii, w.T, w.resolution, w.dimension, types=w.types, **okw)
+    assert np.array_equal(outb.view(np.uint32), refb.view(np.uint32))
+    G = np.random.default_rng(3).standard_normal(ref.shape).astype(np.float32)
+    g = gm.mg_backward_index(dev(w.coords), dev(w.types), dev(radii), w.T, dev(G), **kw).cpu().numpy()
+    rg = oracle.backward_index(w.coords, w.types, radii, w.T, w.resolution, w.dimension, G, **okw)
+    assert np.isfinite(g).all()
+    assert grad_err(g[:1], rg[:1]) <= GRAD_RTOL and grad_err(g[2:3], rg[2:3]) <= GRAD_RTOL
+    assert (g[1] == 0).all() and (g[3] == 0).all() and (g[0, 3:8] == 0).all()
+    # vector types: the same atoms, weights instead of types
+    rng = np.random.default_rng(4)
+    wts = rng.dirichlet(0.5 * np.ones(w.T), (w.B, w.N)).astype(np.float32)
+    outv = gm.mg_forward_vector(dev(w.coords), dev(wts), dev(radii), **kw).cpu().numpy()
+    refv = oracle.forward_vector(w.coords, wts, radii, w.resolution, w.dimension, **okw)
+    assert np.isfinite(outv).all() and np.abs(outv - refv).max() <= GRID_TOL
+    gc, gw = gm.mg_backward_vector(dev(w.coords), dev(wts), dev(radii), dev(G), **kw)
+    rc, rw = oracle.backward_vector(w.coords, wts, radii, w.resolution, w.dimension, G, **okw)
+    gc, gw = gc.cpu().numpy(), gw.cpu().numpy()
+    assert np.isfinite(gc).all() and np.isfinite(gw).all()
+    for b in (0, 2):
+        assert np.abs(gc[b] - rc[b]).max() <= GRAD_RTOL * np.abs(rc[b]).max()
+        assert np.abs(gw[b] - rw[b]).max() <= GRAD_RTOL * np.abs(rw[b]).max()
+    assert (gc[1] == 0).all() and (gw[3] == 0).all() and (gw[:, :, 1:3] == 0).all()

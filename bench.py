@@ -121,6 +121,8 @@ def main():
     ap.add_argument("--lds-floor", type=int, default=None, help="forward kernel tuning knob")
     ap.add_argument("--waves-per-tile", type=int, default=None, help="forward kernel tuning knob")
     ap.add_argument("--xcd-run", type=int, default=None, help="forward kernel tuning knob")
+    ap.add_argument("--tile-order", type=int, default=None, help="forward kernel tuning knob")
+    ap.add_argument("--keep-alive", type=int, default=None, help="forward kernel tuning knob")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size (for scaling rocprofv3 counters)")
     args = ap.parse_args()
@@ -153,6 +155,10 @@ def main():
         molgrid.set_option("debug", args.debug)
     if args.xcd_run is not None:
         molgrid.set_option("xcd_run", args.xcd_run)
+    if args.tile_order is not None:
+        molgrid.set_option("tile_order", args.tile_order)
+    if args.keep_alive is not None:
+        molgrid.set_option("keep_alive", args.keep_alive)
     if args.lds_floor is not None:
         molgrid.set_option("lds_floor", args.lds_floor)
     if args.waves_per_tile is not None:

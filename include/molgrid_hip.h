@@ -242,12 +242,17 @@ int mg_last_hip_error(void);
 /*
  * Tuning knobs, for measurement only (results do not depend on them beyond
  * rounding).  Process-wide; not meant to be changed while calls are in flight.
- *   "tile_floats"     1024, 2048 or 4096 (default 2048; 4096 needs 2 or 4
- *                     wavefronts): consecutive output floats one forward
- *                     workgroup produces
+ *   "tile_floats"     0, 1024, 2048 or 4096 (default 0 = chosen per call from
+ *                     the shapes; 4096 needs 2 or 4 wavefronts): consecutive
+ *                     output floats one forward workgroup produces
  *   "waves_per_tile"  1, 2 or 4 (default 1): wavefronts in that workgroup
  *   "xcd_run"         0 or a power of two (default 0): runs of this many
  *                     consecutive tiles go to one XCD
+ *   "keep_alive"      0 or 1 (default 1): every forward wavefront (index types,
+ *                     float grid) also reads 1 KB of the workspace tables so that
+ *                     they stay cached while the grid is streamed out
+ *   "tile_order"      0 or 1 (default 0): 0 = all tiles of a channel, then the
+ *                     next channel; 1 = tile k of every channel, then tile k+1
  *   "lds_floor"       -1..65536 (default -1 = none): least LDS bytes a forward
  *                     workgroup requests; caps how many are resident on a CU
  *   "debug"           0..3: 0 = normal, 1 = no density evaluation, 2 = no atoms,

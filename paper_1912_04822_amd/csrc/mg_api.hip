@@ -19,10 +19,12 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
-int g_tile_floats = 2048;
+int g_tile_floats = 0;       // 0: chosen by the launcher
 int g_waves_per_tile = 1;
 int g_xcd_run = 0;
 int g_lds_floor = -1;     // < 0: chosen by the launcher
+int g_tile_order = 0;
+int g_keep_alive = 1;
 int g_debug = 0;
 
 // The caller's timing events for the main kernel of this call, if set (cleared by the call).
@@ -214,7 +216,7 @@ static int forward_call(const mg_gridmaker *gm, int B, int N, int T, const float
     rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
     if (rc != MG_OK) return rc;
     return hip_status(mg::launch_forward(gm->gs, bt, ws, out, out_is_double, g_tile_floats,
-                                         g_waves_per_tile, g_xcd_run, g_lds_floor, g_debug,
+                                         g_waves_per_tile, g_xcd_run, g_lds_floor, g_debug, g_tile_order, g_keep_alive,
                                          take_events(), (hipStream_t)stream));
 }
 
@@ -376,7 +378,7 @@ int mg_set_option(const char *key, int value)
 {
     if (!key) return MG_ENULL;
     if (std::strcmp(key, "tile_floats") == 0) {
-        if (value != 1024 && value != 2048 && value != 4096) return MG_EPARAM;
+        if (value != 0 && value != 1024 && value != 2048 && value != 4096) return MG_EPARAM;
         g_tile_floats = value;
         return MG_OK;
     }
@@ -388,6 +390,16 @@ int mg_set_option(const char *key, int value)
     if (std::strcmp(key, "xcd_run") == 0) {
         if (value < 0 || value > 32768 || (value & (value - 1)) != 0) return MG_EPARAM;
         g_xcd_run = value;
+        return MG_OK;
+    }
+    if (std::strcmp(key, "keep_alive") == 0) {
+        if (value != 0 && value != 1) return MG_EPARAM;
+        g_keep_alive = value;
+        return MG_OK;
+    }
+    if (std::strcmp(key, "tile_order") == 0) {
+        if (value != 0 && value != 1) return MG_EPARAM;
+        g_tile_order = value;
         return MG_OK;
     }
     if (std::strcmp(key, "lds_floor") == 0) {

@@ -142,7 +142,7 @@ hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                        hipStream_t stream);
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                           void *out, bool out_is_double, int tile_floats, int waves_per_tile,
-                          int xcd_run, int lds_floor, int debug, KernelEvents ev,
+                          int xcd_run, int lds_floor, int debug, int tile_order, int keep_alive, KernelEvents ev,
                           hipStream_t stream);
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                            const void *grad_out, bool grad_is_double, float *grad_coords,

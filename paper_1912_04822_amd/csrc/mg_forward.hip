@@ -78,13 +78,15 @@ struct FwdParams {
     void *out;                      // float or double grid
     int subgrids, N, T;             // subgrids: virtual examples per example (weights are per example)
     int tile_floats;                // floats per tile (a multiple of 512)
-    unsigned tiles;                 // tiles per channel
+    unsigned tiles;                 // divisor of the workgroup id: tiles per channel, or channels (B*T) when pos_major
+    unsigned pos_major;             // 0: all tiles of a channel, then the next channel; 1: tile k of every channel, then tile k+1
     unsigned long long div_magic;   // ceil(2^40 / D): x / D = (x * div_magic) >> 40 for x < D^3
     unsigned long long tiles_magic; // ceil(2^64 / tiles), see div_u32
     unsigned long long t_magic;     // ceil(2^64 / T)
     int xcd_shift;                  // >= 0: runs of 2^xcd_shift consecutive tiles go to one XCD
     unsigned n_remap;               // workgroups covered by that mapping (the rest map 1:1)
     int debug;
+    unsigned ka_chunks, ka_last;    // keep-alive reads: 1 KB chunks of the tables (0: none), byte offset of the last one
     float sk;           // sqrt(k), k = 2 log2(e)
     float inv_sk;
     float g2k, c2k;     // g^2 k, c^2 k
@@ -713,15 +715,28 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
         : "=s"(zero)
         : "s"((unsigned long long)p.range), "s"((unsigned long long)p.rec),
           "s"((unsigned long long)p.gcen), "s"((unsigned long long)p.out), "s"(p.tiles_magic),
-          "s"(p.t_magic), "s"(p.div_magic), "s"(p.tiles), "s"(p.xcd_shift), "s"(p.n_remap), "s"(D),
+          "s"(p.t_magic), "s"(p.div_magic), "s"(p.tiles), "s"(p.pos_major), "s"(p.ka_chunks), "s"(p.ka_last), "s"(p.xcd_shift), "s"(p.n_remap), "s"(D),
           "s"(T), "s"(N), "s"(p.debug), "s"(gs.half));
     unsigned u = blockIdx.x + zero;
     if (p.xcd_shift >= 0 && u < p.n_remap) {
         const unsigned xcd = u & 7u, slot = u >> 3, sh = (unsigned)p.xcd_shift;
         u = ((slot >> sh) << (sh + 3)) + (xcd << sh) + (slot & ((1u << sh) - 1u));
     }
-    const unsigned chan = div_u32(u, p.tiles_magic);
-    const unsigned tile_in_chan = u - chan * p.tiles;
+    // Keep-alive read: the tables the prep kernel wrote (records, spans, poses: a few MB) are read
+    // example by example, so those of the later examples would lie untouched while hundreds of
+    // MB of stores pass and be written back to HBM before their turn -- and a read that has to
+    // come from HBM while the chip streams stores costs far more than its bytes.  Every
+    // wavefront therefore also reads 1 KB of the tables, at a position scattered by its id
+    // (the result is not used): every line is touched every few microseconds and stays cached.
+    float4 ka = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (p.ka_chunks) {
+        const unsigned c = __umulhi((blockIdx.x + zero) * 2654435761u, p.ka_chunks);
+        const unsigned off = min(c << 10, p.ka_last) + ((threadIdx.x & 63u) << 4);
+        ka = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(p.rec) + off);
+    }
+    const unsigned uq = div_u32(u, p.tiles_magic), ur = u - uq * p.tiles;
+    const unsigned chan = p.pos_major ? ur : uq;
+    const unsigned tile_in_chan = p.pos_major ? uq : ur;
     const int b = (int)div_u32(chan, p.t_magic);
     const int t = (int)chan - b * T;
     const size_t group = (size_t)b * T + (VECTOR ? 0 : t);
@@ -739,6 +754,7 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     asm volatile("" ::"s"(r0), "s"(r1), "s"(cen.x), "s"(cen.y), "s"(cen.z));  // all in flight before the first wait
     if (p.debug == 2) r1 = r0;
     tile_body<VECTOR, BINARY, ALIGNED, ITERS, NW, OUT>(p, lds, b, t, tg, r0, r1, cen);
+    asm volatile("" ::"v"(ka.x), "v"(ka.y), "v"(ka.z), "v"(ka.w));     // the keep-alive read is waited for here
 }
 
 }  // namespace
@@ -764,8 +780,20 @@ unsigned long long magic64(unsigned d)      // ceil(2^64 / d); 0 stands for d ==
 
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws, void *out,
                           bool out_is_double, int tile_floats, int waves_per_tile, int xcd_run,
-                          int lds_floor, int debug, KernelEvents ev, hipStream_t stream)
+                          int lds_floor, int debug, int tile_order, int keep_alive, KernelEvents ev, hipStream_t stream)
 {
+    if (tile_floats == 0) {
+        // 4 KB tiles unless a tile meets many records (then the fixed cost per tile counts for
+        // more than the shorter life of a small tile): about N/T atoms per channel, of which
+        // those within a cutoff sphere's width (taken as 6 A) of the tile's x-plane are read.
+        // Measured: 48^3 at 0.5 A with 2040 atoms (20 per tile) 102 us against 111 us with 8 KB
+        // tiles; 96^3 at 0.25 A with 8000 atoms (74 per tile) 290 us with 8 KB tiles against 306 us.
+        const double groups = bt.weights ? 1.0 : (double)bt.T;
+        const double planes = 6.0 / (double)gs.res + 1.0;
+        const double per_tile = (double)bt.N / groups * (planes < gs.D ? planes / gs.D : 1.0);
+        tile_floats = per_tile > 48.0 ? 2048 : 1024;
+        if (waves_per_tile > tile_floats / 512) waves_per_tile = tile_floats / 512;
+    }
     if (out_is_double) {        // 512 voxels = 4 KB of doubles per one-wavefront workgroup
         tile_floats = 512;
         waves_per_tile = 1;
@@ -785,8 +813,9 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     p.div_magic = ((1ULL << 40) + (unsigned long long)gs.D - 1ULL) / (unsigned long long)gs.D;
     const int iters = tile_floats / 512;
     const int nw = waves_per_tile < iters ? waves_per_tile : iters;
-    p.tiles = (unsigned)fg.tiles;
-    p.tiles_magic = magic64((unsigned)fg.tiles);
+    p.pos_major = tile_order == 1 ? 1u : 0u;
+    p.tiles = p.pos_major ? (unsigned)bt.B * (unsigned)bt.T : (unsigned)fg.tiles;
+    p.tiles_magic = magic64(p.tiles);
     p.t_magic = magic64((unsigned)bt.T);
     const unsigned long long groups = (unsigned long long)bt.B * bt.T * fg.tiles;
     p.xcd_shift = -1;
@@ -798,6 +827,16 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
         p.n_remap = (unsigned)(groups / chunk * chunk);
     }
     p.debug = debug;
+    {   // the tables lie one after the other in the workspace, from the records to the grid centres
+        const size_t bytes = (size_t)((const char *)(ws.gcen + (size_t)bt.B * 4) - (const char *)ws.rec);
+        p.ka_chunks = 0;
+        p.ka_last = 0;
+        // (vector types are bound by arithmetic and a grid of doubles by its own stores: measured no gain)
+        if (keep_alive && !bt.weights && !out_is_double && bytes >= 1024 && bytes < (1ull << 31)) {
+            p.ka_chunks = (unsigned)((bytes + 1023) >> 10);
+            p.ka_last = (unsigned)(bytes - 1024);
+        }
+    }
     const double k = 2.8853900817779268;        // 2 / ln 2
     p.sk = (float)std::sqrt(k);
     p.inv_sk = (float)(1.0 / std::sqrt(k));

@@ -137,6 +137,7 @@ def test_calls_reject_bad_arguments_before_any_launch(L):
     assert b"unknown" in L.mg_strerror(-99)
     L.mg_set_option.argtypes = [ctypes.c_char_p, ci]
     assert L.mg_set_option(b"tile_floats", 2048) == 0
+    assert L.mg_set_option(b"tile_floats", 0) == 0
     assert L.mg_set_option(b"tile_floats", 1000) == -3
     assert L.mg_set_option(b"nope", 0) == -3
     for hh in (h, hb, hp):

@@ -177,7 +177,7 @@ def test_forward_protein_ligand_subset_and_determinism(mg):
         try:
             other = run_forward_index(mg, w)
         finally:
-            mg.set_option("tile_floats", 2048)
+            mg.set_option("tile_floats", 0)
             mg.set_option("waves_per_tile", 1)
         # the knob changes the order in which overlapping atoms are summed: equal to rounding
         assert np.abs(got - other).max() <= 2e-6
@@ -305,7 +305,7 @@ def test_tile_shapes_binary_and_vector(mg, tile_floats, waves):
         ref = oracle_forward_index(w, natoms=nat)
         assert np.abs(got - ref).max() <= GRID_TOL
     finally:
-        mg.set_option("tile_floats", 2048)
+        mg.set_option("tile_floats", 0)
         mg.set_option("waves_per_tile", 1)
 
 

@@ -34,16 +34,20 @@
 // the tile).  With more than one wavefront there are two barriers per tile: after
 // the zero fill and the decision between fixed point and float (which needs the
 // bound over all wavefronts), and before the tile is read back.  The default is
-// one wavefront per 8 KB tile (no barrier at all); the other shapes measure the
-// same within 1 % on the 48^3 workload.  A grid of doubles takes 512 voxels per
-// workgroup (4 KB of output) and stores 1 KB per instruction.
+// one wavefront per 4 KB tile (no barrier at all; 8 KB when a tile meets many
+// records).  A grid of doubles takes 512 voxels per workgroup (4 KB of output) and
+// stores 1 KB per instruction.
 //
 // Why 4 KB / 8 KB tiles on 4 KB boundaries: measured on this chip, one-wavefront
 // workgroups that each write one aligned 4 KB or 8 KB run sustain 6.3-6.6 TB/s
 // when nothing else is going on, while runs of 6, 9, 18 or 36 KB per wavefront
-// (whole x-planes of a 48^3 grid are 9 KB) fall to 5.2-5.4 TB/s.  What the full
-// kernel loses against that (109 us against 94-110 us of stores alone) is the
-// reads: wavefronts wait for their records behind the chip's own store stream.
+// (whole x-planes of a 48^3 grid are 9 KB) fall to 5.2-5.4 TB/s.  Reads do not
+// disturb that stream as long as a cache serves them; reads that must come from
+// HBM do, far beyond their bytes.  The tables this kernel reads (a few MB, written
+// by the prep kernel just before) would be pushed out to HBM by the hundreds of MB
+// of stores before the later examples' turn, so every wavefront also touches 1 KB
+// of them (see the kernel's preamble): 102 us against 108 us per launch on the
+// 48^3 batch of 50, 257 us against 328 us on a 96^3 batch of 16.
 //
 // The density is rho(x) = exp(-2x^2) for x <= g, A(x-c)^2 for g < x < c, else 0
 // (x = d/r).  Distances are carried in units of r/sqrt(k), k = 2*log2(e), so

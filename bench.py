@@ -219,6 +219,24 @@ def main():
             rows[name] = {"ms_per_call": ms, "kernel_ms_avg": mk, "grids_per_s": w.B / (ms * 1e-3),
                           "algorithmic_GBs": nbytes / (mk * 1e-3) / 1e9}
 
+        # for scale: the runtime's memset of the same output buffer (no atoms, no arithmetic)
+        hip = hip_runtime()
+        hip.hipMemsetAsync.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p]
+        stream_h = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+        def memset_out():
+            assert hip.hipMemsetAsync(ctypes.c_void_p(out.data_ptr()), 0, w.out_bytes, stream_h) == 0
+
+        for _ in range(20):
+            memset_out()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(200):
+            memset_out()
+        torch.cuda.synchronize()
+        ms_memset = (time.perf_counter() - t0) * 1e3 / 200
+        rows["memset_same_buffer"] = {"ms_per_call": ms_memset,
+                                      "algorithmic_GBs": w.out_bytes / (ms_memset * 1e-3) / 1e9}
         add("forward_binary", lambda: gmb.mg_forward_index(
             coords, types, radii, w.T, centers=centers, quats=quats, translations=trans, out=out,
             workspace=ws), w.out_bytes, args.steps)

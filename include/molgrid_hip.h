@@ -253,7 +253,8 @@ int mg_last_hip_error(void);
  *                     they stay cached while the grid is streamed out
  *   "tile_order"      0 or 1 (default 0): 0 = all tiles of a channel, then the
  *                     next channel; 1 = tile k of every channel, then tile k+1
- *   "lds_floor"       -1..65536 (default -1 = none): least LDS bytes a forward
+ *   "lds_floor"       -1..65536 (default -1 = chosen per call: 6144 for 4 KB
+ *                     tiles of index types, else none): least LDS bytes a forward
  *                     workgroup requests; caps how many are resident on a CU
  *   "debug"           0..3: 0 = normal, 1 = no density evaluation, 2 = no atoms,
  *                     3 = stores only (output then wrong: times parts of the kernel)

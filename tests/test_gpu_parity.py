@@ -184,6 +184,24 @@ def test_forward_protein_ligand_subset_and_determinism(mg):
         assert np.abs(other - ref).max() <= GRID_TOL
 
 
+@pytest.mark.parametrize("key,value", [("keep_alive", 0), ("tile_order", 1), ("xcd_run", 8),
+                                       ("lds_floor", 0), ("lds_floor", 16384)])
+def test_launch_knobs_do_not_change_a_bit(mg, key, value):
+    """Launch order, residency and the keep-alive reads only change when things run: the grid is
+    the same to the bit (index types, binary, and an unaligned grid)."""
+    cases = [workloads.protein_ligand(B=3, seed=17), workloads.ragged_small()]
+    base = [(run_forward_index(mg, w), run_forward_index(mg, w, binary=True)) for w in cases]
+    default = {"keep_alive": 1, "tile_order": 0, "xcd_run": 0, "lds_floor": -1}[key]
+    mg.set_option(key, value)
+    try:
+        for w, (real, binary) in zip(cases, base):
+            assert np.array_equal(run_forward_index(mg, w).view(np.uint32), real.view(np.uint32))
+            assert np.array_equal(run_forward_index(mg, w, binary=True).view(np.uint32),
+                                  binary.view(np.uint32))
+    finally:
+        mg.set_option(key, default)
+
+
 def test_forward_single_type_many_atoms(mg):
     """All atoms in one channel: the record list of that channel is longer than one LDS round."""
     w = workloads.protein_ligand(B=2)

@@ -140,6 +140,11 @@ def test_calls_reject_bad_arguments_before_any_launch(L):
     assert L.mg_set_option(b"tile_floats", 0) == 0
     assert L.mg_set_option(b"tile_floats", 1000) == -3
     assert L.mg_set_option(b"nope", 0) == -3
+    for key, good, bad, default in ((b"keep_alive", 0, 2, 1), (b"tile_order", 1, 2, 0),
+                                    (b"lds_floor", 8192, 70000, -1), (b"xcd_run", 8, 12, 0)):
+        assert L.mg_set_option(key, good) == 0
+        assert L.mg_set_option(key, bad) == -3
+        assert L.mg_set_option(key, default) == 0
     for hh in (h, hb, hp):
         L.mg_gridmaker_destroy(hh)
 

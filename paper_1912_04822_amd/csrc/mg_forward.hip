@@ -791,11 +791,12 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
         // more than the shorter life of a small tile): about N/T atoms per channel, of which
         // those within a cutoff sphere's width (taken as 6 A) of the tile's x-plane are read.
         // Measured: 48^3 at 0.5 A with 2040 atoms (20 per tile) 102 us against 111 us with 8 KB
-        // tiles; 96^3 at 0.25 A with 8000 atoms (74 per tile) 290 us with 8 KB tiles against 306 us.
+        // tiles; 96^3 at 0.25 A with 8000 atoms (74 per tile) 275 us with 8 KB tiles against 297 us,
+        // with 6000 atoms (56 per tile) 281 against 279 us, with 5000 (47) 285 against 275 us.
         const double groups = bt.weights ? 1.0 : (double)bt.T;
         const double planes = 6.0 / (double)gs.res + 1.0;
         const double per_tile = (double)bt.N / groups * (planes < gs.D ? planes / gs.D : 1.0);
-        tile_floats = per_tile > 48.0 ? 2048 : 1024;
+        tile_floats = per_tile > 60.0 ? 2048 : 1024;
         if (waves_per_tile > tile_floats / 512) waves_per_tile = tile_floats / 512;
     }
     if (out_is_double) {        // 512 voxels = 4 KB of doubles per one-wavefront workgroup

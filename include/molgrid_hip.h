@@ -161,6 +161,29 @@ int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T,
                      void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * mg_forward_index for callers that cannot allocate or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the same call and the same kernels, with the workspace in a
+ * static device array of MG_STATIC_WORKSPACE_BYTES inside the library (each
+ * GPU the library runs on holds its own copy until the process ends).  The
+ * call allocates and frees nothing; its first use on a device looks the
+ * array's address up (hipGetSymbolAddress), later calls reuse it.  The device
+ * of `stream` must be the current device.
+ * Returns MG_EWORKSPACE -- before anything is enqueued -- when
+ * mg_workspace_bytes(gm, B, N, T) exceeds MG_STATIC_WORKSPACE_BYTES (8 MiB
+ * holds B = 50, N = 2040, T = 28 at 48 points per side, 2.6 MB, and B = 16,
+ * N = 8000, T = 28 at 96 points, 2.9 MB).
+ * All calls on one GPU share that GPU's array: calls that overlap in time
+ * (different streams or threads) race; order them.  Nothing in the array has
+ * to start at zero: every call writes each table entry before reading it.
+ */
+#define MG_STATIC_WORKSPACE_BYTES (8u << 20)
+int mg_forward_index_static(const mg_gridmaker *gm, int B, int N, int T,
+                            const float *coords, const int32_t *types, const float *radii,
+                            const int32_t *natoms, const float *centers, const float *quats,
+                            const float *translations, float *out, void *stream);
+
+/*
  * Forward, vector types (Atom Typing section: a type may be a vector):
  *   out[b][t][p] = sum_a weights[b][a][t] * rho(|p - x'_a| / (radius_scale * radii[t]))
  * weights [B][N][T] float; radii [T] float, indexed by type id (the GridMaker

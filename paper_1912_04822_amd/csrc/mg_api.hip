@@ -2,6 +2,7 @@
 // launches.  No allocation, no synchronisation, no host<->device copies.
 #include "../../include/molgrid_hip.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -14,6 +15,11 @@ struct mg_gridmaker {
     float dimension;
     float grm;
 };
+
+// The workspace of mg_forward_index_static: one array per GPU, held until the process ends.
+// The name is a host-side stand-in, not a device address: host code only ever uses the
+// per-device address hipGetSymbolAddress returned (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[MG_STATIC_WORKSPACE_BYTES];
 
 namespace {
 
@@ -34,6 +40,32 @@ mg::KernelEvents take_events()
     g_ev_start = nullptr;
     g_ev_stop = nullptr;
     return ev;
+}
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Address of `scratch` on the current device, looked up once per device (each GPU holds its
+// own copy of the array at its own address).  Two threads racing here store the same value.
+int static_scratch(void **ptr, int *hip_error)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        *hip_error = (int)(e != hipSuccess ? e : hipErrorInvalidDevice);
+        return MG_EHIP;
+    }
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            *hip_error = (int)(e != hipSuccess ? e : hipErrorInvalidSymbol);
+            return MG_EHIP;
+        }
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return MG_OK;
 }
 
 bool finite_pos(float v) { return std::isfinite(v) && v > 0.0f; }
@@ -228,6 +260,27 @@ int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T, const float *c
     if (!types) return MG_ENULL;
     return forward_call(gm, B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
                         translations, out, false, workspace, workspace_bytes, stream);
+}
+
+int mg_forward_index_static(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
+                            const int32_t *types, const float *radii, const int32_t *natoms,
+                            const float *centers, const float *quats, const float *translations,
+                            float *out, void *stream)
+{
+    if (!gm || !types) return MG_ENULL;
+    const int rc = check_shape(gm, B, N, T);
+    if (rc != MG_OK) return rc;
+    if (mg::workspace_bytes(gm->gs, gm->sub.count, B * gm->sub.count, N, T) > (size_t)MG_STATIC_WORKSPACE_BYTES)
+        return MG_EWORKSPACE;
+    if (!coords || !radii || !out) return MG_ENULL;       // before the device is asked for anything
+    void *ws = nullptr;
+    int herr = 0;
+    if (static_scratch(&ws, &herr) != MG_OK) {
+        g_last_hip_error = herr;
+        return MG_EHIP;
+    }
+    return forward_call(gm, B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
+                        translations, out, false, ws, (size_t)MG_STATIC_WORKSPACE_BYTES, stream);
 }
 
 int mg_forward_index_f64(const mg_gridmaker *gm, int B, int N, int T, const float *coords,

@@ -20,7 +20,7 @@ EXPORTS = [
     "mg_gridmaker_create", "mg_gridmaker_create_subgrids", "mg_gridmaker_subgrids_per_side",
     "mg_gridmaker_destroy", "mg_gridmaker_points_per_side",
     "mg_workspace_bytes", "mg_transform_forward", "mg_transform_backward", "mg_draw_transforms",
-    "mg_forward_index", "mg_forward_vector", "mg_forward_index_f64", "mg_forward_vector_f64",
+    "mg_forward_index", "mg_forward_index_static", "mg_forward_vector", "mg_forward_index_f64", "mg_forward_vector_f64",
     "mg_backward_index_f64", "mg_backward_vector_f64",
     "mg_backward_index", "mg_backward_vector", "mg_strerror", "mg_last_hip_error",
     "mg_set_option", "mg_time_next_kernel",
@@ -64,6 +64,8 @@ def lib() -> ctypes.CDLL:
         L.mg_draw_transforms.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ci, ci, cf, vp, vp, vp]
         L.mg_forward_index.restype = ci
         L.mg_forward_index.argtypes = [vp, ci, ci, ci] + [vp] * 8 + [vp, sz, vp]
+        L.mg_forward_index_static.restype = ci
+        L.mg_forward_index_static.argtypes = [vp, ci, ci, ci] + [vp] * 8 + [vp]
         L.mg_forward_vector.restype = ci
         L.mg_forward_vector.argtypes = [vp, ci, ci, ci] + [vp] * 8 + [vp, sz, vp]
         for name, src in (("mg_forward_index_f64", "mg_forward_index"),
@@ -247,6 +249,20 @@ class GridMaker:
             _stream())
         if rc != MG_OK:
             raise MolgridError(rc, "mg_forward_index")
+        return out
+
+    def mg_forward_index_static(self, coords, types, radii, T, out, natoms=None, centers=None,
+                                quats=None, translations=None):
+        """``mg_forward_index`` with the workspace in the library's static device array: the
+        call allocates nothing, so ``out`` is required."""
+        B, N, pc, pn, pce, pq, pt = self._common(coords, natoms, centers, quats, translations)
+        rshape = (T,) if self.radius_type_indexed else (B, N)
+        rc = lib().mg_forward_index_static(
+            self._h, B, N, T, pc, _ptr(types, torch.int32, "types", (B, N)),
+            _ptr(radii, torch.float32, "radii", rshape), pn, pce, pq, pt,
+            _ptr(out, torch.float32, "out", self.grid_shape(B, T)), _stream())
+        if rc != MG_OK:
+            raise MolgridError(rc, "mg_forward_index_static")
         return out
 
     def mg_forward_vector(self, coords, weights, radii, natoms=None, centers=None, quats=None,

@@ -159,3 +159,26 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr
     assert r.stdout.strip() == ""
+
+
+def test_static_workspace_call_refuses_sizes_beyond_its_array_on_the_host(L):
+    """mg_forward_index_static holds its workspace in an 8 MiB static device array; a problem
+    whose tables do not fit is refused before the device is asked for anything."""
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    L.mg_forward_index_static.argtypes = [vp, ci, ci, ci] + [vp] * 8 + [vp]
+    L.mg_workspace_bytes.argtypes = [vp, ci, ci, ci, ctypes.POINTER(sz)]
+    rc, h = make(L, 0.5, 23.5, 0, 1, 1.0, 1.0)
+    assert rc == 0
+    n = sz()
+    assert L.mg_workspace_bytes(h, 400, 2040, 28, ctypes.byref(n)) == 0 and n.value > 8 << 20
+    fake = vp(4096)         # never dereferenced: the size check comes first
+    assert L.mg_forward_index_static(h, 400, 2040, 28, fake, fake, fake, None, None, None, None,
+                                     fake, None) == -4          # MG_EWORKSPACE
+    assert L.mg_forward_index_static(None, 1, 1, 1, fake, fake, fake, None, None, None, None,
+                                     fake, None) == -1          # MG_ENULL
+    assert L.mg_forward_index_static(h, 0, 1, 1, fake, fake, fake, None, None, None, None,
+                                     fake, None) == -2          # MG_ESHAPE
+    assert L.mg_forward_index_static(h, 1, 1, 1, None, fake, fake, None, None, None, None,
+                                     fake, None) == -1          # no coords
+    L.mg_gridmaker_destroy.argtypes = [vp]
+    L.mg_gridmaker_destroy(h)

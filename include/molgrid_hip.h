@@ -48,7 +48,8 @@ enum {
     MG_EWORKSPACE = -4,  /* workspace NULL, misaligned or too small             */
     MG_EHIP = -5,        /* the HIP runtime refused a launch (see mg_last_hip_error) */
     MG_EMODE = -6,       /* call not defined for this GridMaker (e.g. backward in binary mode) */
-    MG_EALIGN = -7       /* a float / int array is not 4-byte (double: 8-byte) aligned */
+    MG_EALIGN = -7,      /* a float / int array is not 4-byte (double: 8-byte) aligned */
+    MG_ENOMEM = -8       /* the host could not allocate the GridMaker handle     */
 };
 
 #define MG_MAX_POINTS 1024      /* largest supported D (points per side) */
@@ -263,12 +264,15 @@ const char *mg_strerror(int code);
 int mg_last_hip_error(void);
 
 /*
- * Tuning knobs, for measurement only (results do not depend on them beyond
- * rounding).  Process-wide; not meant to be changed while calls are in flight.
+ * Launch knobs, for measurement (results do not depend on them beyond the
+ * order of float additions).  Process-wide, each read once per call; setting
+ * one while another thread is inside a call affects that call or the next.
  *   "tile_floats"     0, 1024, 2048 or 4096 (default 0 = chosen per call from
- *                     the shapes; 4096 needs 2 or 4 wavefronts): consecutive
- *                     output floats one forward workgroup produces
+ *                     the shapes): consecutive output floats one forward
+ *                     workgroup produces
  *   "waves_per_tile"  1, 2 or 4 (default 1): wavefronts in that workgroup
+ *                     (never more than tile_floats / 512; 4096-float tiles
+ *                     take at least 2)
  *   "xcd_run"         0 or a power of two (default 0): runs of this many
  *                     consecutive tiles go to one XCD
  *   "keep_alive"      0 or 1 (default 1): every forward wavefront (index types,
@@ -279,10 +283,12 @@ int mg_last_hip_error(void);
  *   "lds_floor"       -1..65536 (default -1 = chosen per call: 6144 for 4 KB
  *                     tiles of index types, else none): least LDS bytes a forward
  *                     workgroup requests; caps how many are resident on a CU
- *   "debug"           0..3: 0 = normal, 1 = no density evaluation, 2 = no atoms,
- *                     3 = stores only (output then wrong: times parts of the kernel)
- *   "prep_stop"       0..6: end the prep kernel after that stage (output wrong)
- * Returns MG_EPARAM for an unknown key or value.
+ * Returns MG_EPARAM for an unknown key or a value outside the ranges above.
+ * No knob of the library as built by default can change a result beyond that
+ * rounding.  (A measurement build, compiled with -DMG_TIMING_AIDS, also knows
+ * "debug" 0..3 -- 1 = no density evaluation, 2 = no atoms, 3 = stores only --
+ * and "prep_stop" 0..6 -- end the prep kernel after that stage and skip the
+ * main kernel; both leave the output wrong and exist to time parts of a call.)
  */
 int mg_set_option(const char *key, int value);
 

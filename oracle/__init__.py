@@ -243,6 +243,29 @@ def forward_binary(coords, radii, T, resolution, dimension, *, types=None, weigh
     return out
 
 
+def binary_knife_edges(coords, radii, T, resolution, dimension, *, types=None, weights=None,
+                       radius_scale=1.0, radius_type_indexed=True, natoms=None, centers=None,
+                       quats=None, translations=None, eps=1e-5):
+    """uint8 mask [B,T,D,D,D]: voxels where some atom of the channel has |d^2 - r^2| < eps in
+    double, i.e. where the float predicate of the binary mode is decided by rounding."""
+    coords, B, N, natoms, centers, quats, translations = _common(
+        coords, natoms, centers, quats, translations)
+    assert (types is None) != (weights is None)
+    types = _i32(types, (B, N))
+    weights = _f32(weights, (B, N, T)) if weights is not None else None
+    radii = _f32(radii, (T,) if (radius_type_indexed or types is None) else (B, N))
+    D = points_per_side(resolution, dimension)
+    mask = np.empty((B, T, D, D, D), np.uint8)
+    lib().orc_binary_knife_edges(
+        ctypes.c_int(B), ctypes.c_int(N), ctypes.c_int(T), ctypes.c_float(resolution),
+        ctypes.c_float(dimension), ctypes.c_float(radius_scale),
+        ctypes.c_int(int(radius_type_indexed)), ctypes.c_double(eps), _p(coords, _f32p),
+        _p(types, _i32p), _p(weights, _f32p), _p(radii, _f32p), _p(natoms, _i32p),
+        _p(centers, _f32p), _p(quats, _f32p), _p(translations, _f32p),
+        mask.ctypes.data_as(ctypes.POINTER(ctypes.c_ubyte)))
+    return mask
+
+
 def _grad_ptrs(grad_out, shape):
     if grad_out.dtype == np.float64:
         G = np.ascontiguousarray(grad_out)

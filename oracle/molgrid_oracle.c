@@ -28,7 +28,8 @@
  * volume integral (erf + polynomial), lattice sum versus quadrature, box
  * variant == brute force bitwise, rotation against scipy's Rotation, 90-degree
  * rotation equivariance, one-hot vector types == index types, ball lattice
- * counts for binary mode, backward against central finite differences and the
+ * counts for binary mode (and exact-distance lattice shells for its knife
+ * edges), backward against central finite differences and the
  * translational-invariance identity, the Philox known answers, Haar and
  * uniform-box statistics of the drawn transforms, inverse(forward) = identity.
  * Nothing here is "parity unpinned"
@@ -570,6 +571,69 @@ int orc_forward_binary(int B, int N, int T, float res, float dimension,
         }
     }
     return used;
+}
+
+/*
+ * Knife edges of the binary mode: voxels where, for some atom of the channel,
+ * the exact (double) squared distance lies within `eps` of r^2, so that the
+ * float predicate above is decided by rounding rather than by geometry.  A
+ * binary grid computed in another float order could legitimately differ there
+ * and nowhere else.  mask: [B,T,D,D,D] bytes, 1 on a knife edge.  Index types
+ * when `types` is given, else vector types as in orc_forward_binary.  The atom
+ * position is the float-rounded transformed coordinate (what the predicate
+ * sees); the grid point and the radius are taken in double.
+ * Pin: an atom on a lattice point with r a multiple of the spacing has as its
+ * knife edges exactly the lattice points with i^2+j^2+k^2 = (r/res)^2.
+ */
+int orc_binary_knife_edges(int B, int N, int T, float res, float dimension,
+                           float radius_scale, int radius_type_indexed, double eps,
+                           const float *coords, const int32_t *types, const float *weights,
+                           const float *radii, const int32_t *natoms, const float *centers,
+                           const float *quats, const float *translations,
+                           unsigned char *mask)
+{
+    setup S;
+    make_setup(&S, B, N, T, (double)res, (double)dimension, 1.0, (double)radius_scale,
+               radius_type_indexed, 1);
+    const int D = S.D;
+    const size_t D3 = (size_t)D * D * D, per_ex = D3 * T;
+    for (int b = 0; b < B; ++b) {
+        unsigned char *ex = mask + (size_t)b * per_ex;
+        memset(ex, 0, per_ex);
+        xform X;
+        load_xform(&X, b, centers, quats, translations);
+        const int n = atom_count(&S, natoms, b);
+        for (int a = 0; a < n; ++a) {
+            double pos[3];
+            if (!atom_position(&S, &X, coords, b, a, pos)) continue;
+            const double af[3] = {(double)(float)pos[0], (double)(float)pos[1], (double)(float)pos[2]};
+            const int t0 = types ? types[(size_t)b * N + a] : 0;
+            const int t1 = types ? t0 + 1 : T;
+            if (types && (t0 < 0 || t0 >= T)) continue;
+            for (int t = t0; t < t1; ++t) {
+                if (!types && !(weights[((size_t)b * N + a) * T + t] > 0.0f)) continue;
+                const float rad = (radius_type_indexed || !types) ? radii[t] : radii[(size_t)b * N + a];
+                const double r = (double)radius_scale * (double)rad;
+                if (!(r > 0.0)) continue;
+                int lo[3], hi[3];
+                for (int m = 0; m < 3; ++m)
+                    axis_range(&S, X.c[m] - S.half, af[m], r + sqrt(eps) + S.res, &lo[m], &hi[m]);
+                for (int i = lo[0]; i <= hi[0]; ++i) {
+                    const double dx = (X.c[0] - S.half + i * S.res) - af[0];
+                    for (int j = lo[1]; j <= hi[1]; ++j) {
+                        const double dy = (X.c[1] - S.half + j * S.res) - af[1];
+                        for (int k = lo[2]; k <= hi[2]; ++k) {
+                            const double dz = (X.c[2] - S.half + k * S.res) - af[2];
+                            const double d2 = dx * dx + dy * dy + dz * dz;
+                            if (fabs(d2 - r * r) < eps)
+                                ex[(size_t)t * D3 + ((size_t)i * D + j) * D + k] = 1;
+                        }
+                    }
+                }
+            }
+        }
+    }
+    return 0;
 }
 
 /* ------------------------------------------------------------------------ */

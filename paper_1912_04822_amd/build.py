@@ -9,6 +9,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmolgrid_hip.so")
+# measurement build: the same sources with -DMG_TIMING_AIDS (kernel phases can be switched off
+# to time the rest; such runs write wrong grids, so the release library has none of it)
+LIB_TIMING = os.path.join(HERE, "libmolgrid_hip_timing.so")
 
 # -ffp-contract=off: nothing is fused behind the code's back (the binary-mode
 # predicate and the double-precision transform are specified operation by
@@ -26,9 +29,10 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build_library(verbose: bool = False) -> str:
+def build_library(verbose: bool = False, timing_aids: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB] + sources()
+    out = LIB_TIMING if timing_aids else LIB
+    cmd = [hipcc] + HIPCC_FLAGS + (["-DMG_TIMING_AIDS"] if timing_aids else []) + ["-o", out] + sources()
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -38,9 +42,9 @@ def build_library(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + msgs)
     if verbose and msgs.strip():
         print(msgs)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    print(build_library(verbose=True, timing_aids="--timing-aids" in sys.argv[1:]))
     sys.exit(0)

@@ -25,13 +25,36 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
-int g_tile_floats = 0;       // 0: chosen by the launcher
-int g_waves_per_tile = 1;
-int g_xcd_run = 0;
-int g_lds_floor = -1;     // < 0: chosen by the launcher
-int g_tile_order = 0;
-int g_keep_alive = 1;
-int g_debug = 0;
+// Launch knobs (mg_set_option): process-wide, read once per call.  Atomic so that a thread
+// that sets one while another thread makes a call is a defined (if unordered) program.
+std::atomic<int> g_tile_floats{0};       // 0: chosen by the launcher
+std::atomic<int> g_waves_per_tile{1};
+std::atomic<int> g_xcd_run{0};
+std::atomic<int> g_lds_floor{-1};        // < 0: chosen by the launcher
+std::atomic<int> g_tile_order{0};
+std::atomic<int> g_keep_alive{1};
+#ifdef MG_TIMING_AIDS
+std::atomic<int> g_debug{0};             // measurement build only: kernel phases switched off
+std::atomic<int> g_prep_stop{0};         // measurement build only: prep kernel ended after a stage
+#endif
+
+int timing_debug()
+{
+#ifdef MG_TIMING_AIDS
+    return g_debug.load(std::memory_order_relaxed);
+#else
+    return 0;
+#endif
+}
+
+int timing_prep_stop()
+{
+#ifdef MG_TIMING_AIDS
+    return g_prep_stop.load(std::memory_order_relaxed);
+#else
+    return 0;
+#endif
+}
 
 // The caller's timing events for the main kernel of this call, if set (cleared by the call).
 mg::KernelEvents take_events()
@@ -138,7 +161,7 @@ int mg_gridmaker_create_subgrids(mg_gridmaker **out, float resolution, float dim
     const double dd = std::floor((double)dimension / (double)resolution + 0.5) + 1.0;
     if (!(dd >= 1.0) || dd > (double)MG_MAX_POINTS) return MG_ESHAPE;
     mg_gridmaker *gm = new (std::nothrow) mg_gridmaker;
-    if (!gm) return MG_EHIP;
+    if (!gm) return MG_ENOMEM;
     const int D = (int)dd;
     const double g = (double)gaussian_radius_multiple;
     const double c = (1.0 + 2.0 * g * g) / (2.0 * g);
@@ -245,10 +268,13 @@ static int forward_call(const mg_gridmaker *gm, int B, int N, int T, const float
     const mg::Batch bt = make_batch(gm, B, N, T, coords, types, weights, radii, natoms, centers,
                                     quats, translations);
     const mg::Workspace ws = mg::carve_workspace(gm->gs, gm->sub.count, workspace, bt.B, N, T);
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, (hipStream_t)stream));
-    if (rc != MG_OK) return rc;
-    return hip_status(mg::launch_forward(gm->gs, bt, ws, out, out_is_double, g_tile_floats,
-                                         g_waves_per_tile, g_xcd_run, g_lds_floor, g_debug, g_tile_order, g_keep_alive,
+    const int stop = timing_prep_stop();
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, stop, (hipStream_t)stream));
+    if (rc != MG_OK || stop != 0) return rc;    // a prep kernel cut short leaves no tables to read
+    const auto knob = [](const std::atomic<int> &k) { return k.load(std::memory_order_relaxed); };
+    return hip_status(mg::launch_forward(gm->gs, bt, ws, out, out_is_double, knob(g_tile_floats),
+                                         knob(g_waves_per_tile), knob(g_xcd_run), knob(g_lds_floor),
+                                         timing_debug(), knob(g_tile_order), knob(g_keep_alive),
                                          take_events(), (hipStream_t)stream));
 }
 
@@ -341,8 +367,9 @@ static int backward_call(const mg_gridmaker *gm, int B, int N, int T, const floa
     const bool sub = gm->sub.count > 1;
     float *gc = (sub && grad_coords) ? ws.gtmp : grad_coords;
     float *gw = (sub && grad_weights) ? ws.wtmp : grad_weights;
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, gc, gw, (hipStream_t)stream));
-    if (rc != MG_OK) return rc;
+    const int stop = timing_prep_stop();
+    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, gc, gw, stop, (hipStream_t)stream));
+    if (rc != MG_OK || stop != 0) return rc;    // a prep kernel cut short leaves no tables to read
     rc = hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, grad_is_double, gc, gw,
                                         take_events(), (hipStream_t)stream));
     if (rc != MG_OK || !sub) return rc;
@@ -414,6 +441,7 @@ const char *mg_strerror(int code)
     case MG_EHIP: return "the HIP runtime refused a launch (mg_last_hip_error has the hipError_t)";
     case MG_EMODE: return "call not defined for this GridMaker (binary backward, or vector types without radius_type_indexed)";
     case MG_EALIGN: return "an array argument is not 4-byte aligned";
+    case MG_ENOMEM: return "out of host memory";
     default: return "unknown error code";
     }
 }
@@ -460,8 +488,10 @@ int mg_set_option(const char *key, int value)
         g_lds_floor = value;
         return MG_OK;
     }
+#ifdef MG_TIMING_AIDS
     if (std::strcmp(key, "prep_stop") == 0) {
-        mg::g_prep_stop = value;
+        if (value < 0 || value > 6) return MG_EPARAM;
+        g_prep_stop = value;
         return MG_OK;
     }
     if (std::strcmp(key, "debug") == 0) {
@@ -469,6 +499,7 @@ int mg_set_option(const char *key, int value)
         g_debug = value;
         return MG_OK;
     }
+#endif
     return MG_EPARAM;
 }
 

@@ -85,6 +85,8 @@ struct Box {
 
 constexpr int kSlotCap = 1024;      // live slots of a group of 128 rows: at most 8 per row
 constexpr int kMaxCulledSegs = 8;   // boxes with more z-segments per row take the plain loop
+constexpr int kMaxCulledRows = 32768;   // ... and so do boxes with more rows: below that, row / nr by a
+                                        // float reciprocal is exact (error <= rows * 2e-7 < 0.5)
 
 // grid points within `reach` of the atom along each axis, padded by 1e-3 steps
 __device__ inline bool atom_box(const GridSpec &gs, float reach, const float4 &a, float ox, float oy,
@@ -178,17 +180,18 @@ __device__ inline void reduce_channel_box(const BwdParams &p, const GT *Gc, cons
 {
     const GridSpec &gs = p.gs;
     const int per_plane = bx.nr * bx.ns;
-    const int slots = bx.np * per_plane;
-    const float inv_pp = 1.0f / (float)per_plane, inv_ns = 1.0f / (float)bx.ns;
+    const int slots = bx.np * per_plane;        // at most D^3 / 4 < 2^31
     const float s = p.sk / r, step = gs.res * s;
     const float azs = (a.z - oz) * s;
     // scaled distance of the box's first row; rows step by `step`
     const float ux0 = (a.x - (ox + (float)bx.ilo * gs.res)) * s;
     const float uy0 = (a.y - (oy + (float)bx.jlo * gs.res)) * s;
     for (int sl = (int)(threadIdx.x & 63u); sl < slots; sl += 64) {
-        const int pi = (int)(((float)sl + 0.5f) * inv_pp);
+        // integer division: a box of hundreds of voxels per side has more slots than a float
+        // holds exactly
+        const int pi = sl / per_plane;
         const int rem = sl - pi * per_plane;
-        const int row = (int)(((float)rem + 0.5f) * inv_ns);
+        const int row = rem / bx.ns;
         const int seg = rem - row * bx.ns;
         const float ux = fmaf(-(float)pi, step, ux0), uy = fmaf(-(float)row, step, uy0);
         SlotData d;
@@ -208,7 +211,7 @@ __device__ inline void reduce_channel(const BwdParams &p, const GT *G, int t, si
                                       float oz, unsigned char *marks, float &sx, float &sy,
                                       float &sz, float &sv)
 {
-    if (bx.ns > kMaxCulledSegs) {
+    if (bx.ns > kMaxCulledSegs || bx.np * bx.nr > kMaxCulledRows) {
         reduce_channel_box<ALIGNED, WANT_VALUE>(p, G + (size_t)t * D3, a, r, bx, ox, oy, oz, sx, sy,
                                                 sz, sv);
         return;
@@ -326,14 +329,13 @@ __device__ inline void for_each_slot(const BwdParams &p, const float4 &a, float 
     const float ux0 = (a.x - (ox + (float)bx.ilo * gs.res)) * s;
     const float uy0 = (a.y - (oy + (float)bx.jlo * gs.res)) * s;
     const unsigned off0 = ((unsigned)bx.ilo * D + (unsigned)bx.jlo) * D;   // the box's first row
-    if (bx.ns > kMaxCulledSegs) {       // very many segments per row: every slot of the box
+    if (bx.ns > kMaxCulledSegs || bx.np * bx.nr > kMaxCulledRows) {     // a very large box: every slot of it
         const int per_plane = bx.nr * bx.ns;
-        const int slots = bx.np * per_plane;
-        const float inv_pp = 1.0f / (float)per_plane, inv_ns = 1.0f / (float)bx.ns;
+        const int slots = bx.np * per_plane;        // at most D^3 / 4 < 2^31
         for (int sl = lane; sl < slots; sl += 64) {
-            const int pi = (int)(((float)sl + 0.5f) * inv_pp);
+            const int pi = sl / per_plane;          // integer division: exact for any box
             const int rem = sl - pi * per_plane;
-            const int row = (int)(((float)rem + 0.5f) * inv_ns);
+            const int row = rem / bx.ns;
             const int seg = rem - row * bx.ns;
             body(off0 + ((unsigned)pi * D + (unsigned)row) * D, (bx.seg0 + seg) << 2,
                  fmaf(-(float)pi, step, ux0), fmaf(-(float)row, step, uy0));

@@ -128,7 +128,16 @@ struct KernelEvents {
     hipEvent_t start, stop;
 };
 
-extern int g_prep_stop;                 // timing aid: stop the prep kernel after a stage
+// Timing aids (kernel phases switched off, prep kernel ended after a stage) give wrong grids
+// and exist only in a library built with -DMG_TIMING_AIDS (a measurement build); in the
+// release library the tests below are compile-time false and their branches vanish.
+#ifdef MG_TIMING_AIDS
+#define MG_DEBUG_IS(p, n) ((p).debug == (n))
+#define MG_STOP_IS(stop, n) ((stop) == (n))
+#else
+#define MG_DEBUG_IS(p, n) false
+#define MG_STOP_IS(stop, n) false
+#endif
 
 // Launchers (each enqueues on `stream`, returns the hipError_t of the launch).
 hipError_t launch_transform(int B, int N, const float *coords, const float *centers,
@@ -138,7 +147,7 @@ hipError_t launch_draw_transforms(uint64_t seed, uint64_t draw, int B, bool rand
                                   float max_translation, float *quats, float *translations,
                                   hipStream_t stream);
 hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
-                       float *grad_coords_to_clear, float *grad_weights_to_clear,
+                       float *grad_coords_to_clear, float *grad_weights_to_clear, int stop,
                        hipStream_t stream);
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                           void *out, bool out_is_double, int tile_floats, int waves_per_tile,

@@ -2,9 +2,10 @@
 // types, binary occupancy), GridMaker section of the paper.
 //
 // Design (gfx950, wave64).  Each channel of the output (D*D*D floats, z fastest)
-// is cut into flat tiles of `tile_floats` consecutive floats (2048 = 8192 B by
-// default), whatever rows and x-planes that run happens to cover; with the
-// usual grids (D = 48, 96) every tile starts on a 4 KB boundary of the output.
+// is cut into flat tiles of `tile_floats` consecutive floats (1024 = 4096 B by
+// default, 2048 when a tile is expected to meet many records), whatever rows and
+// x-planes that run happens to cover; with the usual grids (D = 48, 96) every
+// tile starts on a 4 KB boundary of the output.
 // One workgroup of 1, 2 or 4 wavefronts produces one tile; its wavefronts split
 // the atoms and, at the end, the 2 KB chunks of the tile between them:
 //   1. the workgroup loads the records of the channel's atoms that can reach the
@@ -310,7 +311,7 @@ __device__ inline PairHit pair_test(const TileCtx &cx, const FwdParams &p, const
     h.cd.pxB = 0.0f;
     if (jaB < jbB)      // uniform: most tiles of small tile sizes lie in one plane
         h.nB = plane_rows<BINARY>(cx, p, at, gxB, xcB, jaB, jbB, sks, inv_stepk, fyi, fzi, h.cd.pxB, jloB);
-    if (cx.debug == 1) { h.nA = 0; h.nB = 0; }
+    if (MG_DEBUG_IS(cx, 1)) { h.nA = 0; h.nB = 0; }
     if (h.nA == 0) jloA = 0;        // both are packed into bit fields below
     if (h.nB == 0) jloB = 0;
     if (BINARY) {
@@ -751,12 +752,12 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     const float4 cen = *reinterpret_cast<const float4 *>(p.gcen + 4 * b);   // one 16-byte load
     const TileGeom tg = tile_geom<ITERS>(p, D, tile_in_chan);
     int r0 = 0, r1 = 0;
-    if (p.debug != 3) {         // debug 3, a timing aid: nothing but the zero stores
+    if (!MG_DEBUG_IS(p, 3)) {   // timing aid 3: nothing but the zero stores
         r0 = span[tg.i_lo].x;
         r1 = span[tg.i_hi].y;
     }
     asm volatile("" ::"s"(r0), "s"(r1), "s"(cen.x), "s"(cen.y), "s"(cen.z));  // all in flight before the first wait
-    if (p.debug == 2) r1 = r0;
+    if (MG_DEBUG_IS(p, 2)) r1 = r0;
     tile_body<VECTOR, BINARY, ALIGNED, ITERS, NW, OUT>(p, lds, b, t, tg, r0, r1, cen);
     asm volatile("" ::"v"(ka.x), "v"(ka.y), "v"(ka.z), "v"(ka.w));     // the keep-alive read is waited for here
 }
@@ -817,7 +818,8 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     p.tile_floats = fg.tile_floats;
     p.div_magic = ((1ULL << 40) + (unsigned long long)gs.D - 1ULL) / (unsigned long long)gs.D;
     const int iters = tile_floats / 512;
-    const int nw = waves_per_tile < iters ? waves_per_tile : iters;
+    int nw = waves_per_tile < iters ? waves_per_tile : iters;
+    if (iters == 8 && nw < 2) nw = 2;           // 16 KB tiles are built for two or four wavefronts
     p.pos_major = tile_order == 1 ? 1u : 0u;
     p.tiles = p.pos_major ? (unsigned)bt.B * (unsigned)bt.T : (unsigned)fg.tiles;
     p.tiles_magic = magic64(p.tiles);

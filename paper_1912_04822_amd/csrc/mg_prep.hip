@@ -207,8 +207,7 @@ struct ExLayout {       // LDS, in ints
     __host__ __device__ int rmax() const { return 2 * K; }
     __host__ __device__ int rad() const { return 2 * K + Tg; }                  // float[Tg]
     __host__ __device__ int part() const { return 2 * K + 2 * Tg; }
-    __host__ __device__ int key() const { return 2 * K + 2 * Tg + 32; }         // ushort[N]
-    __host__ __device__ int order() const { return key() + (N + 1) / 2; }       // ushort[N]
+    __host__ __device__ int order() const { return 2 * K + 2 * Tg + 32; }       // ushort[N]
     __host__ __device__ int ints() const { return order() + (N + 1) / 2; }
 };
 
@@ -221,7 +220,7 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     const int b = blockIdx.x, tid = threadIdx.x;
     const int bs = source_example(bt.sub.count, b);       // whose atoms and pose this (virtual) example reads
     const int N = bt.N, T = bt.T, D = gs.D;
-    if (stop == 1) return;
+    if (MG_STOP_IS(stop, 1)) return;
     const int Tg = VECTOR ? 1 : T;      // groups per example
     const int nb = D + 3;               // bins per group; bin D+2 holds the culled atoms
     ExLayout L;
@@ -232,7 +231,6 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     int *s_rmax = s_mem + L.rmax();
     float *s_rad = reinterpret_cast<float *>(s_mem + L.rad());
     int *s_part = s_mem + L.part();
-    unsigned short *s_key = reinterpret_cast<unsigned short *>(s_mem + L.key());
     unsigned short *s_order = reinterpret_cast<unsigned short *>(s_mem + L.order());
 
     // Everything this thread needs from HBM is requested before anything is waited for:
@@ -282,7 +280,7 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
 
     if (!VECTOR && gs.radius_type_indexed)
         for (int k = tid; k < Tg; k += kExThreads) s_rad[k] = bt.radii[k];
-    if (stop == 2) return;
+    if (MG_STOP_IS(stop, 2)) return;
     for (int k = tid; k < K; k += kExThreads) s_cnt[k] = 0;
     for (int k = tid; k < Tg; k += kExThreads) s_rmax[k] = 0;
     __syncthreads();
@@ -327,10 +325,9 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
         } else {
             clear_grads(gclear, wclear, (size_t)b * N + a, T);   // no group owns this atom
         }
-        s_key[a] = (unsigned short)my_key[u];
     }
     __syncthreads();
-    if (stop == 3) return;
+    if (MG_STOP_IS(stop, 3)) return;
 
     // ---- 2. exclusive scan of the counts ----
     const int chunk = (K + kExThreads - 1) / kExThreads;
@@ -356,7 +353,7 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
         run += s_cnt[k];
     }
     __syncthreads();
-    if (stop == 4) return;
+    if (MG_STOP_IS(stop, 4)) return;
 
     // ---- 3. atoms into their bins in any order; group descriptors and spans meanwhile ----
 #pragma unroll
@@ -378,7 +375,7 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
         ws.range[((size_t)b * T + tg) * D + i] = make_int2(s_pos[tg * nb + lo], s_pos[tg * nb + hi + 1]);
     }
     __syncthreads();
-    if (stop == 5) return;
+    if (MG_STOP_IS(stop, 5)) return;
 
     // ---- 4. every atom writes its record where its rank inside the bin puts it ----
     // (rank = how many atoms of the bin have a smaller index: the order in which the
@@ -415,7 +412,7 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
     const int b = blockIdx.y, t = blockIdx.x, lane = threadIdx.x;
     const int bs = source_example(bt.sub.count, b);       // whose atoms and pose this (virtual) example reads
     const int N = bt.N, T = bt.T, D = gs.D;
-    if (stop == 1) return;
+    if (MG_STOP_IS(stop, 1)) return;
     int n = N;
     if (bt.natoms) {
         n = bt.natoms[bs];
@@ -448,13 +445,13 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
             }
         }
     }
-    if (stop == 2) { if (less + eq == 12345) ws.rot[0] = 1.0f; return; }
+    if (MG_STOP_IS(stop, 2)) { if (less + eq == 12345) ws.rot[0] = 1.0f; return; }
     int M, first;
     const int my_first = wave_exclusive_scan(eq, &M);
     (void)wave_exclusive_scan(less, &first);
     if (VECTOR) first = 0;
     if (t == 0 && lane < 9) ws.rot[b * 12 + lane] = (float)X.R[lane];
-    if (stop == 3) { if (M + first == 12345) ws.rot[0] = 1.0f; return; }
+    if (MG_STOP_IS(stop, 3)) { if (M + first == 12345) ws.rot[0] = 1.0f; return; }
 
     float vec_reach = 0.0f;         // reach of the widest channel, for vector types
     if (VECTOR) {
@@ -510,7 +507,7 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
             s_bin[m] = (unsigned short)bin;
         }
         lds_sync();
-        if (stop == 4) return;
+        if (MG_STOP_IS(stop, 4)) return;
         // ---- 3. bin starts (exclusive scan over the bins) ----
         const int bper = (nbins + 63) / 64;
         const int k0 = min(nbins, lane * bper), k1 = min(nbins, k0 + bper);
@@ -532,7 +529,7 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
             ws.range[group * D + i] = make_int2(first + s_pos[lo], first + (hi + 1 < nbins ? s_pos[hi + 1] : L));
         }
         lds_sync();
-        if (stop == 5) return;
+        if (MG_STOP_IS(stop, 5)) return;
         // ---- 5. placement: any order inside a bin, then sort each bin by atom order ----
         for (int m = lane; m < M; m += 64) {
             const int bin = s_bin[m];
@@ -552,7 +549,7 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
             }
         }
         lds_sync();
-        if (stop == 6) return;
+        if (MG_STOP_IS(stop, 6)) return;
         // ---- 6. records in sorted order (the transform is cheap: done again) ----
         for (int pos = lane; pos < M; pos += 64) {
             if (pos < L) {
@@ -667,11 +664,9 @@ hipError_t launch_transform(int B, int N, const float *coords, const float *cent
     return hipGetLastError();
 }
 
-int g_prep_stop = 0;
 hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws, float *gclear,
-                       float *wclear, hipStream_t stream)
+                       float *wclear, int stop, hipStream_t stream)
 {
-    const int stop = g_prep_stop;
     const bool vec = bt.weights != nullptr;
     ExLayout L;
     L.Tg = vec ? 1 : bt.T;

@@ -35,14 +35,17 @@ class MolgridError(RuntimeError):
         super().__init__("%s: %s (code %d)" % (where, strerror(code), code))
 
 
-def lib() -> ctypes.CDLL:
-    """Load libmolgrid_hip.so (built by ``paper_1912_04822_amd.build``); raise if absent."""
+def lib(path: Optional[str] = None) -> ctypes.CDLL:
+    """Load libmolgrid_hip.so (built by ``paper_1912_04822_amd.build``); raise if absent.
+    ``path`` (first call only) names another build of the same library, e.g. the measurement
+    build with the timing aids."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
+        path = path or LIB_PATH
+        if not os.path.exists(path):
             raise FileNotFoundError(
-                "HIP library not built: %s (run python -m paper_1912_04822_amd.build)" % LIB_PATH)
-        L = ctypes.CDLL(LIB_PATH)
+                "HIP library not built: %s (run python -m paper_1912_04822_amd.build)" % path)
+        L = ctypes.CDLL(path)
         vp, ci, cf, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
         L.mg_gridmaker_create.restype = ci
         L.mg_gridmaker_create.argtypes = [ctypes.POINTER(vp), cf, cf, ci, ci, cf, cf]
@@ -196,7 +199,9 @@ class GridMaker:
         self.D = d.value
         self.binary = bool(binary)
         self.radius_type_indexed = bool(radius_type_indexed)
-        self._ws: Optional[torch.Tensor] = None
+        # workspaces the binding allocated, one per (device, stream): calls on different
+        # streams may run at the same time and must not share tables
+        self._ws = {}
 
     def __del__(self):
         h = getattr(self, "_h", None)
@@ -220,9 +225,12 @@ class GridMaker:
         need = self.workspace_bytes(B, N, T)
         if workspace is not None:
             return workspace, workspace.numel() * workspace.element_size()
-        if self._ws is None or self._ws.numel() < need or self._ws.device != device:
-            self._ws = torch.empty(need, dtype=torch.uint8, device=device)
-        return self._ws, self._ws.numel()
+        key = (str(device), torch.cuda.current_stream().cuda_stream)    # the stream the call uses
+        ws = self._ws.get(key)
+        if ws is None or ws.numel() < need:
+            ws = torch.empty(need, dtype=torch.uint8, device=device)
+            self._ws[key] = ws
+        return ws, ws.numel()
 
     def _common(self, coords, natoms, centers, quats, translations):
         B, N, _ = coords.shape

@@ -132,7 +132,7 @@ def test_calls_reject_bad_arguments_before_any_launch(L):
     assert L.mg_forward_vector(hp, 1, 1, 1, fake, fake, fake, None, None, None, None, fake, fake,
                                1 << 20, None) == -6
     L.mg_strerror.restype = ctypes.c_char_p
-    for code in range(-7, 1):
+    for code in range(-8, 1):
         assert len(L.mg_strerror(code)) > 1
     assert b"unknown" in L.mg_strerror(-99)
     L.mg_set_option.argtypes = [ctypes.c_char_p, ci]
@@ -140,6 +140,12 @@ def test_calls_reject_bad_arguments_before_any_launch(L):
     assert L.mg_set_option(b"tile_floats", 0) == 0
     assert L.mg_set_option(b"tile_floats", 1000) == -3
     assert L.mg_set_option(b"nope", 0) == -3
+    # the timing aids (which write wrong grids) are not in the library as built by default
+    assert L.mg_set_option(b"debug", 1) == -3
+    assert L.mg_set_option(b"prep_stop", 3) == -3
+    for key, bad in ((b"waves_per_tile", 3), (b"waves_per_tile", 0), (b"xcd_run", -1),
+                     (b"lds_floor", -2), (b"keep_alive", -1), (b"tile_order", -1)):
+        assert L.mg_set_option(key, bad) == -3
     for key, good, bad, default in ((b"keep_alive", 0, 2, 1), (b"tile_order", 1, 2, 0),
                                     (b"lds_floor", 8192, 70000, -1), (b"xcd_run", 8, 12, 0)):
         assert L.mg_set_option(key, good) == 0

@@ -2,7 +2,8 @@
 
 The oracle's cutoff-box variant finishes each of these in seconds, so every output
 element is compared (not a sample): protein-ligand forward (B=50), its binary mode, its
-backward, the vector-typed forward, and two 16-example chunks of the high-resolution case.
+backward, the vector-typed forward and backward, and all eight 16-example chunks of the
+high-resolution case.
 """
 import numpy as np
 import pytest
@@ -68,8 +69,20 @@ def test_protein_ligand_binary_full_bit_exact(mg, c1):
     del out
     ref = oracle.forward_binary(w.coords, w.radii, w.T, w.resolution, w.dimension, types=w.types,
                                 **okw(w))
-    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
-    # voxels where the double-precision distance is within 1e-5 of r^2 ("knife edges"): count them
+    # Knife edges: voxels where some atom's exact squared distance is within 1e-5 of r^2, i.e.
+    # where rounding rather than geometry decides the float predicate.  A mismatch outside that
+    # set would be an error of the kernel, one inside it a difference in float order; the two
+    # sides follow the same order, so there is none at all.
+    edges = oracle.binary_knife_edges(w.coords, w.radii, w.T, w.resolution, w.dimension,
+                                      types=w.types, **okw(w))
+    mismatch = got.view(np.uint32) != ref.view(np.uint32)
+    n_edges, n_mismatch = int(edges.sum()), int(mismatch.sum())
+    print("binary, protein-ligand batch: %d ones of %d voxels, %d knife-edge voxels "
+          "(|d^2 - r^2| < 1e-5), %d mismatches, %d of them off a knife edge"
+          % (int(got.sum()), got.size, n_edges, n_mismatch, int((mismatch & (edges == 0)).sum())))
+    assert not (mismatch & (edges == 0)).any()
+    assert n_mismatch == 0
+    assert 0 < n_edges < 1e-4 * got.size
     assert got.sum() > 1e5
 
 
@@ -102,7 +115,24 @@ def test_protein_ligand_vector_forward_full(mg, c1):
     assert got.min() >= 0.0
 
 
-@pytest.mark.parametrize("chunk", [0, 5])
+def test_protein_ligand_vector_backward_full(mg, c1):
+    """Both gradients of the vector-typed path at the full size (50 x 2040 atoms x 28 channels)."""
+    w = c1
+    gm = mg.GridMaker(w.resolution, w.dimension, radius_type_indexed=True)
+    gc, gw = gm.mg_backward_vector(dev(w.coords), dev(w.weights), dev(w.radii), dev(w.grad_out),
+                                   **dkw(w))
+    torch.cuda.synchronize()
+    gc, gw = gc.cpu().numpy(), gw.cpu().numpy()
+    rc, rw = oracle.backward_vector(w.coords, w.weights, w.radii, w.resolution, w.dimension,
+                                    w.grad_out, **okw(w))
+    assert gc.shape == (50, 2040, 3) and gw.shape == (50, 2040, 28)
+    for b in range(w.B):
+        assert np.abs(gc[b] - rc[b]).max() <= GRAD_RTOL * np.abs(rc[b]).max(), b
+        assert np.abs(gw[b] - rw[b]).max() <= GRAD_RTOL * np.abs(rw[b]).max(), b
+    assert ((rc == 0) == (gc == 0)).all()
+
+
+@pytest.mark.parametrize("chunk", range(8))
 def test_high_resolution_chunk(mg, chunk):
     """B=128 is produced in chunks of 16 examples; each chunk is one call."""
     w = workloads.large_chunk(chunk)

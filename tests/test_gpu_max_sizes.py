@@ -97,3 +97,27 @@ def test_65535_channels(mg):
     assert np.abs(g - rg).max() <= GRAD_RTOL * np.abs(rg).max()
     with pytest.raises(mg.MolgridError):
         gm.workspace_bytes(B, N, T + 1)
+
+
+def test_backward_boxes_of_hundreds_of_voxels_per_side(mg):
+    """Radii so large that an atom's cutoff box spans the whole 256^3 grid: millions of 4-voxel
+    slots per atom (more than a float counts exactly), the every-slot-of-the-box path of the
+    backward kernel, index and vector types.  The oracle's box variant visits the same voxels."""
+    D, res, T = 256, 0.25, 2
+    dim = (D - 1) * res
+    rng = np.random.default_rng(44)
+    coords = rng.uniform(-20.0, 20.0, (1, 3, 3)).astype(np.float32)
+    types = np.array([[0, 1, 1]], np.int32)
+    radii = np.array([30.0, 22.0], np.float32)          # cutoff 45 A and 33 A: 180 / 132 voxels
+    G = rng.standard_normal((1, T, D, D, D)).astype(np.float32)
+    gm = mg.GridMaker(res, dim, radius_type_indexed=True)
+    assert gm.D == D
+    dG = dev(G)
+    g = gm.mg_backward_index(dev(coords), dev(types), dev(radii), T, dG).cpu().numpy()
+    rg = oracle.backward_index(coords, types, radii, T, res, dim, G)
+    assert np.abs(g - rg).max() <= GRAD_RTOL * np.abs(rg).max()
+    weights = rng.uniform(0.1, 1.0, (1, 3, T)).astype(np.float32)
+    gc, gw = gm.mg_backward_vector(dev(coords), dev(weights), dev(radii), dG)
+    rc, rw = oracle.backward_vector(coords, weights, radii, res, dim, G)
+    assert np.abs(gc.cpu().numpy() - rc).max() <= GRAD_RTOL * np.abs(rc).max()
+    assert np.abs(gw.cpu().numpy() - rw).max() <= GRAD_RTOL * np.abs(rw).max()

@@ -16,6 +16,13 @@ GRID_TOL = 1e-5
 GRAD_RTOL = 1e-4
 
 
+def grid_tol(ref):
+    """1e-5 as long as no voxel sum passes 8 (every workload of the paper's shape: their sums stay
+    below 3); where thousands of atoms pile up on a voxel the bound follows the largest sum, 2e-6
+    of it (about 17 float spacings of that value), and is never below 1e-5."""
+    return max(GRID_TOL, 2e-6 * float(np.max(ref)))
+
+
 @pytest.fixture(scope="module")
 def mg():
     from paper_1912_04822_amd import molgrid
@@ -171,7 +178,8 @@ def test_forward_protein_ligand_subset_and_determinism(mg):
     assert got.max() > 1.0
     again = run_forward_index(mg, w)
     assert np.array_equal(got.view(np.uint32), again.view(np.uint32))
-    for tile_floats, waves in ((1024, 1), (1024, 2), (2048, 2), (2048, 4), (4096, 2), (4096, 4)):
+    for tile_floats, waves in ((1024, 1), (1024, 2), (2048, 2), (2048, 4), (4096, 1), (4096, 2),
+                               (4096, 4)):
         mg.set_option("tile_floats", tile_floats)
         mg.set_option("waves_per_tile", waves)
         try:
@@ -208,7 +216,9 @@ def test_forward_single_type_many_atoms(mg):
     w.types[:] = 3
     got = run_forward_index(mg, w)
     ref = oracle_forward_index(w)
-    assert np.abs(got - ref).max() <= 2 * GRID_TOL      # sums reach ~10 here
+    assert ref.max() > 5                                # 2040 atoms of one type pile up
+    err = np.abs(got - ref).max()
+    assert err <= grid_tol(ref), (err, ref.max())
     assert got[:, :3].max() == 0 and got[:, 4:].max() == 0
 
 

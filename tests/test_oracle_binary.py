@@ -92,3 +92,49 @@ def test_vector_typed_binary_uses_positive_weights_and_channel_radii():
     b = oracle.forward_binary(w.coords, w.radii, w.T, w.resolution, w.dimension, weights=onehot,
                               **kw)
     assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("r_steps,res", [(3, 0.5), (5, 0.5), (6, 0.25), (2, 0.75)])
+def test_knife_edges_of_a_lattice_atom_are_the_exact_distance_shell(r_steps, res):
+    """An atom on a lattice point whose radius is a whole number of grid steps: the voxels at
+    distance exactly r are the lattice points with i^2+j^2+k^2 = (r/res)^2 (counted in integers),
+    and those are all the knife edges there are."""
+    reach = r_steps + 2
+    D = 2 * reach + 1
+    r = r_steps * res                      # multiples of 0.25: exact in float
+    mask = oracle.binary_knife_edges(np.zeros((1, 1, 3), np.float32), np.array([r], np.float32), 1,
+                                     res, (D - 1) * res, types=np.zeros((1, 1), np.int32))
+    want = np.zeros((D, D, D), np.uint8)
+    for i in range(-reach, reach + 1):
+        for j in range(-reach, reach + 1):
+            for k in range(-reach, reach + 1):
+                if i * i + j * j + k * k == r_steps * r_steps:
+                    want[i + reach, j + reach, k + reach] = 1
+    assert want.sum() >= 6
+    assert np.array_equal(mask[0, 0], want)
+
+
+def test_knife_edges_cover_every_disagreement_between_float_and_double_predicates():
+    """Where the float predicate of the binary mode and the same test in double disagree, the
+    voxel is a knife edge (and generic inputs have very few of them)."""
+    w = workloads.ragged_small()
+    kw = dict(types=w.types, natoms=w.extra["natoms"], centers=w.centers, quats=w.quats,
+              translations=w.translations)
+    out = oracle.forward_binary(w.coords, w.radii, w.T, w.resolution, w.dimension, **kw)
+    mask = oracle.binary_knife_edges(w.coords, w.radii, w.T, w.resolution, w.dimension, **kw)
+    pos = oracle.transform(w.coords, w.centers, w.quats, w.translations).astype(np.float64)
+    ax = np.arange(w.D) * w.resolution - 0.5 * (w.D - 1) * w.resolution
+    nat = w.extra["natoms"]
+    for b in range(w.B):
+        inside = np.zeros((w.T, w.D, w.D, w.D), bool)
+        for a in range(int(nat[b])):
+            t = int(w.types[b, a])
+            if t < 0 or t >= w.T:
+                continue
+            g = [w.centers[b, m].astype(np.float64) + ax for m in range(3)]
+            d2 = ((g[0][:, None, None] - pos[b, a, 0]) ** 2 + (g[1][None, :, None] - pos[b, a, 1]) ** 2
+                  + (g[2][None, None, :] - pos[b, a, 2]) ** 2)
+            inside[t] |= d2 <= float(w.radii[t]) ** 2
+        differ = inside != (out[b] == 1.0)
+        assert not (differ & (mask[b] == 0)).any()
+    assert mask.mean() < 1e-3

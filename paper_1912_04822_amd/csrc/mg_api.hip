@@ -28,7 +28,7 @@ thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 // Launch knobs (mg_set_option): process-wide, read once per call.  Atomic so that a thread
 // that sets one while another thread makes a call is a defined (if unordered) program.
 std::atomic<int> g_tile_floats{0};       // 0: chosen by the launcher
-std::atomic<int> g_waves_per_tile{1};
+std::atomic<int> g_waves_per_tile{0};    // 0: chosen by the launcher
 std::atomic<int> g_xcd_run{0};
 std::atomic<int> g_lds_floor{-1};        // < 0: chosen by the launcher
 std::atomic<int> g_tile_order{0};
@@ -459,12 +459,12 @@ int mg_set_option(const char *key, int value)
 {
     if (!key) return MG_ENULL;
     if (std::strcmp(key, "tile_floats") == 0) {
-        if (value != 0 && value != 1024 && value != 2048 && value != 4096) return MG_EPARAM;
+        if (value != 0 && value != 512 && value != 1024 && value != 2048 && value != 4096) return MG_EPARAM;
         g_tile_floats = value;
         return MG_OK;
     }
     if (std::strcmp(key, "waves_per_tile") == 0) {
-        if (value != 1 && value != 2 && value != 4) return MG_EPARAM;
+        if (value != 0 && value != 1 && value != 2 && value != 4) return MG_EPARAM;
         g_waves_per_tile = value;
         return MG_OK;
     }

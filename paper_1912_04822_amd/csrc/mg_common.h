@@ -77,6 +77,9 @@ __host__ __device__ inline int source_example(int subgrid_count, int e)
 //                         streams stores cost far more than their bytes
 //   rot   [B][12] float   rotation matrix rows (9 used), for the backward pass
 //   gcen  [B][4] float    centre of the example's grid (3 used)
+//   chan_order [B][T] int32  vector types: the channels in order of radius (ties by index;
+//                         as they come beyond kRankCap channels), so that channels taken
+//                         together have spheres of nearly the same size
 //   gtmp  [B][N][3] float, wtmp [B][N][T] float: with subgrids only, the
 //                         gradients per virtual example before they are summed
 // With subgrids B counts virtual examples everywhere above.
@@ -88,6 +91,7 @@ struct Workspace {
     int2   *range;
     float  *rot;
     float  *gcen;
+    int    *chan_order;
     float  *gtmp;
     float  *wtmp;
 };
@@ -120,6 +124,7 @@ struct ForwardGeometry {
 ForwardGeometry forward_geometry(int D, int tile_floats);
 
 constexpr int kSortCap = 2048;          // longest group the prep kernel bins by x-plane
+constexpr int kRankCap = 256;           // most channels that are put in order of radius
 
 // Timing events for the main kernel of the current call (null: none).  The launchers pass
 // them to hipExtLaunchKernelGGL, which stamps them at the start and the end of that very

@@ -80,6 +80,8 @@ struct FwdParams {
     const float *weights;
     const float *radii;
     const float *gcen;          // [B][4] grid centres, written by the prep kernel
+    const int *chan_order;      // [B][T] vector types: channels in order of radius
+    unsigned groups;            // vector types: groups of kVecGroup channels per example
     void *out;                      // float or double grid
     int subgrids, N, T;             // subgrids: virtual examples per example (weights are per example)
     int tile_floats;                // floats per tile (a multiple of 512)
@@ -762,6 +764,351 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     asm volatile("" ::"v"(ka.x), "v"(ka.y), "v"(ka.z), "v"(ka.w));     // the keep-alive read is waited for here
 }
 
+
+// ---------------------------------------------------------------------------
+// Vector types, real density: kVecGroup channels of one spatial tile per wavefront.
+//
+// Every atom feeds every channel, and the channels differ only in the radius that scales
+// the distance (radii are looked up by type id) and in the atom's weight.  One pass over the
+// atoms in reach of the tile therefore serves several channels: the records are loaded and
+// tested against the tile's rows once, the tasks are staged once, and per voxel the squared
+// distance x'^2 (in units of rmax/sqrt(k), rmax the widest radius of the group) is worked
+// out once; channel q rescales it, x'^2_q = x'^2 (rmax/r_q)^2, evaluates its density and adds
+// w_q rho_q into its own tile in LDS.  Beyond channel q's own cutoff rho_q is 0 by its
+// formula, so the voxels of the widest sphere that a narrower one does not reach add nothing.
+// The channels are taken in order of radius (chan_order, written by the prep kernel), so the
+// spheres of a group are nearly the same size.
+//   Gaussian  w exp2(-x'^2_q)          = sgn exp2(log2|w| - ratio2_q x'^2)
+//   tail      w (sqrt(x'^2_q) sA - cA)^2 = sgn (s sqrt|w| sA ratio_q - sqrt|w| cA)^2,  s = sqrt(x'^2)
+// log2|w|, sqrt|w| sA ratio_q and sqrt|w| cA are worked out once per atom (in the lane that
+// holds the atom) and fetched by the lanes that walk its chords.
+// ---------------------------------------------------------------------------
+constexpr int kVecGroup = 4;
+
+struct VecGroup {           // wave-uniform: the channels of this workgroup
+    int chan[kVecGroup];        // channel index (for dead slots: any valid channel)
+    bool live[kVecGroup];       // slot q holds a channel with a positive radius
+    float ratio2[kVecGroup];    // (rmax / r_q)^2
+    float sAq[kVecGroup];       // sA rmax / r_q
+    float thq[kVecGroup];       // Gaussian region of channel q: x'^2 <= g^2 k / ratio2_q
+    float rmax;
+};
+
+struct VecAtom {            // per atom, per channel of the group
+    float lw[kVecGroup];        // log2 |w_q|  (-inf for w_q = 0: the Gaussian is then 0)
+    float su[kVecGroup];        // sqrt|w_q| sA ratio_q
+    float sc[kVecGroup];        // sqrt|w_q| cA
+    int neg;                    // bit q: w_q < 0
+};
+
+// Run the staged tasks [0, ntasks): one (atom, row) chord per lane, kVecGroup channels per voxel.
+// tiles: channel q's tile starts at cx.tile + q * stride floats.
+template <bool FIXED, bool SIGNED>
+__device__ inline void run_tasks_group(const TileCtx &cx, const VecGroup &vg, const Cand &cd,
+                                       const VecAtom &va, int stride, int ntasks)
+{
+    int carry = 0;
+    for (int base = 0; base < ntasks; base += 64) {
+        const int tau = base + cx.lane;
+        bool act = tau < ntasks;
+        const int owner = max(carry, wave_inclusive_max((int)cx.marks[tau]));
+        carry = bcast(owner, 63);
+        const int src = (act ? owner - 1 : 0) << 2;
+        const float fy = fetch(src, cd.c0), fz = fetch(src, cd.c1), stepk = fetch(src, cd.c2),
+                    inv_stepk = fetch(src, cd.c3);
+        const float pxA = fetch(src, cd.pxA), pxB = fetch(src, cd.pxB);
+        const int pack = __builtin_amdgcn_ds_bpermute(src, cd.pack);
+        const int k = tau - __builtin_amdgcn_ds_bpermute(src, cd.start);   // row number within the atom
+        float lw[kVecGroup], su[kVecGroup], sc[kVecGroup];
+#pragma unroll
+        for (int q = 0; q < kVecGroup; ++q) {
+            lw[q] = fetch(src, va.lw[q]);
+            su[q] = fetch(src, va.su[q]);
+            sc[q] = fetch(src, va.sc[q]);
+        }
+        int sb[kVecGroup];
+        if (SIGNED) {
+            const int neg = __builtin_amdgcn_ds_bpermute(src, va.neg);
+#pragma unroll
+            for (int q = 0; q < kVecGroup; ++q) sb[q] = ((neg >> q) & 1) << 31;
+        }
+        const int nA = (pack >> 10) & 1023;
+        const bool inB = k >= nA;
+        const int j = inB ? (pack >> 20) + (k - nA) : (pack & 1023) + k;   // row in its plane
+        const int trow = (inB ? cx.rowB : cx.rowA) + j;                    // row in the tile
+        const float px2 = inB ? pxB : pxA;                                 // plane term of x'^2
+        const int clip_lo = trow == 0 ? cx.c0 : 0;
+        const int clip_hi = trow == cx.nrows - 1 ? cx.c1 : cx.D - 1;
+        float *rowp = cx.tile + (trow * cx.D - cx.c0);
+        const float dyk = (((float)j - cx.hD) - fy) * stepk;
+        const float x2b = fmaf(dyk, dyk, px2);
+        const float rem = cx.c2k - x2b;
+        act = act && rem > 0.0f;
+        const float hz = __builtin_amdgcn_sqrtf(fmaxf(rem, 0.0f)) * inv_stepk + 1.0e-3f;
+        const float fzi = fz + cx.hD;                                       // as a grid index
+        const int klo = max(clip_lo, (int)ceilf(fzi - hz));
+        const int khi = min(clip_hi, (int)floorf(fzi + hz));
+        const int nz = act ? khi - klo + 1 : 0;
+        const float z0 = (((float)klo - cx.hD) - fz) * stepk;
+        const float fnz = (float)nz;
+        float *q0 = rowp + klo;
+        for (float fi = 0.0f; fi < fnz; fi += 1.0f, ++q0) {
+            const float zs = fmaf(fi, stepk, z0);
+            const float x2 = fmaf(zs, zs, x2b);
+            const float sx = __builtin_amdgcn_sqrtf(x2);
+#pragma unroll
+            for (int q = 0; q < kVecGroup; ++q) {
+                const float e = __builtin_amdgcn_exp2f(fmaf(-vg.ratio2[q], x2, lw[q]));
+                const float u = fminf(fmaf(sx, su[q], -sc[q]), 0.0f);
+                float val = x2 <= vg.thq[q] ? e : u * u;                    // |w_q| rho_q, 0 beyond the cutoff
+                if (SIGNED) val = __int_as_float(__float_as_int(val) | sb[q]);
+                if (FIXED) {
+                    // |val| 2^24 + 1/2, truncated: rounded to the nearest fixed-point step
+                    const float half = SIGNED ? __int_as_float(0x3f000000 | sb[q]) : 0.5f;
+                    __hip_atomic_fetch_add(reinterpret_cast<int *>(q0) + q * stride,
+                                           (int)fmaf(val, kFixedOne, half), __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_WORKGROUP);
+                } else {
+                    __hip_atomic_fetch_add(q0 + q * stride, val, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+            }
+        }
+    }
+    lds_sync();
+}
+
+// Stage the tasks of the hits and run them (as pair_run, for a group of channels).
+template <bool SIGNED>
+__device__ inline bool pair_run_group(const TileCtx &cx, const VecGroup &vg, PairHit &h,
+                                      const VecAtom &va, int stride, bool fixed)
+{
+    int todo = h.nA + h.nB;
+    if (__ballot(todo > 0) == 0ull) return false;
+    while (true) {
+        const int incl = wave_inclusive_scan(todo);
+        int total = bcast(incl, 63);
+        if (total == 0) break;
+        bool now = todo > 0;
+        if (total > kTaskCap) {     // rare: the rest waits for the next round
+            now = now && incl <= kTaskCap;
+            total = bcast(wave_inclusive_scan(now ? todo : 0), 63);
+            if (total == 0) break;
+        }
+        if (cx.lane < kTaskCap / 16)
+            reinterpret_cast<float4 *>(cx.marks)[cx.lane] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (now) {
+            h.cd.start = incl - todo;
+            cx.marks[h.cd.start] = (unsigned char)(cx.lane + 1);
+            todo = 0;
+        }
+        lds_sync();
+        if (fixed) run_tasks_group<true, SIGNED>(cx, vg, h.cd, va, stride, total);
+        else run_tasks_group<false, SIGNED>(cx, vg, h.cd, va, stride, total);
+    }
+    return true;
+}
+
+// One workgroup of NW wavefronts per (example, group of kVecGroup channels, tile).  The
+// wavefronts share the group's tiles in LDS and take the rounds of 64 records in turn; every
+// wavefront stages and runs its own tasks.  The tiles accumulate in fixed point; the bound on
+// what can reach one voxel is summed up on the way, and a workgroup whose bound passes the
+// limit at the end (rare) starts over in floats, all records taken by its first wavefront so
+// that the order of the float additions is the same in every run.
+template <bool ALIGNED, int ITERS, int NW, typename OUT>
+__global__ __launch_bounds__(64 * NW) void forward_vector_kernel(FwdParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds[];   // kVecGroup tiles | marks per wave | bound
+    constexpr int kTile = ITERS * 512;
+    const GridSpec &gs = p.gs;
+    const int D = gs.D, T = p.T, N = p.N;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const unsigned u = blockIdx.x;
+    const unsigned uq = div_u32(u, p.tiles_magic), tile_in_chan = u - uq * p.tiles;
+    const int b = (int)div_u32(uq, p.t_magic);          // t_magic: ceil(2^64 / groups)
+    const int g = (int)uq - b * (int)p.groups;
+    const int2 *span = p.range + (size_t)b * T * D;     // vector types: one record list per example
+    const float4 cen = *reinterpret_cast<const float4 *>(p.gcen + 4 * b);
+    const TileGeom tg = tile_geom<ITERS>(p, D, tile_in_chan);
+    const int r0 = span[tg.i_lo].x, r1 = span[tg.i_hi].y;
+
+    // the channels of this group and what depends on their radii only
+    VecGroup vg;
+    vg.rmax = 0.0f;
+    float rq[kVecGroup];
+#pragma unroll
+    for (int q = 0; q < kVecGroup; ++q) {
+        const int pos = g * kVecGroup + q;
+        vg.chan[q] = p.chan_order[(size_t)b * T + min(pos, T - 1)];
+        rq[q] = gs.radius_scale * p.radii[vg.chan[q]];
+        vg.live[q] = pos < T && rq[q] > 0.0f && rq[q] < 1.0e30f;
+        if (vg.live[q]) vg.rmax = fmaxf(vg.rmax, rq[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < kVecGroup; ++q) {
+        const float ratio = vg.live[q] ? vg.rmax * __builtin_amdgcn_rcpf(rq[q]) : 1.0f;
+        vg.ratio2[q] = ratio * ratio;
+        vg.sAq[q] = p.sA * ratio;
+        vg.thq[q] = p.g2k * __builtin_amdgcn_rcpf(vg.ratio2[q]);
+    }
+
+    TileCtx cx;
+    cx.tile = lds;
+    cx.marks = reinterpret_cast<unsigned char *>(lds + kVecGroup * kTile) + wave * kTaskCap;
+    cx.shared = reinterpret_cast<int *>(lds + kVecGroup * kTile + NW * (kTaskCap / 4));
+    cx.lane = lane;
+    cx.wave = wave;
+    cx.D = D;
+    cx.n = tg.f1 - tg.f0;
+    cx.nrows = tg.R1 - tg.R0;
+    cx.c0 = tg.f0 - tg.R0 * D;
+    cx.c1 = tg.f1 - 1 - (tg.R1 - 1) * D;
+    cx.rowA = 0;
+    cx.rowB = 0;
+    cx.res = gs.res;
+    cx.inv_res = gs.inv_res;
+    cx.g2k = p.g2k; cx.c2k = p.c2k; cx.sA = p.sA; cx.cA = p.cA;
+    cx.debug = 0;
+    cx.cen_x = cen.x; cx.cen_y = cen.y; cx.cen_z = cen.z;
+    cx.hD = 0.5f * (float)(D - 1);
+    const float ox = cx.cen_x - gs.half;
+    cx.oy = cx.cen_y - gs.half;
+    cx.oz = cx.cen_z - gs.half;
+
+    const size_t total = (size_t)D * D * D;
+    OUT *out = reinterpret_cast<OUT *>(p.out);
+    auto store_all = [&](bool touched, bool fixed) {
+#pragma unroll
+        for (int q = 0; q < kVecGroup; ++q) {
+            if (g * kVecGroup + q >= T) break;              // uniform
+            TileCtx cq = cx;
+            cq.tile = lds + q * kTile;
+            OUT *dst = out + ((size_t)b * T + vg.chan[q]) * total + tg.f0;
+            store_tile<ALIGNED, ITERS, NW, OUT>(cq, dst, touched && vg.live[q], fixed);
+        }
+    };
+    const int count = r1 - r0;
+    if (count <= 0 || !(vg.rmax > 0.0f)) {      // uniform: nothing can reach these tiles
+        store_all(false, false);
+        return;
+    }
+
+    const float4 *rec = p.rec + (size_t)b * N + r0;
+    const int *idx = p.idx + (size_t)b * N + r0;
+    const float *wbase = p.weights + (size_t)source_example(p.subgrids, b) * N * T;
+    struct Raw {
+        float4 a;
+        int ai;
+    };
+    auto load_raw = [&](int base) {
+        Raw r;
+        r.a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        r.ai = 0;
+        if (base + lane < count) {
+            r.a = rec[base + lane];
+            r.ai = idx[base + lane];
+        }
+        return r;
+    };
+    struct Wq {
+        float w[kVecGroup];
+    };
+    auto gather = [&](const Raw &r) {
+        Wq o;
+        const float *row = wbase + (size_t)r.ai * T;
+#pragma unroll
+        for (int q = 0; q < kVecGroup; ++q)
+            o.w[q] = (r.a.w > 0.0f && vg.live[q]) ? row[vg.chan[q]] : 0.0f;
+        return o;
+    };
+    auto clear_tiles = [&]() {
+        const float4 z4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);     // same bits as integer zeros
+#pragma unroll
+        for (int it = 0; it < kVecGroup * kTile / (256 * NW); ++it)
+            reinterpret_cast<float4 *>(lds)[it * 64 * NW + threadIdx.x] = z4;
+        if (threadIdx.x < 2) cx.shared[threadIdx.x] = 0;
+    };
+
+    // One pass over the rounds first, first + stride, ...: returns whether any task ran; adds
+    // what the hits can put into one voxel at most to `bound` (1/256 units).  Records and
+    // indices are requested two rounds ahead, the weights (gathered through the indices) one
+    // round ahead; clear_first: the tiles are cleared while the first loads are in flight.
+    auto pass = [&](int first, int stride, bool fixed, bool clear_first, int &bound) {
+        bool any = false;
+        Raw rc = load_raw(64 * first);
+        Raw rn = load_raw(64 * (first + stride));
+        Wq wc = gather(rc);
+        if (clear_first) {
+            clear_tiles();
+            if (NW > 1) __syncthreads();
+        }
+        Wq wn = gather(rn);
+        for (int base = 64 * first; base < count; base += 64 * stride) {
+            const Raw rnn = load_raw(base + 128 * stride);
+            // this round's atom: what its chords will need, per channel
+            Atom at;
+            at.a = rc.a;
+            float wmax = 0.0f;
+            VecAtom va;
+            va.neg = 0;
+#pragma unroll
+            for (int q = 0; q < kVecGroup; ++q) {
+                const float aw = fabsf(wc.w[q]);
+                wmax = fmaxf(wmax, aw);
+                const float sw = __builtin_amdgcn_sqrtf(aw);
+                va.lw[q] = __builtin_amdgcn_logf(aw);               // log2
+                va.su[q] = sw * vg.sAq[q];
+                va.sc[q] = sw * cx.cA;
+                va.neg |= (wc.w[q] < 0.0f ? 1 : 0) << q;
+            }
+            at.w = wmax;
+            at.valid = (rc.a.w > 0.0f) && (wmax > 0.0f);
+            at.a.w = vg.rmax;
+            const bool any_neg = __ballot(at.valid && va.neg != 0) != 0ull;
+            for (int iA = tg.i_lo; iA <= tg.i_hi; iA += 2) {
+                cx.rowA = iA * D - tg.R0;
+                cx.rowB = cx.rowA + D;
+                const int jaA = max(-cx.rowA, 0), jbA = min(tg.R1 - tg.R0 - cx.rowA, D);
+                const int jaB = max(-cx.rowB, 0), jbB = iA < tg.i_hi ? min(tg.R1 - tg.R0 - cx.rowB, D) : 0;
+                PairHit h = pair_test<false, false>(cx, p, at, ox, iA, jaA, jbA, jaB, jbB);
+                bound = min(bound + min(pair_bound<true>(h, at), 1 << 24), 1 << 26);
+                const bool ran = any_neg ? pair_run_group<true>(cx, vg, h, va, kTile, fixed)
+                                         : pair_run_group<false>(cx, vg, h, va, kTile, fixed);
+                any = ran || any;
+            }
+            rc = rn;
+            wc = wn;
+            rn = rnn;
+            wn = gather(rn);
+        }
+        return any;
+    };
+
+    const int limit = (int)(kFixedLimit * 256.0f);
+    int bound = 0;
+    bool fixed = true;
+    bool any = pass(wave, NW, true, true, bound);
+    if (NW > 1) {
+        if (lane == 0) {
+            atomicAdd(&cx.shared[0], bound);
+            if (any) cx.shared[1] = 1;
+        }
+        __syncthreads();                    // every wavefront's additions are in the tiles
+        bound = cx.shared[0];
+        any = cx.shared[1] != 0;
+    }
+    if (bound > limit) {                    // uniform over the workgroup: the sums may not fit; again, in floats
+        if (NW > 1) __syncthreads();        // shared[] has been read by all
+        fixed = false;
+        clear_tiles();
+        if (NW > 1) __syncthreads();
+        int unused = 0;
+        if (wave == 0) pass(0, 1, false, false, unused);
+        if (NW > 1) __syncthreads();
+    }
+    store_all(any, fixed);
+}
+
 }  // namespace
 
 ForwardGeometry forward_geometry(int D, int tile_floats)
@@ -783,10 +1130,89 @@ unsigned long long magic64(unsigned d)      // ceil(2^64 / d); 0 stands for d ==
 }
 }  // namespace
 
+// Vector types, real density: one wavefront per (example, group of kVecGroup channels, tile).
+static hipError_t launch_forward_vector(const GridSpec &gs, const Batch &bt, const Workspace &ws,
+                                        void *out, bool out_is_double, int tile_floats,
+                                        int waves_per_tile, KernelEvents ev, hipStream_t stream)
+{
+    // 2048-float tiles and four wavefronts per workgroup: the four channel tiles of a group take
+    // 33 KB of LDS, so four workgroups (sixteen wavefronts, what 111 registers allow) fit a CU.
+    // Measured on the 48^3 batch of 50 x 2040 atoms x 28 channels: 0.52 ms; 1024 floats x 2
+    // wavefronts 0.57 ms (each tile tests the atoms in reach anew); 2048 x 2 0.74 ms and 1024 x 1
+    // 0.75 ms (too few wavefronts); 512 x 1 0.69 ms.  A grid of doubles takes 512 voxels per tile.
+    if (tile_floats != 512 && tile_floats != 1024 && tile_floats != 2048) tile_floats = 2048;
+    if (out_is_double) tile_floats = 512;
+    const ForwardGeometry fg = forward_geometry(gs.D, tile_floats);
+    FwdParams p;
+    p.gs = gs;
+    p.rec = ws.rec;
+    p.idx = ws.idx;
+    p.range = ws.range;
+    p.weights = bt.weights;
+    p.radii = bt.radii;
+    p.gcen = ws.gcen;
+    p.chan_order = ws.chan_order;
+    p.groups = (unsigned)((bt.T + kVecGroup - 1) / kVecGroup);
+    p.out = out;
+    p.subgrids = bt.sub.count; p.N = bt.N; p.T = bt.T;
+    p.tile_floats = fg.tile_floats;
+    p.div_magic = ((1ULL << 40) + (unsigned long long)gs.D - 1ULL) / (unsigned long long)gs.D;
+    p.pos_major = 0u;
+    p.tiles = (unsigned)fg.tiles;
+    p.tiles_magic = magic64(p.tiles);
+    p.t_magic = magic64(p.groups);
+    p.xcd_shift = -1;
+    p.n_remap = 0;
+    p.debug = 0;
+    p.ka_chunks = 0;
+    p.ka_last = 0;
+    const double k = 2.8853900817779268;        // 2 / ln 2
+    p.sk = (float)std::sqrt(k);
+    p.inv_sk = (float)(1.0 / std::sqrt(k));
+    p.g2k = (float)((double)gs.g2 * k);
+    p.c2k = (float)((double)gs.c * (double)gs.c * k);
+    p.sA = (float)std::sqrt((double)gs.A / k);
+    p.cA = (float)((double)gs.c * std::sqrt((double)gs.A));
+    const unsigned long long wgs = (unsigned long long)bt.B * p.groups * fg.tiles;
+    if (wgs > 0x7fffffffULL) return hipErrorInvalidValue;
+    // two wavefronts per workgroup by default: they share the tiles, so twice as many
+    // wavefronts are resident for the same LDS (the kernel is bound by vector arithmetic and
+    // needs them to keep the SIMDs busy)
+    int nw = waves_per_tile == 0 ? 4 : waves_per_tile;
+    if (tile_floats == 512 || out_is_double) nw = 1;
+    if (nw > tile_floats / 512) nw = tile_floats / 512;
+    const size_t lds_bytes = (size_t)kVecGroup * tile_floats * sizeof(float) + (size_t)nw * kTaskCap + 16;
+    const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)out & 15u) == 0);
+    const dim3 blk(64 * nw), grd((unsigned)wgs);
+#define MG_VEC(Al, It, Nw, Ot) \
+    hipExtLaunchKernelGGL((forward_vector_kernel<Al, It, Nw, Ot>), grd, blk, (uint32_t)lds_bytes, stream, \
+                          ev.start, ev.stop, 0, p)
+#define MG_VEC_NW(Al, It, Ot) \
+    if (nw == 1) MG_VEC(Al, It, 1, Ot); else MG_VEC(Al, It, 2, Ot)
+    if (out_is_double) {
+        if (aligned) MG_VEC(true, 1, 1, double); else MG_VEC(false, 1, 1, double);
+    } else if (tile_floats == 512) {
+        if (aligned) MG_VEC(true, 1, 1, float); else MG_VEC(false, 1, 1, float);
+    } else if (tile_floats == 1024) {
+        if (aligned) { MG_VEC_NW(true, 2, float); } else { MG_VEC_NW(false, 2, float); }
+    } else if (nw == 4) {
+        if (aligned) MG_VEC(true, 4, 4, float); else MG_VEC(false, 4, 4, float);
+    } else {
+        if (aligned) { MG_VEC_NW(true, 4, float); } else { MG_VEC_NW(false, 4, float); }
+    }
+#undef MG_VEC_NW
+#undef MG_VEC
+    return hipGetLastError();
+}
+
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws, void *out,
                           bool out_is_double, int tile_floats, int waves_per_tile, int xcd_run,
                           int lds_floor, int debug, int tile_order, int keep_alive, KernelEvents ev, hipStream_t stream)
 {
+    if (bt.weights && !gs.binary)
+        return launch_forward_vector(gs, bt, ws, out, out_is_double, tile_floats, waves_per_tile, ev, stream);
+    if (tile_floats == 512) tile_floats = 1024;     // the smallest tile of these kernels
+    if (waves_per_tile == 0) waves_per_tile = 1;
     if (tile_floats == 0) {
         // 4 KB tiles unless a tile meets many records (then the fixed cost per tile counts for
         // more than the shorter life of a small tile): about N/T atoms per channel, of which
@@ -813,6 +1239,8 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     p.weights = bt.weights;
     p.radii = bt.radii;
     p.gcen = ws.gcen;
+    p.chan_order = ws.chan_order;
+    p.groups = 0;
     p.out = out;
     p.subgrids = bt.sub.count; p.N = bt.N; p.T = bt.T;
     p.tile_floats = fg.tile_floats;
@@ -878,9 +1306,8 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     case 8 * 8 + 4: MG_LAUNCH5(V, Bn, Al, 8, 4); break;                         \
     default: return hipErrorInvalidValue;                                       \
     }
-    if (vec) {
-        if (gs.binary) { if (aligned) MG_LAUNCH(true, true, true) else MG_LAUNCH(true, true, false) }
-        else           { if (aligned) MG_LAUNCH(true, false, true) else MG_LAUNCH(true, false, false) }
+    if (vec) {      // binary occupancy with vector types (the real density took the kernel above)
+        if (aligned) MG_LAUNCH(true, true, true) else MG_LAUNCH(true, true, false)
     } else {
         if (gs.binary) { if (aligned) MG_LAUNCH(false, true, true) else MG_LAUNCH(false, true, false) }
         else           { if (aligned) MG_LAUNCH(false, false, true) else MG_LAUNCH(false, false, false) }

@@ -193,6 +193,28 @@ __device__ inline void clear_grads(float *gclear, float *wclear, size_t atom, in
         for (int k = 0; k < T; ++k) wclear[atom * T + k] = 0.0f;
 }
 
+// Vector types: the channels of (virtual) example b in order of radius, for the kernels that
+// take several channels of an atom together (thread `tid` of `nthreads`).  NaN and negative
+// radii rank as 0, so the result is a permutation whatever the table holds.
+__device__ inline void rank_channels(const Batch &bt, const Workspace &ws, int b, int tid, int nthreads)
+{
+    const int T = bt.T;
+    for (int k = tid; k < T; k += nthreads) {
+        int rank = k;
+        if (T <= kRankCap) {
+            float mine = bt.radii[k];
+            mine = mine > 0.0f ? mine : 0.0f;
+            rank = 0;
+            for (int j = 0; j < T; ++j) {
+                float other = bt.radii[j];
+                other = other > 0.0f ? other : 0.0f;
+                rank += (other < mine || (other == mine && j < k)) ? 1 : 0;
+            }
+        }
+        ws.chan_order[(size_t)b * T + rank] = k;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // One workgroup per example: counting sort by (type, x-bin) in LDS.
 // ---------------------------------------------------------------------------
@@ -264,6 +286,7 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     if (tid < 9) ws.rot[b * 12 + tid] = (float)X.R[tid];
     float vec_reach = 0.0f;         // reach of the widest channel, for vector types
     if (VECTOR) {
+        rank_channels(bt, ws, b, tid, kExThreads);
         for (int k = 0; k < T; ++k) {
             const float r = gs.radius_scale * bt.radii[k];
             if (r > vec_reach) vec_reach = r;
@@ -451,6 +474,7 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
     (void)wave_exclusive_scan(less, &first);
     if (VECTOR) first = 0;
     if (t == 0 && lane < 9) ws.rot[b * 12 + lane] = (float)X.R[lane];
+    if (VECTOR) rank_channels(bt, ws, b, lane, kPrepThreads);      // (one wavefront per example)
     if (MG_STOP_IS(stop, 3)) { if (M + first == 12345) ws.rot[0] = 1.0f; return; }
 
     float vec_reach = 0.0f;         // reach of the widest channel, for vector types
@@ -616,6 +640,7 @@ size_t workspace_bytes(const GridSpec &gs, int subgrid_count, int B, int N, int 
     bytes += align16(bt * (size_t)gs.D * sizeof(int2));     // range
     bytes += (size_t)B * 12 * sizeof(float);                // rot
     bytes += (size_t)B * 4 * sizeof(float);                 // gcen
+    bytes += align16(bt * sizeof(int));                     // chan_order
     if (subgrid_count > 1) {
         bytes += align16(bn * 3 * sizeof(float));           // gtmp
         if (gs.radius_type_indexed) bytes += align16(bn * (size_t)T * sizeof(float));   // wtmp
@@ -640,6 +665,8 @@ Workspace carve_workspace(const GridSpec &gs, int subgrid_count, void *base, int
     p += (size_t)B * 12 * sizeof(float);
     ws.gcen = (float *)p;
     p += (size_t)B * 4 * sizeof(float);
+    ws.chan_order = (int *)p;
+    p += align16(bt * sizeof(int));
     ws.gtmp = nullptr;
     ws.wtmp = nullptr;
     if (subgrid_count > 1) {

@@ -143,7 +143,7 @@ def test_calls_reject_bad_arguments_before_any_launch(L):
     # the timing aids (which write wrong grids) are not in the library as built by default
     assert L.mg_set_option(b"debug", 1) == -3
     assert L.mg_set_option(b"prep_stop", 3) == -3
-    for key, bad in ((b"waves_per_tile", 3), (b"waves_per_tile", 0), (b"xcd_run", -1),
+    for key, bad in ((b"waves_per_tile", 3), (b"waves_per_tile", 8), (b"xcd_run", -1),
                      (b"lds_floor", -2), (b"keep_alive", -1), (b"tile_order", -1)):
         assert L.mg_set_option(key, bad) == -3
     for key, good, bad, default in ((b"keep_alive", 0, 2, 1), (b"tile_order", 1, 2, 0),

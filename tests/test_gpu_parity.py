@@ -186,7 +186,7 @@ def test_forward_protein_ligand_subset_and_determinism(mg):
             other = run_forward_index(mg, w)
         finally:
             mg.set_option("tile_floats", 0)
-            mg.set_option("waves_per_tile", 1)
+            mg.set_option("waves_per_tile", 0)
         # the knob changes the order in which overlapping atoms are summed: equal to rounding
         assert np.abs(got - other).max() <= 2e-6
         assert np.abs(other - ref).max() <= GRID_TOL
@@ -301,6 +301,28 @@ def test_forward_vector_small_and_subset(mg):
     assert got.min() >= 0 and got.max() > 0.1
 
 
+def test_forward_vector_negative_weights_large_weights_and_ragged_channel_groups(mg):
+    """Weights of both signs (the signed path of the kernel that takes four channels at a time),
+    weights so large that a tile's sums cannot stay in fixed point (it starts over in floats),
+    and channel counts that leave the last group of four partly empty."""
+    for T, scale, seed in ((5, 1.0, 1), (6, 1.0, 2), (7, 60.0, 3), (28, 200.0, 4), (1, 1.0, 5)):
+        rng = np.random.default_rng(100 + seed)
+        w = workloads.protein_ligand(B=2, seed=50 + seed)
+        w.T = T
+        w.radii = rng.uniform(1.0, 2.2, T).astype(np.float32)
+        w.weights = (rng.standard_normal((w.B, w.N, T)) * scale).astype(np.float32)
+        w.weights[rng.random((w.B, w.N, T)) < 0.3] = 0.0
+        got = run_forward_vector(mg, w)
+        ref = oracle.forward_vector(w.coords, w.weights, w.radii, w.resolution, w.dimension,
+                                    centers=w.centers, quats=w.quats, translations=w.translations)
+        scale_ref = float(np.abs(ref).max())
+        assert scale_ref > 1.0
+        err = float(np.abs(got - ref).max())
+        assert err <= max(GRID_TOL, 2e-6 * scale_ref), (T, scale, err, scale_ref)
+        again = run_forward_vector(mg, w)           # float tiles too repeat bit for bit
+        assert np.array_equal(got.view(np.uint32), again.view(np.uint32))
+
+
 def test_forward_vector_binary_is_bit_exact(mg):
     w = workloads.ragged_small()
     wt = w.weights.copy()
@@ -312,7 +334,8 @@ def test_forward_vector_binary_is_bit_exact(mg):
     assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
 
 
-@pytest.mark.parametrize("tile_floats,waves", [(1024, 2), (2048, 4), (4096, 4)])
+@pytest.mark.parametrize("tile_floats,waves", [(512, 1), (1024, 1), (1024, 2), (2048, 1), (2048, 2),
+                                               (2048, 4), (4096, 4)])
 def test_tile_shapes_binary_and_vector(mg, tile_floats, waves):
     """The other tile sizes and workgroup shapes of the forward kernel, in binary and vector mode
     (several wavefronts per tile, several rounds of atoms, more than one pair of planes)."""
@@ -334,7 +357,7 @@ def test_tile_shapes_binary_and_vector(mg, tile_floats, waves):
         assert np.abs(got - ref).max() <= GRID_TOL
     finally:
         mg.set_option("tile_floats", 0)
-        mg.set_option("waves_per_tile", 1)
+        mg.set_option("waves_per_tile", 0)
 
 
 # ---------------------------------------------------------------------------

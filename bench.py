@@ -412,6 +412,9 @@ def main():
             gmt.mg_forward_index(ct, tt, rt, wt.T, out=outt, workspace=wst)
 
         r = row(tiny_call, 1000, settle_ms=5.0, timed_kernel=False)
+        molgrid.set_option("single_launch", 0)      # for comparison: prep kernel + forward kernel
+        r2 = row(tiny_call, 1000, settle_ms=2.0, timed_kernel=False)
+        molgrid.set_option("single_launch", 1)
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -431,8 +434,10 @@ def main():
         ms_graph = (time.perf_counter() - t0) * 1e3 / 1000
         rows["forward_tiny"] = {
             "latency_us_eager": r["ms_per_call"] * 1e3, "latency_us_graph": ms_graph * 1e3,
+            "latency_us_eager_two_launches": r2["ms_per_call"] * 1e3,
             "roofline": None,
-            "workload": "configs[0]: B=1, N=100, T=4, 24^3 @0.5A (221 KB out): calls back to back; "
+            "workload": "configs[0]: B=1, N=100, T=4, 24^3 @0.5A (221 KB out): calls back to back, "
+                        "one kernel launch per call (every tile looks at the 100 atoms itself); "
                         "launch-bound, so a latency and no roofline fraction"}
         result["rows"] = rows
         result["distinct_in_cutoff_voxels"] = {"index_types": distinct_index,

@@ -280,6 +280,12 @@ int mg_last_hip_error(void);
  *   "keep_alive"      0 or 1 (default 1): every forward wavefront (index types,
  *                     float grid) also reads 1 KB of the workspace tables so that
  *                     they stay cached while the grid is streamed out
+ *   "single_launch"   0 or 1 (default 1): index types into a float grid with at most
+ *                     256 atoms per example and 2048 in the batch run as ONE kernel
+ *                     launch (every tile's wavefront transforms, culls and filters the
+ *                     example's atoms itself; no prep kernel, the workspace is not
+ *                     touched); 0 = always the prep kernel and its tables.  Binary
+ *                     grids are the same to the bit either way, real ones to rounding
  *   "tile_order"      0 or 1 (default 0): 0 = all tiles of a channel, then the
  *                     next channel; 1 = tile k of every channel, then tile k+1
  *   "lds_floor"       -1..65536 (default -1 = chosen per call: 6144 for 4 KB

@@ -33,6 +33,7 @@ std::atomic<int> g_xcd_run{0};
 std::atomic<int> g_lds_floor{-1};        // < 0: chosen by the launcher
 std::atomic<int> g_tile_order{0};
 std::atomic<int> g_keep_alive{1};
+std::atomic<int> g_single_launch{1};     // small problems: the forward kernel alone, no prep kernel
 #ifdef MG_TIMING_AIDS
 std::atomic<int> g_debug{0};             // measurement build only: kernel phases switched off
 std::atomic<int> g_prep_stop{0};         // measurement build only: prep kernel ended after a stage
@@ -268,13 +269,18 @@ static int forward_call(const mg_gridmaker *gm, int B, int N, int T, const float
     const mg::Batch bt = make_batch(gm, B, N, T, coords, types, weights, radii, natoms, centers,
                                     quats, translations);
     const mg::Workspace ws = mg::carve_workspace(gm->gs, gm->sub.count, workspace, bt.B, N, T);
-    const int stop = timing_prep_stop();
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, stop, (hipStream_t)stream));
-    if (rc != MG_OK || stop != 0) return rc;    // a prep kernel cut short leaves no tables to read
     const auto knob = [](const std::atomic<int> &k) { return k.load(std::memory_order_relaxed); };
+    const int stop = timing_prep_stop();
+    // a few hundred atoms in all: one launch, every tile looks at the atoms itself
+    const bool single = knob(g_single_launch) != 0 && stop == 0 && timing_debug() == 0 &&
+                        mg::forward_takes_single_launch(bt, out_is_double);
+    if (!single) {
+        rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, stop, (hipStream_t)stream));
+        if (rc != MG_OK || stop != 0) return rc;    // a prep kernel cut short leaves no tables to read
+    }
     return hip_status(mg::launch_forward(gm->gs, bt, ws, out, out_is_double, knob(g_tile_floats),
                                          knob(g_waves_per_tile), knob(g_xcd_run), knob(g_lds_floor),
-                                         timing_debug(), knob(g_tile_order), knob(g_keep_alive),
+                                         timing_debug(), knob(g_tile_order), knob(g_keep_alive), single,
                                          take_events(), (hipStream_t)stream));
 }
 
@@ -476,6 +482,11 @@ int mg_set_option(const char *key, int value)
     if (std::strcmp(key, "keep_alive") == 0) {
         if (value != 0 && value != 1) return MG_EPARAM;
         g_keep_alive = value;
+        return MG_OK;
+    }
+    if (std::strcmp(key, "single_launch") == 0) {
+        if (value != 0 && value != 1) return MG_EPARAM;
+        g_single_launch = value;
         return MG_OK;
     }
     if (std::strcmp(key, "tile_order") == 0) {

@@ -6,8 +6,14 @@
 //     = 2A (1 - c/x)             g < x < c   (rho' = 2A (x - c))
 //     = 0                        x >= c
 // (dividing rho' by x removes the square root from the Gaussian branch and makes
-// d = 0 contribute exactly 0 through u = 0).  The gradient with respect to the
-// caller's coordinates is R^T times that sum.
+// d = 0 contribute exactly 0 through u = 0).  The kernels sum -f/4 instead,
+//   -f/4 = exp(-2x^2)            x <= g
+//        = (A/2) (c/x - 1)       g < x < c     (at most exp(-2g^2) <= 1 there)
+//        = 0                     x >= c
+// which the hardware evaluates as one fused multiply-add clamped to [0,1] (the tail
+// is <= 1 on its own interval and negative beyond the cutoff), and the factor -4 goes
+// into the scale applied once per atom.  The gradient with respect to the caller's
+// coordinates is R^T times that sum.
 //
 // One wavefront per atom record (four records per workgroup, no barrier).  The
 // work items are "slots": runs of four voxels along z in the grid rows (x-plane,
@@ -52,7 +58,7 @@ struct BwdParams {
     unsigned units, share;          // workgroups in all; per XCD (ceil(units / 8))
     unsigned long long wg_magic;    // ceil(2^64 / wgs_per_example), 0 if that is 1
     float sk, inv_sk, g2k, c2k;     // sqrt(k), 1/sqrt(k), g^2 k, c^2 k with k = 2 log2(e)
-    float A2, cAk2;         // 2A, 2A c sqrt(k)
+    float hA, hAck;         // A/2, (A/2) c sqrt(k): -f/4 = clamp(hAck / x' - hA, 0, 1) in the tail
     float sAk, cA;          // sqrt(A/k), c sqrt(A)
 };
 
@@ -105,9 +111,9 @@ __device__ inline bool atom_box(const GridSpec &gs, float reach, const float4 &a
 }
 
 // Accumulate over one channel volume, in coordinates scaled to units of r/sqrt(k),
-// k = 2 log2(e) (then exp(-2x^2) = exp2(-x'^2)):  (sx, sy, sz) += sum G f u',  sv += sum G rho.
-//   f = -4 exp2(-x'^2)                   x'^2 <= g^2 k
-//     = min(2A - 2A c sqrt(k) / x', 0)   beyond (zero from the cutoff on)
+// k = 2 log2(e) (then exp(-2x^2) = exp2(-x'^2)):  (sx, sy, sz) += sum G (-f/4) u',  sv += sum G rho.
+//   -f/4 = exp2(-x'^2)                                  x'^2 <= g^2 k
+//        = clamp((A/2) c sqrt(k) / x' - A/2, 0, 1)      beyond (zero from the cutoff on)
 // One slot: the four voxels k4 .. k4+3 of the grid row at float offset `row_off` of the
 // channel (a channel has at most 2^30 floats); ux, uy: the row's scaled x and y distance.
 struct SlotData {
@@ -157,8 +163,8 @@ __device__ inline void reduce_slot(const BwdParams &p, float step, float azs, co
         const float x2 = fmaf(uz, uz, b2);
         const float e = __builtin_amdgcn_exp2f(-x2);
         const float rs = __builtin_amdgcn_rsqf(x2);
-        const float ft = fminf(fmaf(-p.cAk2, rs, p.A2), 0.0f);
-        const float f = x2 <= p.g2k ? -4.0f * e : ft;
+        const float ft = __builtin_amdgcn_fmed3f(fmaf(p.hAck, rs, -p.hA), 0.0f, 1.0f);
+        const float f = x2 <= p.g2k ? e : ft;       // -f/4
         const float gf = gv[u] * f;
         fsum += gf;
         sz = fmaf(gf, uz, sz);
@@ -265,9 +271,11 @@ __device__ inline void reduce_channel(const BwdParams &p, const GT *G, int t, si
         lds_sync();
         asm volatile("" : "+v"(t));     // nothing above waits for t
         const GT *Gc = G + (size_t)t * D3;
-        // Round k works on slots 64k .. 64k+63, one per lane.  (Issuing the read of round k+1
-        // before the arithmetic of round k was measured slower: the kernel is bound by
-        // instruction issue, and other wavefronts cover the wait.)
+        // Round k works on slots 64k .. 64k+63, one per lane.  (Issuing the reads of two or three
+        // rounds before the arithmetic of the first was measured slower, 73 against 68 us in the same
+        // session: the kernel fetches every 128-byte line of the gradient grid that holds an
+        // in-cutoff voxel exactly once -- 270 MB on the 48^3 batch -- and runs at the rate those
+        // scattered lines arrive, whatever the wavefronts have in flight.)
         int carry = 0;
         for (int base = 0; base < total; base += 64) {
             const int sidx = base + lane;
@@ -309,7 +317,7 @@ constexpr int kChanGroup = 4;
 
 struct GroupCoef {
     float ratio2[kChanGroup];       // (rmax / r_q)^2
-    float cq[kChanGroup];           // w_q rmax / (sqrt(k) r_q^2): channel q's share of the coordinate sums
+    float cq[kChanGroup];           // -4 w_q rmax / (sqrt(k) r_q^2): channel q's share of the coordinate sums
     bool live[kChanGroup];          // r_q > 0 and t0 + q < T (uniform over the wavefront)
 };
 
@@ -431,8 +439,8 @@ __device__ inline void reduce_group(const BwdParams &p, const GT *const (&Gq)[kC
                 const float x2 = x2m * gc.ratio2[q];
                 const float e = __builtin_amdgcn_exp2f(-x2);
                 const float rs = __builtin_amdgcn_rsqf(x2);
-                const float ft = fminf(fmaf(-p.cAk2, rs, p.A2), 0.0f);
-                const float f = x2 <= p.g2k ? -4.0f * e : ft;
+                const float ft = __builtin_amdgcn_fmed3f(fmaf(p.hAck, rs, -p.hA), 0.0f, 1.0f);
+                const float f = x2 <= p.g2k ? e : ft;       // -f/4
                 F = fmaf(gc.cq[q], d[q].gv[u] * f, F);
                 const float tl = fminf(fmaf(x2 * rs, p.sAk, -p.cA), 0.0f);     // sqrt(A) (x - c)
                 const float rho = x2 <= p.g2k ? e : tl * tl;
@@ -507,7 +515,8 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
         if (atom_box(gs, r * gs.c, a, ox, oy, oz, bx))
             reduce_channel<ALIGNED, false>(p, reinterpret_cast<const GT *>(p.G) + (size_t)b * T * D3, t, D3, a, r, bx, ox, oy, oz,
                                            marks, sx, sy, sz, sv);
-        const float inv_r2 = __builtin_amdgcn_rcpf(r * p.sk);    // 1/r^2 times r/sqrt(k): the sums are in scaled units
+        // -4 (the sums hold -f/4) / r^2 times r/sqrt(k) (they are in scaled units)
+        const float inv_r2 = -4.0f * __builtin_amdgcn_rcpf(r * p.sk);
         tx = wave_sum(sx) * inv_r2;
         ty = wave_sum(sy) * inv_r2;
         tz = wave_sum(sz) * inv_r2;
@@ -552,7 +561,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
                 const float inv = gc.live[q] ? __builtin_amdgcn_rcpf(rq[q]) : 0.0f;
                 const float ratio = rmax * inv;
                 gc.ratio2[q] = ratio * ratio;
-                gc.cq[q] = wq[q] * ratio * inv * p.inv_sk;
+                gc.cq[q] = -4.0f * (wq[q] * ratio * inv * p.inv_sk);
                 sv[q] = 0.0f;
             }
             Box bx;
@@ -623,8 +632,8 @@ hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace 
         p.inv_sk = (float)(1.0 / std::sqrt(k));
         p.g2k = (float)((double)gs.g2 * k);
         p.c2k = (float)((double)gs.c * (double)gs.c * k);
-        p.A2 = (float)(2.0 * (double)gs.A);
-        p.cAk2 = (float)(2.0 * (double)gs.A * (double)gs.c * std::sqrt(k));
+        p.hA = (float)(0.5 * (double)gs.A);
+        p.hAck = (float)(0.5 * (double)gs.A * (double)gs.c * std::sqrt(k));
         p.sAk = (float)std::sqrt((double)gs.A / k);
         p.cA = (float)((double)gs.c * std::sqrt((double)gs.A));
     }

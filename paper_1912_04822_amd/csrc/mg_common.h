@@ -154,10 +154,15 @@ hipError_t launch_draw_transforms(uint64_t seed, uint64_t draw, int B, bool rand
 hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                        float *grad_coords_to_clear, float *grad_weights_to_clear, int stop,
                        hipStream_t stream);
+// Small problems (index types, float grid): the forward kernel alone, no prep kernel -- every
+// tile's wavefront transforms, culls and filters the example's atoms itself.
+constexpr int kSmallAtoms = 256;        // most atoms per example
+constexpr int kSmallTotal = 2048;       // most atoms in the batch
+bool forward_takes_single_launch(const Batch &bt, bool out_is_double);
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                           void *out, bool out_is_double, int tile_floats, int waves_per_tile,
-                          int xcd_run, int lds_floor, int debug, int tile_order, int keep_alive, KernelEvents ev,
-                          hipStream_t stream);
+                          int xcd_run, int lds_floor, int debug, int tile_order, int keep_alive,
+                          bool single_launch, KernelEvents ev, hipStream_t stream);
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                            const void *grad_out, bool grad_is_double, float *grad_coords,
                            float *grad_weights, KernelEvents ev, hipStream_t stream);

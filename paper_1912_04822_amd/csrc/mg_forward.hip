@@ -63,6 +63,7 @@
 
 #include "mg_common.h"
 #include "mg_wave.h"
+#include "mg_xform.h"
 
 namespace mg {
 
@@ -72,8 +73,18 @@ constexpr int kTaskCap = 256;                   // (atom, row) tasks staged per 
 constexpr float kFixedOne = 16777216.0f;        // 2^24
 constexpr float kFixedLimit = 120.0f;           // largest |sum| trusted to fixed point
 
+// The caller's arrays, for the single-launch path of small problems (no prep kernel, no tables).
+struct RawInputs {
+    const float *coords;
+    const int32_t *types;
+    const float *radii;
+    const int32_t *natoms;
+    const float *centers, *quats, *translations;
+};
+
 struct FwdParams {
     GridSpec gs;
+    RawInputs raw;
     const float4 *rec;
     const int *idx;
     const int2 *range;
@@ -482,7 +493,10 @@ __device__ inline TileGeom tile_geom(const FwdParams &p, int D, unsigned tile_in
 
 // One tile of channel (b, t): the records [r0, r1) of the example can reach it; cen is the
 // grid centre.
-template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS, int NW, typename OUT>
+// FUSED (small problems, index types): there are no records; the "records" [r0, r1) are the
+// example's atoms themselves, and a lane transforms, culls and filters by type the atom it takes,
+// with the arithmetic and the tests of the prep kernel.
+template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS, int NW, typename OUT, bool FUSED = false>
 __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b, int t,
                                           const TileGeom &tg, int r0, int r1, const float4 &cen)
 {
@@ -526,6 +540,8 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
         store_tile<ALIGNED, ITERS, NW, OUT>(cx, dst, false, false);
         return;
     }
+    Xform X;
+    if (FUSED) load_xform(X, b, p.raw.centers, p.raw.quats, p.raw.translations);
 
     // How the wavefronts share the work: the `nsplit` wavefronts of a set take the atoms of
     // the span in turn (atom e goes to lane e / nsplit of member e % nsplit, round after
@@ -547,6 +563,29 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
         Atom at;
         at.a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         at.w = 1.0f;
+        if (FUSED) {
+            // type, coordinates and radius are requested together (one trip to memory), whatever
+            // the type turns out to be
+            const int ec = min(e, count - 1);           // count >= 1 here
+            const int te = p.raw.types[(size_t)b * N + ec];
+            const float *c3 = p.raw.coords + ((size_t)b * N + ec) * 3;
+            const float cc[3] = {c3[0], c3[1], c3[2]};
+            const float rad = p.raw.radii[gs.radius_type_indexed ? (size_t)t : (size_t)b * N + ec];
+            if (e < count && te == t) {
+                float pp[3];
+                apply_xform(X, cc, pp);
+                const float r = gs.radius_scale * rad;
+                const float reach = BINARY ? r : r * gs.c;
+                const float org[3] = {ox, cx.oy, cx.oz};
+                const float span = (float)(D - 1) * gs.res, pad = 1.0e-3f * gs.res;
+                bool live = (r > 0.0f) && (reach < 1.0e30f);
+                for (int k = 0; k < 3; ++k)     // also false for NaN / infinite coordinates
+                    live = live && (pp[k] >= org[k] - reach - pad) && (pp[k] <= org[k] + span + reach + pad);
+                if (live) at.a = make_float4(pp[0], pp[1], pp[2], r);
+            }
+            at.valid = at.a.w > 0.0f;
+            return at;
+        }
         if (e < count) {
             at.a = rec[e];
             if (VECTOR && at.a.w > 0.0f) at.w = wcol[(size_t)idx[e] * T];
@@ -704,7 +743,7 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
 
 
 // One workgroup per tile.  OUT: float, or double for a grid of doubles.
-template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS, int NW, typename OUT>
+template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS, int NW, typename OUT, bool FUSED = false>
 __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];   // tile | marks per wave | shared
@@ -746,6 +785,24 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     const unsigned tile_in_chan = p.pos_major ? uq : ur;
     const int b = (int)div_u32(chan, p.t_magic);
     const int t = (int)chan - b * T;
+    if (FUSED) {
+        // small problems: no tables; the grid centre is the example's centre, the candidates are
+        // the example's atoms (tile_body transforms and filters them)
+        const TileGeom tgf = tile_geom<ITERS>(p, D, tile_in_chan);
+        float4 cenf = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (p.raw.centers) {
+            cenf.x = p.raw.centers[3 * b];
+            cenf.y = p.raw.centers[3 * b + 1];
+            cenf.z = p.raw.centers[3 * b + 2];
+        }
+        int n = N;
+        if (p.raw.natoms) {
+            n = p.raw.natoms[b];
+            n = n < 0 ? 0 : (n > N ? N : n);
+        }
+        tile_body<VECTOR, BINARY, ALIGNED, ITERS, NW, OUT, true>(p, lds, b, t, tgf, 0, n, cenf);
+        return;
+    }
     const size_t group = (size_t)b * T + (VECTOR ? 0 : t);
     // All the scalar loads of the preamble are issued together (one trip to L2, which is
     // slow while the chip streams stores): the span of records that can reach the planes
@@ -1152,6 +1209,7 @@ static hipError_t launch_forward_vector(const GridSpec &gs, const Batch &bt, con
     p.radii = bt.radii;
     p.gcen = ws.gcen;
     p.chan_order = ws.chan_order;
+    p.raw = RawInputs{};
     p.groups = (unsigned)((bt.T + kVecGroup - 1) / kVecGroup);
     p.out = out;
     p.subgrids = bt.sub.count; p.N = bt.N; p.T = bt.T;
@@ -1205,14 +1263,31 @@ static hipError_t launch_forward_vector(const GridSpec &gs, const Batch &bt, con
     return hipGetLastError();
 }
 
+bool forward_takes_single_launch(const Batch &bt, bool out_is_double)
+{
+    // index types into a float grid, no subgrids, at most kSmallAtoms atoms per example and
+    // kSmallTotal in all: every tile's wavefront can afford to look at all of them itself
+    return !bt.weights && !out_is_double && bt.sub.count == 1 && bt.N <= kSmallAtoms &&
+           (long long)bt.B * bt.N <= kSmallTotal;
+}
+
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws, void *out,
                           bool out_is_double, int tile_floats, int waves_per_tile, int xcd_run,
-                          int lds_floor, int debug, int tile_order, int keep_alive, KernelEvents ev, hipStream_t stream)
+                          int lds_floor, int debug, int tile_order, int keep_alive, bool single_launch,
+                          KernelEvents ev, hipStream_t stream)
 {
     if (bt.weights && !gs.binary)
         return launch_forward_vector(gs, bt, ws, out, out_is_double, tile_floats, waves_per_tile, ev, stream);
     if (tile_floats == 512) tile_floats = 1024;     // the smallest tile of these kernels
     if (waves_per_tile == 0) waves_per_tile = 1;
+    if (single_launch) {        // one shape only: 4 KB tiles, one wavefront, ids in order
+        tile_floats = 1024;
+        waves_per_tile = 1;
+        xcd_run = 0;
+        tile_order = 0;
+        keep_alive = 0;
+        lds_floor = 0;
+    }
     if (tile_floats == 0) {
         // 4 KB tiles unless a tile meets many records (then the fixed cost per tile counts for
         // more than the shorter life of a small tile): about N/T atoms per channel, of which
@@ -1241,6 +1316,8 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     p.gcen = ws.gcen;
     p.chan_order = ws.chan_order;
     p.groups = 0;
+    p.raw.coords = bt.coords; p.raw.types = bt.types; p.raw.radii = bt.radii; p.raw.natoms = bt.natoms;
+    p.raw.centers = bt.centers; p.raw.quats = bt.quats; p.raw.translations = bt.translations;
     p.out = out;
     p.subgrids = bt.sub.count; p.N = bt.N; p.T = bt.T;
     p.tile_floats = fg.tile_floats;
@@ -1306,7 +1383,14 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     case 8 * 8 + 4: MG_LAUNCH5(V, Bn, Al, 8, 4); break;                         \
     default: return hipErrorInvalidValue;                                       \
     }
-    if (vec) {      // binary occupancy with vector types (the real density took the kernel above)
+    if (single_launch) {
+#define MG_FUSED(Bn, Al) \
+    hipExtLaunchKernelGGL((forward_kernel<false, Bn, Al, 2, 1, float, true>), grd, blk, (uint32_t)lds_bytes, \
+                          stream, ev.start, ev.stop, 0, p)
+        if (gs.binary) { if (aligned) MG_FUSED(true, true); else MG_FUSED(true, false); }
+        else           { if (aligned) MG_FUSED(false, true); else MG_FUSED(false, false); }
+#undef MG_FUSED
+    } else if (vec) {      // binary occupancy with vector types (the real density took the kernel above)
         if (aligned) MG_LAUNCH(true, true, true) else MG_LAUNCH(true, true, false)
     } else {
         if (gs.binary) { if (aligned) MG_LAUNCH(false, true, true) else MG_LAUNCH(false, true, false) }

@@ -30,6 +30,16 @@ def mg():
     return molgrid
 
 
+@pytest.fixture(autouse=True, params=[1, 0], ids=["single_launch", "prep_tables"])
+def both_small_problem_paths(request, mg):
+    """Small problems (at most 256 atoms per example, 2048 in all) run as one kernel launch by
+    default; every test of this file also runs with that path switched off, so that the small
+    and awkward cases keep exercising the prep kernel and its tables as well."""
+    mg.set_option("single_launch", request.param)
+    yield
+    mg.set_option("single_launch", 1)
+
+
 def dev(a, dtype=None):
     if a is None:
         return None
@@ -220,6 +230,28 @@ def test_forward_single_type_many_atoms(mg):
     err = np.abs(got - ref).max()
     assert err <= grid_tol(ref), (err, ref.max())
     assert got[:, :3].max() == 0 and got[:, 4:].max() == 0
+
+
+def test_single_launch_path_equals_the_prep_path_bit_for_bit(mg):
+    """Fixed-point sums do not depend on the order of the atoms, and both paths transform and
+    cull with the same arithmetic: the grids are identical, real and binary."""
+    cases = [(workloads.tiny(), None), (workloads.ragged_small(), workloads.ragged_small().extra["natoms"]),
+             (workloads.protein_ligand(B=8, n_receptor=216, n_ligand=40, seed=9), None)]
+    for w, nat in cases:
+        assert w.N <= 256 and w.B * w.N <= 2048
+        for binary in (False, True):
+            for per_atom in (False, True):
+                grids = []
+                for single in (1, 0):
+                    mg.set_option("single_launch", single)
+                    grids.append(run_forward_index(mg, w, binary=binary, natoms=nat,
+                                                   per_atom_radii=per_atom))
+                assert np.array_equal(grids[0].view(np.uint32), grids[1].view(np.uint32))
+                ref = oracle_forward_index(w, binary=binary, natoms=nat, per_atom_radii=per_atom)
+                if binary:
+                    assert np.array_equal(grids[0].view(np.uint32), ref.view(np.uint32))
+                else:
+                    assert np.abs(grids[0] - ref).max() <= GRID_TOL
 
 
 def test_forward_overwrites_output_and_empty_batch(mg):

@@ -379,9 +379,20 @@ def main():
                                  translations=trans, grad_coords=gc, workspace=ws)
 
         r = row(train_step, n_fast, timed_kernel=False)
+
+        def train_step_prepared():      # the tables built once, both passes on them
+            gm.mg_prepare(coords, types, radii, w.T, centers=centers, quats=quats,
+                          translations=trans, workspace=ws)
+            gm.mg_forward_index_prepared(w.B, w.N, w.T, ws, out=out)
+            gm.mg_backward_index_prepared(w.B, w.N, w.T, G, ws, grad_coords=gc)
+
+        r2 = row(train_step_prepared, n_fast, timed_kernel=False)
         rows["forward_plus_backward_index"] = {
             "ms_per_step": r["ms_per_call"],
-            "what": "mg_forward_index then mg_backward_index on the same inputs and workspace"}
+            "ms_per_step_prepared": r2["ms_per_call"],
+            "what": "mg_forward_index then mg_backward_index on the same inputs and workspace; "
+                    "prepared: mg_prepare once, then mg_forward_index_prepared and "
+                    "mg_backward_index_prepared on its tables"}
 
         # one 16-example chunk of the large / high-resolution configuration (96^3 at 0.25 A,
         # 8000 atoms per example); freed first: the chunk's grid is 1.6 GB

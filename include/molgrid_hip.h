@@ -227,6 +227,41 @@ int mg_backward_vector(const mg_gridmaker *gm, int B, int N, int T,
                        void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Tables once, calls many: a training step runs forward and then backward on the
+ * same atoms and poses, and both calls begin by building the same tables in the
+ * workspace (transformed, culled, channel- and plane-binned records: the
+ * transform and culling of the Transformations and GridMaker sections).
+ * mg_prepare builds them alone; the *_prepared calls run on them without the
+ * prep kernel.  Arguments are as in the ordinary calls; types == NULL in
+ * mg_prepare makes the tables of vector types.  The contract is the caller's:
+ * the same GridMaker, B, N, T, the same workspace, and nothing else enqueued on
+ * that workspace in between (every ordinary forward / backward call rebuilds
+ * it); the input arrays must be the ones prepared (weights and radii are read
+ * again by the calls that take them).  As a guard, the tables carry a tag
+ * of (B, N, T, D, subgrids, kind of types, binary, radius_type_indexed) and the
+ * kernels of a *_prepared call whose tag differs return at once and write
+ * nothing -- a mismatch leaves the output untouched rather than reading tables
+ * of another shape.  Results are those of the ordinary calls, bit for bit.
+ */
+int mg_prepare(const mg_gridmaker *gm, int B, int N, int T,
+               const float *coords, const int32_t *types, const float *radii,
+               const int32_t *natoms, const float *centers, const float *quats,
+               const float *translations,
+               void *workspace, size_t workspace_bytes, void *stream);
+int mg_forward_index_prepared(const mg_gridmaker *gm, int B, int N, int T, float *out,
+                              void *workspace, size_t workspace_bytes, void *stream);
+int mg_forward_vector_prepared(const mg_gridmaker *gm, int B, int N, int T,
+                               const float *weights, const float *radii, float *out,
+                               void *workspace, size_t workspace_bytes, void *stream);
+int mg_backward_index_prepared(const mg_gridmaker *gm, int B, int N, int T,
+                               const float *grad_out, float *grad_coords,
+                               void *workspace, size_t workspace_bytes, void *stream);
+int mg_backward_vector_prepared(const mg_gridmaker *gm, int B, int N, int T,
+                                const float *weights, const float *radii, const float *grad_out,
+                                float *grad_coords, float *grad_weights,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The same four calls with the grid held in doubles (the paper's grids come
  * in float and double flavours, e.g. a 5-dimensional double grid on the
  * device): out / grad_out are [B][T][D][D][D] double (8-byte aligned); all

@@ -134,6 +134,7 @@ mg::Batch make_batch(const mg_gridmaker *gm, int B, int N, int T, const float *c
     mg::Batch bt;
     bt.B = B * gm->sub.count; bt.N = N; bt.T = T;
     bt.sub = gm->sub;
+    bt.vec = types == nullptr;      // index types have their type array; everything else is vector types
     bt.coords = coords; bt.types = types; bt.weights = weights; bt.radii = radii;
     bt.natoms = natoms; bt.centers = centers; bt.quats = quats; bt.translations = translations;
     return bt;
@@ -249,15 +250,29 @@ int mg_draw_transforms(uint64_t seed, uint64_t draw, int B, int random_rotation,
                                                  (hipStream_t)stream));
 }
 
+// How a call uses the workspace's tables: builds them and runs (the ordinary calls), builds them
+// only (mg_prepare), or runs on tables an earlier call built (the *_prepared calls).
+enum class Tables { kBuildAndRun, kBuildOnly, kUseBuilt };
+
 // Forward with either kind of types (types or weights is NULL) into a float or double grid.
+// With Tables::kUseBuilt, index types pass `index_types` = true and no arrays but the output
+// (the tables hold everything), vector types pass weights and radii.
 static int forward_call(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
                         const int32_t *types, const float *weights, const float *radii,
                         const int32_t *natoms, const float *centers, const float *quats,
                         const float *translations, void *out, bool out_is_double, void *workspace,
-                        size_t workspace_bytes, void *stream)
+                        size_t workspace_bytes, void *stream, Tables tables = Tables::kBuildAndRun,
+                        bool index_types = false)
 {
-    if (!gm || !coords || (!types && !weights) || !radii || !out) return MG_ENULL;
-    if (weights && !gm->gs.radius_type_indexed) return MG_EMODE;    // vector types need radii per type
+    if (tables == Tables::kUseBuilt) {
+        if (!gm || !out || (!index_types && (!weights || !radii))) return MG_ENULL;
+    } else if (tables == Tables::kBuildOnly) {
+        if (!gm || !coords || !radii) return MG_ENULL;
+    } else {
+        if (!gm || !coords || (!types && !weights) || !radii || !out) return MG_ENULL;
+    }
+    const bool vector_types = tables == Tables::kUseBuilt ? !index_types : types == nullptr;
+    if (vector_types && !gm->gs.radius_type_indexed) return MG_EMODE;    // vector types need radii per type
     int rc = check_shape(gm, B, N, T);
     if (rc != MG_OK) return rc;
     if (misaligned4(coords) || misaligned4(types) || misaligned4(weights) || misaligned4(radii) ||
@@ -266,22 +281,52 @@ static int forward_call(const mg_gridmaker *gm, int B, int N, int T, const float
         return MG_EALIGN;
     rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
     if (rc != MG_OK) return rc;
-    const mg::Batch bt = make_batch(gm, B, N, T, coords, types, weights, radii, natoms, centers,
-                                    quats, translations);
+    mg::Batch bt = make_batch(gm, B, N, T, coords, types, weights, radii, natoms, centers,
+                              quats, translations);
+    bt.vec = vector_types;
     const mg::Workspace ws = mg::carve_workspace(gm->gs, gm->sub.count, workspace, bt.B, N, T);
     const auto knob = [](const std::atomic<int> &k) { return k.load(std::memory_order_relaxed); };
     const int stop = timing_prep_stop();
     // a few hundred atoms in all: one launch, every tile looks at the atoms itself
-    const bool single = knob(g_single_launch) != 0 && stop == 0 && timing_debug() == 0 &&
-                        mg::forward_takes_single_launch(bt, out_is_double);
-    if (!single) {
-        rc = hip_status(mg::launch_prep(gm->gs, bt, ws, nullptr, nullptr, stop, (hipStream_t)stream));
+    const bool single = tables == Tables::kBuildAndRun && knob(g_single_launch) != 0 && stop == 0 &&
+                        timing_debug() == 0 && mg::forward_takes_single_launch(bt, out_is_double);
+    if (tables != Tables::kUseBuilt && !single) {
+        rc = hip_status(mg::launch_prep(gm->gs, bt, ws, stop, (hipStream_t)stream));
         if (rc != MG_OK || stop != 0) return rc;    // a prep kernel cut short leaves no tables to read
     }
+    if (tables == Tables::kBuildOnly) return MG_OK;
+    const unsigned expect = tables == Tables::kUseBuilt ? mg::workspace_tag(gm->gs, bt) : 0u;
     return hip_status(mg::launch_forward(gm->gs, bt, ws, out, out_is_double, knob(g_tile_floats),
                                          knob(g_waves_per_tile), knob(g_xcd_run), knob(g_lds_floor),
                                          timing_debug(), knob(g_tile_order), knob(g_keep_alive), single,
-                                         take_events(), (hipStream_t)stream));
+                                         expect, take_events(), (hipStream_t)stream));
+}
+
+int mg_prepare(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
+               const int32_t *types, const float *radii, const int32_t *natoms,
+               const float *centers, const float *quats, const float *translations,
+               void *workspace, size_t workspace_bytes, void *stream)
+{
+    return forward_call(gm, B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
+                        translations, nullptr, false, workspace, workspace_bytes, stream,
+                        Tables::kBuildOnly);
+}
+
+int mg_forward_index_prepared(const mg_gridmaker *gm, int B, int N, int T, float *out,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    return forward_call(gm, B, N, T, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                        nullptr, out, false, workspace, workspace_bytes, stream, Tables::kUseBuilt,
+                        true);
+}
+
+int mg_forward_vector_prepared(const mg_gridmaker *gm, int B, int N, int T, const float *weights,
+                               const float *radii, float *out, void *workspace,
+                               size_t workspace_bytes, void *stream)
+{
+    return forward_call(gm, B, N, T, nullptr, nullptr, weights, radii, nullptr, nullptr, nullptr,
+                        nullptr, out, false, workspace, workspace_bytes, stream, Tables::kUseBuilt,
+                        false);
 }
 
 int mg_forward_index(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
@@ -351,12 +396,18 @@ static int backward_call(const mg_gridmaker *gm, int B, int N, int T, const floa
                          const int32_t *natoms, const float *centers, const float *quats,
                          const float *translations, const void *grad_out, bool grad_is_double,
                          float *grad_coords, float *grad_weights, void *workspace,
-                         size_t workspace_bytes, void *stream)
+                         size_t workspace_bytes, void *stream, Tables tables = Tables::kBuildAndRun,
+                         bool index_types = false)
 {
-    if (!gm || !coords || (!types && !weights) || !radii || !grad_out) return MG_ENULL;
+    if (tables == Tables::kUseBuilt) {      // index types: nothing but the tables; vector types: weights and radii
+        if (!gm || (!index_types && (!weights || !radii)) || !grad_out) return MG_ENULL;
+    } else {
+        if (!gm || !coords || (!types && !weights) || !radii || !grad_out) return MG_ENULL;
+        index_types = types != nullptr;
+    }
     if (!grad_coords && !grad_weights) return MG_ENULL;
-    if (types && !grad_coords) return MG_ENULL;
-    if (gm->gs.binary || (weights && !gm->gs.radius_type_indexed)) return MG_EMODE;
+    if (index_types && !grad_coords) return MG_ENULL;
+    if (gm->gs.binary || (!index_types && !gm->gs.radius_type_indexed)) return MG_EMODE;
     int rc = check_shape(gm, B, N, T);
     if (rc != MG_OK) return rc;
     if (misaligned4(coords) || misaligned4(types) || misaligned4(weights) || misaligned4(radii) ||
@@ -366,17 +417,21 @@ static int backward_call(const mg_gridmaker *gm, int B, int N, int T, const floa
         return MG_EALIGN;
     rc = check_workspace(gm, B, N, T, workspace, workspace_bytes);
     if (rc != MG_OK) return rc;
-    const mg::Batch bt = make_batch(gm, B, N, T, coords, types, weights, radii, natoms, centers,
-                                    quats, translations);
+    mg::Batch bt = make_batch(gm, B, N, T, coords, types, weights, radii, natoms, centers,
+                              quats, translations);
+    bt.vec = !index_types;
     const mg::Workspace ws = mg::carve_workspace(gm->gs, gm->sub.count, workspace, bt.B, N, T);
     // with subgrids each virtual example's gradient goes to the workspace and they are summed
     const bool sub = gm->sub.count > 1;
     float *gc = (sub && grad_coords) ? ws.gtmp : grad_coords;
     float *gw = (sub && grad_weights) ? ws.wtmp : grad_weights;
-    const int stop = timing_prep_stop();
-    rc = hip_status(mg::launch_prep(gm->gs, bt, ws, gc, gw, stop, (hipStream_t)stream));
-    if (rc != MG_OK || stop != 0) return rc;    // a prep kernel cut short leaves no tables to read
-    rc = hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, grad_is_double, gc, gw,
+    if (tables != Tables::kUseBuilt) {
+        const int stop = timing_prep_stop();
+        rc = hip_status(mg::launch_prep(gm->gs, bt, ws, stop, (hipStream_t)stream));
+        if (rc != MG_OK || stop != 0) return rc;    // a prep kernel cut short leaves no tables to read
+    }
+    const unsigned expect = tables == Tables::kUseBuilt ? mg::workspace_tag(gm->gs, bt) : 0u;
+    rc = hip_status(mg::launch_backward(gm->gs, bt, ws, grad_out, grad_is_double, gc, gw, expect,
                                         take_events(), (hipStream_t)stream));
     if (rc != MG_OK || !sub) return rc;
     if (grad_coords)
@@ -398,6 +453,26 @@ int mg_backward_index(const mg_gridmaker *gm, int B, int N, int T, const float *
     return backward_call(gm, B, N, T, coords, types, nullptr, radii, natoms, centers, quats,
                          translations, grad_out, false, grad_coords, nullptr, workspace,
                          workspace_bytes, stream);
+}
+
+int mg_backward_index_prepared(const mg_gridmaker *gm, int B, int N, int T,
+                               const float *grad_out, float *grad_coords, void *workspace,
+                               size_t workspace_bytes, void *stream)
+{
+    return backward_call(gm, B, N, T, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                         nullptr, grad_out, false, grad_coords, nullptr, workspace, workspace_bytes,
+                         stream, Tables::kUseBuilt, true);
+}
+
+int mg_backward_vector_prepared(const mg_gridmaker *gm, int B, int N, int T, const float *weights,
+                                const float *radii, const float *grad_out, float *grad_coords,
+                                float *grad_weights, void *workspace, size_t workspace_bytes,
+                                void *stream)
+{
+    if (!weights) return MG_ENULL;
+    return backward_call(gm, B, N, T, nullptr, nullptr, weights, radii, nullptr, nullptr, nullptr,
+                         nullptr, grad_out, false, grad_coords, grad_weights, workspace,
+                         workspace_bytes, stream, Tables::kUseBuilt);
 }
 
 int mg_backward_index_f64(const mg_gridmaker *gm, int B, int N, int T, const float *coords,

@@ -46,10 +46,13 @@ struct BwdParams {
     const int *idx;
     const int4 *meta;
     const float *rot;
-    const int32_t *types;
+    const int *rchan;       // [B][N] channel of each record (index types)
     const float *weights;
     const float *radii;
     const float *gcen;
+    const unsigned char *alive;     // [B][N] 1: the atom has a live record
+    const unsigned *tag;            // what the workspace's tables were made for
+    unsigned expect_tag;            // != 0: do nothing unless *tag equals it (calls on prepared tables)
     const void *G;          // upstream gradient grid, float or double
     float *grad_coords;
     float *grad_weights;
@@ -209,8 +212,7 @@ __device__ inline void reduce_channel_box(const BwdParams &p, const GT *Gc, cons
 
 // Only the slots that meet the cutoff sphere.  `marks` is this wavefront's kSlotCap bytes of
 // LDS, all zero on entry and on return.
-// The channel is G + t * D3; t may still be on its way from memory (index types read it
-// from the types array) and is not touched before the first slot is read.
+// The channel is G + t * D3 (index types: t comes with the record, from the workspace).
 template <bool ALIGNED, bool WANT_VALUE, typename GT>
 __device__ inline void reduce_channel(const BwdParams &p, const GT *G, int t, size_t D3,
                                       const float4 &a, float r, const Box &bx, float ox, float oy,
@@ -471,6 +473,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
     // Workgroup ids go round the 8 XCDs (id % 8), each with its own L2.  XCD k takes the k-th
     // eighth of the (example, record) list, so the gradient volume of an example -- and the
     // lines of it that neighbouring records share -- is read through one L2 only.
+    if (p.expect_tag != 0u && *p.tag != p.expect_tag) return;      // not the tables this call expects
     const unsigned lin = blockIdx.x + zero;
     const unsigned v = (lin & 7u) * p.share + (lin >> 3);
     if (v >= p.units || (lin >> 3) >= p.share) return;
@@ -478,6 +481,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
     const int b = (int)bu, slot = (int)((v - bu * p.wgs_per_example) * 4u + (threadIdx.x >> 6));
     const int lane = (int)(threadIdx.x & 63u);
     const int N = p.N, T = p.T, D = gs.D;
+
     __shared__ __attribute__((aligned(16))) unsigned char s_marks[4][kSlotCap];
     unsigned char *marks = s_marks[threadIdx.x >> 6];
     static_assert(kSlotCap == 64 * 16, "one 16-byte store per lane clears the marks");
@@ -488,9 +492,11 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
     // clamped into the array; whether the slot is live is decided afterwards), the grid
     // centre and the rotation.
     const int cslot = min(slot, N - 1);
+    const unsigned char atom_alive = p.alive[(size_t)b * N + cslot];    // of ATOM number `slot`, see below
     const int4 last = p.meta[(size_t)b * T + (VECTOR ? 0 : T - 1)];
     const float4 a = p.rec[(size_t)b * N + cslot];
     const int ai = p.idx[(size_t)b * N + cslot];
+    const int t_rec = VECTOR ? 0 : p.rchan[(size_t)b * N + cslot];
     const float4 gc = *reinterpret_cast<const float4 *>(p.gcen + 4 * b);
     const float *Rp = p.rot + b * 12;
     const float4 Ra = *reinterpret_cast<const float4 *>(Rp);
@@ -498,8 +504,17 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
     const float Rc = Rp[8];
     asm volatile("" ::"s"(last.x), "s"(last.z), "s"(gc.x), "s"(gc.y), "s"(gc.z), "s"(Ra.x), "s"(Ra.y),
                  "s"(Ra.z), "s"(Ra.w), "s"(Rb.x), "s"(Rb.y), "s"(Rb.z), "s"(Rb.w), "s"(Rc));
+    // Every output element is written by someone: the wavefront of record slot s also looks
+    // after ATOM s -- if that atom has no live record (culled, past natoms, type out of range)
+    // nobody else writes its gradient, so its zeros are stored here.
+    if (slot < N && atom_alive == 0) {
+        const size_t atom = (size_t)b * N + slot;
+        if (p.grad_coords && lane < 3) p.grad_coords[atom * 3 + lane] = 0.0f;
+        if (VECTOR && p.grad_weights)
+            for (int k = lane; k < T; k += 64) p.grad_weights[atom * T + k] = 0.0f;
+    }
     if (slot >= last.x + last.z) return;            // past the last group's slots (per wavefront)
-    if (!(a.w > 0.0f)) return;                      // dead record: the prep kernel wrote its zeros
+    if (!(a.w > 0.0f)) return;                      // dead record: its atom's zeros are written above, by slot
     const size_t D3 = (size_t)D * D * D;
     const int bs = source_example(p.subgrids, b);          // types and weights are the source example's
     const float ox = gc.x - gs.half;
@@ -508,7 +523,7 @@ __global__ __launch_bounds__(256) void backward_kernel(BwdParams p)
 
     float tx = 0.0f, ty = 0.0f, tz = 0.0f;          // gradient in the transformed frame
     if (!VECTOR) {
-        const int t = p.types[(size_t)bs * N + ai];
+        const int t = t_rec;
         const float r = a.w;
         Box bx;
         float sx = 0.0f, sy = 0.0f, sz = 0.0f, sv = 0.0f;
@@ -618,12 +633,14 @@ hipError_t launch_sum_subgrids(int subgrid_count, int B_source, size_t per_examp
 
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                            const void *grad_out, bool grad_is_double, float *grad_coords,
-                           float *grad_weights, KernelEvents ev, hipStream_t stream)
+                           float *grad_weights, unsigned expect_tag, KernelEvents ev,
+                           hipStream_t stream)
 {
     BwdParams p;
     p.gs = gs;
     p.rec = ws.rec; p.idx = ws.idx; p.meta = ws.meta; p.rot = ws.rot;
-    p.types = bt.types; p.weights = bt.weights; p.radii = bt.radii; p.gcen = ws.gcen;
+    p.rchan = ws.rchan; p.weights = bt.weights; p.radii = bt.radii; p.gcen = ws.gcen;
+    p.alive = ws.alive; p.tag = ws.tag; p.expect_tag = expect_tag;
     p.G = grad_out; p.grad_coords = grad_coords; p.grad_weights = grad_weights;
     p.subgrids = bt.sub.count; p.N = bt.N; p.T = bt.T;
     {
@@ -646,7 +663,7 @@ hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace 
 #define MG_BWD(V, Al, Gt) \
     hipExtLaunchKernelGGL((backward_kernel<V, Al, Gt>), grd, blk, 0, stream, ev.start, ev.stop, 0, p)
 #define MG_BWD_TYPE(Gt)                                      \
-    if (bt.weights) {                                        \
+    if (bt.vec) {                                        \
         if (aligned) MG_BWD(true, true, Gt);                 \
         else MG_BWD(true, false, Gt);                        \
     } else {                                                 \

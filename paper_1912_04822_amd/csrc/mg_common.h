@@ -80,6 +80,14 @@ __host__ __device__ inline int source_example(int subgrid_count, int e)
 //   chan_order [B][T] int32  vector types: the channels in order of radius (ties by index;
 //                         as they come beyond kRankCap channels), so that channels taken
 //                         together have spheres of nearly the same size
+//   alive [B][N] uint8    1 for an atom that has a live record, 0 for one that is culled,
+//                         past natoms or of a type outside [0,T): the backward kernels write
+//                         the zero gradients of those (the wavefront of record slot s looks
+//                         after atom s)
+//   rchan [B][N] int32    the channel of each record (index types: the atom's type), so that
+//                         the backward kernel has it with the record and not a trip to the
+//                         type array later
+//   tag   [1] uint32      what the tables were made for (workspace_tag), written last
 //   gtmp  [B][N][3] float, wtmp [B][N][T] float: with subgrids only, the
 //                         gradients per virtual example before they are summed
 // With subgrids B counts virtual examples everywhere above.
@@ -92,6 +100,9 @@ struct Workspace {
     float  *rot;
     float  *gcen;
     int    *chan_order;
+    unsigned char *alive;
+    int    *rchan;
+    unsigned *tag;
     float  *gtmp;
     float  *wtmp;
 };
@@ -103,6 +114,7 @@ Workspace carve_workspace(const GridSpec &gs, int subgrid_count, void *base, int
 // B counts virtual examples (see Subgrids); the arrays are indexed by source example.
 struct Batch {
     int B, N, T;
+    bool vec;                     // vector types (weights) rather than index types
     Subgrids sub;
     const float   *coords;        // [B][N][3]
     const int32_t *types;         // [B][N] or null (vector types)
@@ -151,21 +163,24 @@ hipError_t launch_transform(int B, int N, const float *coords, const float *cent
 hipError_t launch_draw_transforms(uint64_t seed, uint64_t draw, int B, bool random_rotation,
                                   float max_translation, float *quats, float *translations,
                                   hipStream_t stream);
-hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
-                       float *grad_coords_to_clear, float *grad_weights_to_clear, int stop,
+unsigned workspace_tag(const GridSpec &gs, const Batch &bt);
+hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws, int stop,
                        hipStream_t stream);
 // Small problems (index types, float grid): the forward kernel alone, no prep kernel -- every
 // tile's wavefront transforms, culls and filters the example's atoms itself.
 constexpr int kSmallAtoms = 256;        // most atoms per example
 constexpr int kSmallTotal = 2048;       // most atoms in the batch
 bool forward_takes_single_launch(const Batch &bt, bool out_is_double);
+// expect_tag != 0 (a *_prepared call): the kernel returns at once, writing nothing, unless the
+// workspace's tag equals it
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                           void *out, bool out_is_double, int tile_floats, int waves_per_tile,
                           int xcd_run, int lds_floor, int debug, int tile_order, int keep_alive,
-                          bool single_launch, KernelEvents ev, hipStream_t stream);
+                          bool single_launch, unsigned expect_tag, KernelEvents ev, hipStream_t stream);
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                            const void *grad_out, bool grad_is_double, float *grad_coords,
-                           float *grad_weights, KernelEvents ev, hipStream_t stream);
+                           float *grad_weights, unsigned expect_tag, KernelEvents ev,
+                           hipStream_t stream);
 // grad[b] = sum over the sub3 virtual examples of b, in order (subgrids only)
 hipError_t launch_sum_subgrids(int subgrid_count, int B_source, size_t per_example,
                                const float *tmp, float *grad, hipStream_t stream);

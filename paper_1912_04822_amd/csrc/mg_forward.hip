@@ -93,6 +93,8 @@ struct FwdParams {
     const float *gcen;          // [B][4] grid centres, written by the prep kernel
     const int *chan_order;      // [B][T] vector types: channels in order of radius
     unsigned groups;            // vector types: groups of kVecGroup channels per example
+    const unsigned *tag;        // what the workspace's tables were made for
+    unsigned expect_tag;        // != 0: do nothing unless *tag equals it (calls on prepared tables)
     void *out;                      // float or double grid
     int subgrids, N, T;             // subgrids: virtual examples per example (weights are per example)
     int tile_floats;                // floats per tile (a multiple of 512)
@@ -763,6 +765,7 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
           "s"((unsigned long long)p.gcen), "s"((unsigned long long)p.out), "s"(p.tiles_magic),
           "s"(p.t_magic), "s"(p.div_magic), "s"(p.tiles), "s"(p.pos_major), "s"(p.ka_chunks), "s"(p.ka_last), "s"(p.xcd_shift), "s"(p.n_remap), "s"(D),
           "s"(T), "s"(N), "s"(p.debug), "s"(gs.half));
+    if (p.expect_tag != 0u && *p.tag != p.expect_tag) return;      // not the tables this call expects
     unsigned u = blockIdx.x + zero;
     if (p.xcd_shift >= 0 && u < p.n_remap) {
         const unsigned xcd = u & 7u, slot = u >> 3, sh = (unsigned)p.xcd_shift;
@@ -980,6 +983,7 @@ __global__ __launch_bounds__(64 * NW) void forward_vector_kernel(FwdParams p)
     const GridSpec &gs = p.gs;
     const int D = gs.D, T = p.T, N = p.N;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (p.expect_tag != 0u && *p.tag != p.expect_tag) return;      // not the tables this call expects
     const unsigned u = blockIdx.x;
     const unsigned uq = div_u32(u, p.tiles_magic), tile_in_chan = u - uq * p.tiles;
     const int b = (int)div_u32(uq, p.t_magic);          // t_magic: ceil(2^64 / groups)
@@ -1190,7 +1194,8 @@ unsigned long long magic64(unsigned d)      // ceil(2^64 / d); 0 stands for d ==
 // Vector types, real density: one wavefront per (example, group of kVecGroup channels, tile).
 static hipError_t launch_forward_vector(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                                         void *out, bool out_is_double, int tile_floats,
-                                        int waves_per_tile, KernelEvents ev, hipStream_t stream)
+                                        int waves_per_tile, unsigned expect_tag, KernelEvents ev,
+                                        hipStream_t stream)
 {
     // 2048-float tiles and four wavefronts per workgroup: the four channel tiles of a group take
     // 33 KB of LDS, so four workgroups (sixteen wavefronts, what 111 registers allow) fit a CU.
@@ -1209,6 +1214,8 @@ static hipError_t launch_forward_vector(const GridSpec &gs, const Batch &bt, con
     p.radii = bt.radii;
     p.gcen = ws.gcen;
     p.chan_order = ws.chan_order;
+    p.tag = ws.tag;
+    p.expect_tag = expect_tag;
     p.raw = RawInputs{};
     p.groups = (unsigned)((bt.T + kVecGroup - 1) / kVecGroup);
     p.out = out;
@@ -1267,17 +1274,18 @@ bool forward_takes_single_launch(const Batch &bt, bool out_is_double)
 {
     // index types into a float grid, no subgrids, at most kSmallAtoms atoms per example and
     // kSmallTotal in all: every tile's wavefront can afford to look at all of them itself
-    return !bt.weights && !out_is_double && bt.sub.count == 1 && bt.N <= kSmallAtoms &&
+    return !bt.vec && !out_is_double && bt.sub.count == 1 && bt.N <= kSmallAtoms &&
            (long long)bt.B * bt.N <= kSmallTotal;
 }
 
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws, void *out,
                           bool out_is_double, int tile_floats, int waves_per_tile, int xcd_run,
                           int lds_floor, int debug, int tile_order, int keep_alive, bool single_launch,
-                          KernelEvents ev, hipStream_t stream)
+                          unsigned expect_tag, KernelEvents ev, hipStream_t stream)
 {
-    if (bt.weights && !gs.binary)
-        return launch_forward_vector(gs, bt, ws, out, out_is_double, tile_floats, waves_per_tile, ev, stream);
+    if (bt.vec && !gs.binary)
+        return launch_forward_vector(gs, bt, ws, out, out_is_double, tile_floats, waves_per_tile, expect_tag, ev,
+                                     stream);
     if (tile_floats == 512) tile_floats = 1024;     // the smallest tile of these kernels
     if (waves_per_tile == 0) waves_per_tile = 1;
     if (single_launch) {        // one shape only: 4 KB tiles, one wavefront, ids in order
@@ -1295,7 +1303,7 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
         // Measured: 48^3 at 0.5 A with 2040 atoms (20 per tile) 102 us against 111 us with 8 KB
         // tiles; 96^3 at 0.25 A with 8000 atoms (74 per tile) 275 us with 8 KB tiles against 297 us,
         // with 6000 atoms (56 per tile) 281 against 279 us, with 5000 (47) 285 against 275 us.
-        const double groups = bt.weights ? 1.0 : (double)bt.T;
+        const double groups = bt.vec ? 1.0 : (double)bt.T;
         const double planes = 6.0 / (double)gs.res + 1.0;
         const double per_tile = (double)bt.N / groups * (planes < gs.D ? planes / gs.D : 1.0);
         tile_floats = per_tile > 60.0 ? 2048 : 1024;
@@ -1315,6 +1323,8 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     p.radii = bt.radii;
     p.gcen = ws.gcen;
     p.chan_order = ws.chan_order;
+    p.tag = ws.tag;
+    p.expect_tag = single_launch ? 0u : expect_tag;
     p.groups = 0;
     p.raw.coords = bt.coords; p.raw.types = bt.types; p.raw.radii = bt.radii; p.raw.natoms = bt.natoms;
     p.raw.centers = bt.centers; p.raw.quats = bt.quats; p.raw.translations = bt.translations;
@@ -1344,7 +1354,7 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
         p.ka_chunks = 0;
         p.ka_last = 0;
         // (vector types are bound by arithmetic and a grid of doubles by its own stores: measured no gain)
-        if (keep_alive && !bt.weights && !out_is_double && bytes >= 1024 && bytes < (1ull << 31)) {
+        if (keep_alive && !bt.vec && !out_is_double && bytes >= 1024 && bytes < (1ull << 31)) {
             p.ka_chunks = (unsigned)((bytes + 1023) >> 10);
             p.ka_last = (unsigned)(bytes - 1024);
         }
@@ -1361,10 +1371,10 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     size_t lds_bytes = (size_t)tile_floats * sizeof(float) + (size_t)nw * kTaskCap + 16;
     // 4 KB tiles, one wavefront each: 26 per CU (104 KB of stores in flight) instead of all 32
     // slots measured 98.2 us against 102.4 us on the 48^3 batch (22 to 30 per CU alike)
-    if (lds_floor < 0) lds_floor = (tile_floats == 1024 && nw == 1 && !out_is_double && !bt.weights) ? 6144 : 0;
+    if (lds_floor < 0) lds_floor = (tile_floats == 1024 && nw == 1 && !out_is_double && !bt.vec) ? 6144 : 0;
     if (lds_bytes < (size_t)lds_floor) lds_bytes = (size_t)lds_floor;
     const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)out & 15u) == 0);
-    const bool vec = bt.weights != nullptr;
+    const bool vec = bt.vec;
     const dim3 blk(64 * nw), grd((unsigned)groups);
 #define MG_LAUNCH5(V, Bn, Al, It, Nw) \
     hipExtLaunchKernelGGL((forward_kernel<V, Bn, Al, It, Nw, float>), grd, blk, (uint32_t)lds_bytes, \

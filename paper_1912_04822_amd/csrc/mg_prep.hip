@@ -117,15 +117,6 @@ __device__ inline bool place_atom(const GridSpec &gs, const Batch &bt, const Xfo
     return live;
 }
 
-__device__ inline void clear_grads(float *gclear, float *wclear, size_t atom, int T)
-{
-    if (gclear) {
-        float *g = gclear + atom * 3;
-        g[0] = 0.0f; g[1] = 0.0f; g[2] = 0.0f;
-    }
-    if (wclear)
-        for (int k = 0; k < T; ++k) wclear[atom * T + k] = 0.0f;
-}
 
 // Vector types: the channels of (virtual) example b in order of radius, for the kernels that
 // take several channels of an atom together (thread `tid` of `nthreads`).  NaN and negative
@@ -169,8 +160,8 @@ struct ExLayout {       // LDS, in ints
 
 template <bool VECTOR, int kPer>
 __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, Batch bt,
-                                                                  Workspace ws, float *gclear,
-                                                                  float *wclear, int stop)
+                                                                  Workspace ws, unsigned tag,
+                                                                  int stop)
 {
     extern __shared__ int s_mem[];
     const int b = blockIdx.x, tid = threadIdx.x;
@@ -218,6 +209,7 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     Xform X;
     load_xform(X, bs, bt.centers, bt.quats, bt.translations);
     if (tid < 9) ws.rot[b * 12 + tid] = (float)X.R[tid];
+    if (b == 0 && tid == 0) *ws.tag = tag;
     float vec_reach = 0.0f;         // reach of the widest channel, for vector types
     if (VECTOR) {
         rank_channels(bt, ws, b, tid, kExThreads);
@@ -278,9 +270,9 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
             }
             my_key[u] = tg * nb + bin;
             my_slot[u] = atomicAdd(&s_cnt[my_key[u]], 1);
-            if (!live) clear_grads(gclear, wclear, (size_t)b * N + a, T);
+            ws.alive[(size_t)b * N + a] = live ? 1 : 0;
         } else {
-            clear_grads(gclear, wclear, (size_t)b * N + a, T);   // no group owns this atom
+            ws.alive[(size_t)b * N + a] = 0;        // no group owns this atom
         }
     }
     __syncthreads();
@@ -351,13 +343,14 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
         }
         ws.rec[(size_t)b * N + lo + rank] = make_float4(my_p[u][0], my_p[u][1], my_p[u][2], my_w[u]);
         ws.idx[(size_t)b * N + lo + rank] = a;
+        if (!VECTOR) ws.rchan[(size_t)b * N + lo + rank] = key / nb;
     }
 }
 
 // One wavefront per group: no barriers, the scans are wavefront shuffles.
 template <bool VECTOR>
 __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspace ws,
-                                                  float *gclear, float *wclear, int stop)
+                                                  unsigned tag, int stop)
 {
     __shared__ int s_list[kSortCap];                // atom index of match m
     __shared__ unsigned short s_bin[kSortCap];      // x-bin of match m, 0xFFFF = culled
@@ -429,6 +422,7 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
 
     float4 *rec = ws.rec + (size_t)b * N + first;
     int *idx = ws.idx + (size_t)b * N + first;
+    int *rchan = ws.rchan + (size_t)b * N + first;
     const size_t group = (size_t)b * T + t;
     const int nbins = D + 2;
 
@@ -459,9 +453,8 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
                 bin = f < 0.0f ? 0 : (f >= (float)D ? D + 1 : (int)f + 1);
                 atomicAdd(&s_cnt[bin], 1);
                 atomicMax(&s_rmax, __float_as_int(r));      // r > 0: ordered like ints
-            } else {
-                clear_grads(gclear, wclear, (size_t)b * N + a, T);
             }
+            ws.alive[(size_t)b * N + a] = live ? 1 : 0;
             s_bin[m] = (unsigned short)bin;
         }
         lds_sync();
@@ -516,9 +509,11 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
                 (void)place_atom<VECTOR>(gs, bt, X, cu, bs, t, a, vec_reach, p, &r);
                 rec[pos] = make_float4(p[0], p[1], p[2], r);
                 idx[pos] = a;
+                rchan[pos] = t;
             } else {
                 rec[pos] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
                 idx[pos] = -1;
+                rchan[pos] = t;
             }
         }
         if (lane == 0) ws.meta[group] = make_int4(first, L, M, 1);
@@ -540,7 +535,8 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
                 const bool live = place_atom<VECTOR>(gs, bt, X, cu, bs, t, a, vec_reach, p, &r);
                 rec[r0 + m] = make_float4(p[0], p[1], p[2], live ? r : 0.0f);
                 idx[r0 + m] = a;
-                if (!live) clear_grads(gclear, wclear, (size_t)b * N + a, T);
+                rchan[r0 + m] = t;
+                ws.alive[(size_t)b * N + a] = live ? 1 : 0;
             }
             lds_sync();
         }
@@ -548,16 +544,17 @@ __global__ __launch_bounds__(64) void prep_kernel(GridSpec gs, Batch bt, Workspa
         if (lane == 0) ws.meta[group] = make_int4(first, M, M, 0);
     }
 
-    // atoms no group owns (past natoms, type outside [0,T)): zero gradients
-    if (t == 0 && (gclear || wclear)) {
+    // atoms no group owns (past natoms, type outside [0,T)) are not alive
+    if (t == 0) {
         for (int a = lane; a < N; a += 64) {
             bool orphan = a >= n;
             if (!VECTOR && !orphan) {
                 const int v = ty[a];
                 orphan = v < 0 || v >= T;
             }
-            if (orphan) clear_grads(gclear, wclear, (size_t)b * N + a, T);
+            if (orphan) ws.alive[(size_t)b * N + a] = 0;
         }
+        if (b == 0 && lane == 0) *ws.tag = tag;
     }
 }
 
@@ -575,6 +572,9 @@ size_t workspace_bytes(const GridSpec &gs, int subgrid_count, int B, int N, int 
     bytes += (size_t)B * 12 * sizeof(float);                // rot
     bytes += (size_t)B * 4 * sizeof(float);                 // gcen
     bytes += align16(bt * sizeof(int));                     // chan_order
+    bytes += align16(bn);                                   // alive
+    bytes += align16(bn * sizeof(int));                     // rchan
+    bytes += 16;                                            // tag
     if (subgrid_count > 1) {
         bytes += align16(bn * 3 * sizeof(float));           // gtmp
         if (gs.radius_type_indexed) bytes += align16(bn * (size_t)T * sizeof(float));   // wtmp
@@ -601,6 +601,12 @@ Workspace carve_workspace(const GridSpec &gs, int subgrid_count, void *base, int
     p += (size_t)B * 4 * sizeof(float);
     ws.chan_order = (int *)p;
     p += align16(bt * sizeof(int));
+    ws.alive = (unsigned char *)p;
+    p += align16(bn);
+    ws.rchan = (int *)p;
+    p += align16(bn * sizeof(int));
+    ws.tag = (unsigned *)p;
+    p += 16;
     ws.gtmp = nullptr;
     ws.wtmp = nullptr;
     if (subgrid_count > 1) {
@@ -625,10 +631,28 @@ hipError_t launch_transform(int B, int N, const float *coords, const float *cent
     return hipGetLastError();
 }
 
-hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws, float *gclear,
-                       float *wclear, int stop, hipStream_t stream)
+// What the tables were made for, folded into one word (never 0): the kernels of a *_prepared
+// call compare it with their own arguments and do nothing if the workspace holds something else.
+unsigned workspace_tag(const GridSpec &gs, const Batch &bt)
 {
-    const bool vec = bt.weights != nullptr;
+    unsigned long long h = 0x9E3779B97F4A7C15ull;
+    const unsigned words[] = {(unsigned)bt.B, (unsigned)bt.N, (unsigned)bt.T, (unsigned)gs.D,
+                              (unsigned)bt.sub.per_side, bt.vec ? 1u : 0u, (unsigned)gs.binary,
+                              (unsigned)gs.radius_type_indexed};
+    for (unsigned w : words) {
+        h ^= w;
+        h *= 0x100000001B3ull;
+        h ^= h >> 29;
+    }
+    const unsigned t = (unsigned)(h ^ (h >> 32));
+    return t ? t : 1u;
+}
+
+hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws, int stop,
+                       hipStream_t stream)
+{
+    const unsigned tag = workspace_tag(gs, bt);
+    const bool vec = bt.vec;
     ExLayout L;
     L.Tg = vec ? 1 : bt.T;
     L.N = bt.N;
@@ -640,26 +664,26 @@ hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
         if (bt.N <= 4 * kExThreads) {
             if (vec)
                 hipLaunchKernelGGL((prep_example_kernel<true, 4>), grd, blk, lds_bytes, stream, gs, bt,
-                                   ws, gclear, wclear, stop);
+                                   ws, tag, stop);
             else
                 hipLaunchKernelGGL((prep_example_kernel<false, 4>), grd, blk, lds_bytes, stream, gs,
-                                   bt, ws, gclear, wclear, stop);
+                                   bt, ws, tag, stop);
         } else {
             if (vec)
                 hipLaunchKernelGGL((prep_example_kernel<true, 8>), grd, blk, lds_bytes, stream, gs, bt,
-                                   ws, gclear, wclear, stop);
+                                   ws, tag, stop);
             else
                 hipLaunchKernelGGL((prep_example_kernel<false, 8>), grd, blk, lds_bytes, stream, gs,
-                                   bt, ws, gclear, wclear, stop);
+                                   bt, ws, tag, stop);
         }
         return hipGetLastError();
     }
     if (vec) {
         hipLaunchKernelGGL(prep_kernel<true>, dim3(1, bt.B), dim3(kPrepThreads), 0, stream, gs, bt,
-                           ws, gclear, wclear, stop);
+                           ws, tag, stop);
     } else {
         hipLaunchKernelGGL(prep_kernel<false>, dim3(bt.T, bt.B), dim3(kPrepThreads), 0, stream, gs,
-                           bt, ws, gclear, wclear, stop);
+                           bt, ws, tag, stop);
     }
     return hipGetLastError();
 }

@@ -23,6 +23,8 @@ EXPORTS = [
     "mg_forward_index", "mg_forward_index_static", "mg_forward_vector", "mg_forward_index_f64", "mg_forward_vector_f64",
     "mg_backward_index_f64", "mg_backward_vector_f64",
     "mg_backward_index", "mg_backward_vector", "mg_strerror", "mg_last_hip_error",
+    "mg_prepare", "mg_forward_index_prepared", "mg_forward_vector_prepared",
+    "mg_backward_index_prepared", "mg_backward_vector_prepared",
     "mg_set_option", "mg_time_next_kernel",
 ]
 
@@ -83,6 +85,16 @@ def lib(path: Optional[str] = None) -> ctypes.CDLL:
         L.mg_backward_index.argtypes = [vp, ci, ci, ci] + [vp] * 9 + [vp, sz, vp]
         L.mg_backward_vector.restype = ci
         L.mg_backward_vector.argtypes = [vp, ci, ci, ci] + [vp] * 10 + [vp, sz, vp]
+        L.mg_prepare.restype = ci
+        L.mg_prepare.argtypes = [vp, ci, ci, ci] + [vp] * 7 + [vp, sz, vp]
+        L.mg_forward_index_prepared.restype = ci
+        L.mg_forward_index_prepared.argtypes = [vp, ci, ci, ci, vp, vp, sz, vp]
+        L.mg_forward_vector_prepared.restype = ci
+        L.mg_forward_vector_prepared.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp, sz, vp]
+        L.mg_backward_index_prepared.restype = ci
+        L.mg_backward_index_prepared.argtypes = [vp, ci, ci, ci, vp, vp, vp, sz, vp]
+        L.mg_backward_vector_prepared.restype = ci
+        L.mg_backward_vector_prepared.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp, vp, vp, sz, vp]
         L.mg_strerror.restype = ctypes.c_char_p
         L.mg_strerror.argtypes = [ci]
         L.mg_last_hip_error.restype = ci
@@ -333,4 +345,81 @@ class GridMaker:
             ctypes.c_void_p(ws.data_ptr()), wsb, _stream())
         if rc != MG_OK:
             raise MolgridError(rc, "mg_backward_vector")
+        return grad_coords, grad_weights
+
+    # ---- tables once, calls many (mg_prepare + the *_prepared calls) ----
+
+    def mg_prepare(self, coords, types, radii, T, natoms=None, centers=None, quats=None,
+                   translations=None, workspace=None):
+        """Build the workspace's tables for these atoms and poses (``types=None``: the tables
+        of vector types) and return the workspace tensor the ``*_prepared`` calls then take."""
+        B, N, pc, pn, pce, pq, pt = self._common(coords, natoms, centers, quats, translations)
+        if workspace is None:
+            workspace = torch.empty(self.workspace_bytes(B, N, T), dtype=torch.uint8,
+                                    device=coords.device)
+        rshape = (T,) if (self.radius_type_indexed or types is None) else (B, N)
+        rc = lib().mg_prepare(
+            self._h, B, N, T, pc, _ptr(types, torch.int32, "types", (B, N)),
+            _ptr(radii, torch.float32, "radii", rshape), pn, pce, pq, pt,
+            ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+            _stream())
+        if rc != MG_OK:
+            raise MolgridError(rc, "mg_prepare")
+        return workspace
+
+    def mg_forward_index_prepared(self, B, N, T, workspace, out=None):
+        if out is None:
+            out = torch.empty(self.grid_shape(B, T), dtype=torch.float32, device=workspace.device)
+        rc = lib().mg_forward_index_prepared(
+            self._h, B, N, T, _ptr(out, torch.float32, "out", self.grid_shape(B, T)),
+            ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+            _stream())
+        if rc != MG_OK:
+            raise MolgridError(rc, "mg_forward_index_prepared")
+        return out
+
+    def mg_forward_vector_prepared(self, weights, radii, workspace, out=None):
+        B, N, T = weights.shape
+        if out is None:
+            out = torch.empty(self.grid_shape(B, T), dtype=torch.float32, device=weights.device)
+        rc = lib().mg_forward_vector_prepared(
+            self._h, B, N, T, _ptr(weights, torch.float32, "weights", (B, N, T)),
+            _ptr(radii, torch.float32, "radii", (T,)),
+            _ptr(out, torch.float32, "out", self.grid_shape(B, T)),
+            ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+            _stream())
+        if rc != MG_OK:
+            raise MolgridError(rc, "mg_forward_vector_prepared")
+        return out
+
+    def mg_backward_index_prepared(self, B, N, T, grad_out, workspace, grad_coords=None):
+        if grad_coords is None:
+            grad_coords = torch.empty((B, N, 3), dtype=torch.float32, device=grad_out.device)
+        rc = lib().mg_backward_index_prepared(
+            self._h, B, N, T,
+            _ptr(grad_out, torch.float32, "grad_out", self.grid_shape(B, T)),
+            _ptr(grad_coords, torch.float32, "grad_coords", (B, N, 3)),
+            ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+            _stream())
+        if rc != MG_OK:
+            raise MolgridError(rc, "mg_backward_index_prepared")
+        return grad_coords
+
+    def mg_backward_vector_prepared(self, weights, radii, grad_out, workspace, grad_coords=None,
+                                    grad_weights=None, want_coords=True, want_weights=True):
+        B, N, T = weights.shape
+        if grad_coords is None and want_coords:
+            grad_coords = torch.empty((B, N, 3), dtype=torch.float32, device=weights.device)
+        if grad_weights is None and want_weights:
+            grad_weights = torch.empty((B, N, T), dtype=torch.float32, device=weights.device)
+        rc = lib().mg_backward_vector_prepared(
+            self._h, B, N, T, _ptr(weights, torch.float32, "weights", (B, N, T)),
+            _ptr(radii, torch.float32, "radii", (T,)),
+            _ptr(grad_out, torch.float32, "grad_out", self.grid_shape(B, T)),
+            _ptr(grad_coords, torch.float32, "grad_coords", (B, N, 3)),
+            _ptr(grad_weights, torch.float32, "grad_weights", (B, N, T)),
+            ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+            _stream())
+        if rc != MG_OK:
+            raise MolgridError(rc, "mg_backward_vector_prepared")
         return grad_coords, grad_weights

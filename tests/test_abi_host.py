@@ -80,7 +80,9 @@ def test_calls_reject_bad_arguments_before_any_launch(L):
     assert rc == 0
     n = sz()
     assert L.mg_workspace_bytes(h, 50, 2040, 28, ctypes.byref(n)) == 0
-    assert 50 * 2040 * 20 <= n.value <= 50 * 2040 * 20 + 50 * 28 * (16 + 48 * 8) + 50 * 64 + 64
+    # records 16 B + atom index 4 B + channel 4 B + liveness 1 B per atom; group table, plane spans and channel
+    # order per (example, type); pose and centre per example; the tag
+    assert 50 * 2040 * 25 <= n.value <= 50 * 2040 * 25 + 50 * 28 * (16 + 48 * 8 + 4) + 50 * 64 + 128
     assert L.mg_workspace_bytes(h, 0, 2040, 28, ctypes.byref(n)) == -2
     # a subgrid decomposition: S^3 virtual examples per example, plus the gradient staging
     L.mg_gridmaker_create_subgrids.argtypes = [ctypes.POINTER(vp), ctypes.c_float, ctypes.c_float,

@@ -1,0 +1,116 @@
+"""mg_prepare + the *_prepared calls: the tables are built once and forward and backward run on
+them without the prep kernel.  The results equal those of the ordinary calls bit for bit (the
+same kernels read the same tables) and meet the oracle's bar; a workspace prepared for another
+shape leaves the outputs untouched."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1912_04822_amd import workloads
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from test_gpu_parity import GRID_TOL, GRAD_RTOL, dev, mg  # noqa: E402,F401
+
+
+def bits(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+@pytest.mark.parametrize("case", ["protein", "ragged", "subgrids"])
+def test_index_types_forward_then_backward_on_one_workspace(mg, case):
+    S = 1
+    if case == "protein":
+        w, nat = workloads.protein_ligand(B=4, with_grad=True), None
+    elif case == "ragged":
+        w = workloads.ragged_small()
+        nat = w.extra["natoms"]
+    else:
+        w, nat, S = workloads.ragged_small(B=2, N=60, T=3, D=8), None, 2
+    gm = mg.GridMaker(w.resolution, w.dimension, radius_type_indexed=True, subgrids_per_side=S)
+    co, ty, ra = dev(w.coords), dev(w.types), dev(w.radii)
+    kw = dict(natoms=dev(nat), centers=dev(w.centers), quats=dev(w.quats),
+              translations=dev(w.translations))
+    G = torch.randn(gm.grid_shape(w.B, w.T), device="cuda", generator=torch.Generator("cuda").manual_seed(3))
+    out = gm.mg_forward_index(co, ty, ra, w.T, **kw)
+    grad = gm.mg_backward_index(co, ty, ra, w.T, G, **kw)
+    ws = gm.mg_prepare(co, ty, ra, w.T, **kw)
+    out_p = torch.full_like(out, float("nan"))
+    gm.mg_forward_index_prepared(w.B, w.N, w.T, ws, out=out_p)
+    grad_p = torch.full_like(grad, float("nan"))
+    gm.mg_backward_index_prepared(w.B, w.N, w.T, G, ws, grad_coords=grad_p)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(out), bits(out_p))
+    assert np.array_equal(bits(grad), bits(grad_p))
+    if S == 1:
+        okw = dict(natoms=nat, centers=w.centers, quats=w.quats, translations=w.translations)
+        ref = oracle.forward_index(w.coords, w.types, w.radii, w.T, w.resolution, w.dimension, **okw)
+        assert np.abs(out_p.cpu().numpy() - ref).max() <= GRID_TOL
+        rg = oracle.backward_index(w.coords, w.types, w.radii, w.T, w.resolution, w.dimension,
+                                   G.cpu().numpy(), **okw)
+        got = grad_p.cpu().numpy()
+        for b in range(w.B):
+            assert np.abs(got[b] - rg[b]).max() <= GRAD_RTOL * max(np.abs(rg[b]).max(), 1e-30)
+
+
+def test_binary_forward_prepared_is_bit_exact(mg):
+    w = workloads.protein_ligand(B=3)
+    gm = mg.GridMaker(w.resolution, w.dimension, binary=True, radius_type_indexed=True)
+    kw = dict(centers=dev(w.centers), quats=dev(w.quats), translations=dev(w.translations))
+    ws = gm.mg_prepare(dev(w.coords), dev(w.types), dev(w.radii), w.T, **kw)
+    out = gm.mg_forward_index_prepared(w.B, w.N, w.T, ws)
+    torch.cuda.synchronize()
+    ref = oracle.forward_binary(w.coords, w.radii, w.T, w.resolution, w.dimension, types=w.types,
+                                centers=w.centers, quats=w.quats, translations=w.translations)
+    assert np.array_equal(bits(out), ref.view(np.uint32))
+
+
+def test_vector_types_forward_then_backward_on_one_workspace(mg):
+    w = workloads.protein_ligand(B=2, with_weights=True, with_grad=True)
+    gm = mg.GridMaker(w.resolution, w.dimension, radius_type_indexed=True)
+    co, we, ra, G = dev(w.coords), dev(w.weights), dev(w.radii), dev(w.grad_out)
+    kw = dict(centers=dev(w.centers), quats=dev(w.quats), translations=dev(w.translations))
+    out = gm.mg_forward_vector(co, we, ra, **kw)
+    gc, gw = gm.mg_backward_vector(co, we, ra, G, **kw)
+    ws = gm.mg_prepare(co, None, ra, w.T, **kw)
+    out_p = gm.mg_forward_vector_prepared(we, ra, ws)
+    gc_p, gw_p = gm.mg_backward_vector_prepared(we, ra, G, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(out), bits(out_p))
+    assert np.array_equal(bits(gc), bits(gc_p))
+    assert np.array_equal(bits(gw), bits(gw_p))
+    okw = dict(centers=w.centers, quats=w.quats, translations=w.translations)
+    ref = oracle.forward_vector(w.coords, w.weights, w.radii, w.resolution, w.dimension, **okw)
+    assert np.abs(out_p.cpu().numpy() - ref).max() <= GRID_TOL
+    rc, rw = oracle.backward_vector(w.coords, w.weights, w.radii, w.resolution, w.dimension,
+                                    w.grad_out, **okw)
+    assert np.abs(gc_p.cpu().numpy() - rc).max() <= GRAD_RTOL * np.abs(rc).max()
+    assert np.abs(gw_p.cpu().numpy() - rw).max() <= GRAD_RTOL * np.abs(rw).max()
+
+
+def test_tables_of_another_shape_leave_the_outputs_untouched(mg):
+    """The kernels of a *_prepared call compare the tag the tables carry with their own shape
+    and return without writing when it differs (here: tables of B = 3 used with B = 2, tables
+    of index types used for vector types, and a workspace nothing was prepared in)."""
+    w = workloads.protein_ligand(B=3, with_weights=True, with_grad=True)
+    gm = mg.GridMaker(w.resolution, w.dimension, radius_type_indexed=True)
+    co, ty, ra, we = dev(w.coords), dev(w.types), dev(w.radii), dev(w.weights)
+    kw = dict(centers=dev(w.centers), quats=dev(w.quats), translations=dev(w.translations))
+    ws = gm.mg_prepare(co, ty, ra, w.T, **kw)
+    out = torch.full(gm.grid_shape(2, w.T), 7.0, device="cuda")
+    gm.mg_forward_index_prepared(2, w.N, w.T, ws, out=out)             # B differs
+    outv = torch.full(gm.grid_shape(w.B, w.T), 7.0, device="cuda")
+    gm.mg_forward_vector_prepared(we, ra, ws, out=outv)                # kind of types differs
+    g = torch.full((2, w.N, 3), 7.0, device="cuda")
+    gm.mg_backward_index_prepared(2, w.N, w.T, dev(w.grad_out[:2]), ws, grad_coords=g)
+    blank = torch.zeros(gm.workspace_bytes(w.B, w.N, w.T), dtype=torch.uint8, device="cuda")
+    out3 = torch.full(gm.grid_shape(w.B, w.T), 7.0, device="cuda")
+    gm.mg_forward_index_prepared(w.B, w.N, w.T, blank, out=out3)       # nothing prepared (tag 0)
+    torch.cuda.synchronize()
+    for t in (out, outv, g, out3):
+        assert float(t.min()) == 7.0 and float(t.max()) == 7.0
+    good = gm.mg_forward_index_prepared(w.B, w.N, w.T, ws)             # the right shape still works
+    ref = gm.mg_forward_index(co, ty, ra, w.T, **kw)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits(good), bits(ref))

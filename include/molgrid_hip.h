@@ -312,9 +312,10 @@ int mg_last_hip_error(void);
  *                     take at least 2; vector types at most 2)
  *   "xcd_run"         0 or a power of two (default 0): runs of this many
  *                     consecutive tiles go to one XCD
- *   "keep_alive"      0 or 1 (default 1): every forward wavefront (index types,
- *                     float grid) also reads 1 KB of the workspace tables so that
- *                     they stay cached while the grid is streamed out
+ *   "keep_alive"      0, 1, 256, 512 or 1024 (default 1 = 256): every forward
+ *                     wavefront (index types, float grid) also reads that many
+ *                     bytes of the workspace tables so that they stay cached while
+ *                     the grid is streamed out
  *   "single_launch"   0 or 1 (default 1): index types into a float grid with at most
  *                     256 atoms per example and 2048 in the batch run as ONE kernel
  *                     launch (every tile's wavefront transforms, culls and filters the

@@ -3,7 +3,10 @@ in place on a Torch tensor, and ``backward`` turns a gradient on the grid into a
 so coordinates -- and, with vector types, type weights -- can be optimised through the grid).
 
 No arithmetic of the method happens here: ``forward`` calls ``mg_forward_*`` and ``backward``
-calls ``mg_backward_*``; this module only tells autograd which call belongs to which.
+calls ``mg_backward_*``; this module only tells autograd which call belongs to which.  When a
+gradient will be asked for, forward builds the tables once (``mg_prepare``) in a workspace of its
+own and both passes run on them (the ``*_prepared`` calls): the backward pass then starts without
+a prep kernel.
 A binary GridMaker has no gradient (the indicator is piecewise constant); asking for one raises.
 """
 from __future__ import annotations
@@ -18,8 +21,13 @@ from . import molgrid
 class _IndexGrid(torch.autograd.Function):
     @staticmethod
     def forward(ctx, coords, gm, types, radii, T, natoms, centers, quats, translations):
-        ctx.gm, ctx.T = gm, T
+        ctx.gm, ctx.T, ctx.ws = gm, T, None
         ctx.save_for_backward(coords, types, radii, natoms, centers, quats, translations)
+        if ctx.needs_input_grad[0] and not gm.binary:
+            B, N, _ = coords.shape
+            ctx.ws = gm.mg_prepare(coords.detach(), types, radii, T, natoms=natoms, centers=centers,
+                                   quats=quats, translations=translations)
+            return gm.mg_forward_index_prepared(B, N, T, ctx.ws)
         return gm.mg_forward_index(coords.detach(), types, radii, T, natoms=natoms, centers=centers,
                                    quats=quats, translations=translations)
 
@@ -28,6 +36,10 @@ class _IndexGrid(torch.autograd.Function):
         if ctx.gm.binary:
             raise RuntimeError("a binary GridMaker has no gradient")
         coords, types, radii, natoms, centers, quats, translations = ctx.saved_tensors
+        if ctx.ws is not None and grad_out.dtype == torch.float32:
+            B, N, _ = coords.shape
+            g = ctx.gm.mg_backward_index_prepared(B, N, ctx.T, grad_out.contiguous(), ctx.ws)
+            return (g,) + (None,) * 8
         g = ctx.gm.mg_backward_index(coords.detach(), types, radii, ctx.T, grad_out.contiguous(),
                                      natoms=natoms, centers=centers, quats=quats,
                                      translations=translations)
@@ -37,8 +49,12 @@ class _IndexGrid(torch.autograd.Function):
 class _VectorGrid(torch.autograd.Function):
     @staticmethod
     def forward(ctx, coords, weights, gm, radii, natoms, centers, quats, translations):
-        ctx.gm = gm
+        ctx.gm, ctx.ws = gm, None
         ctx.save_for_backward(coords, weights, radii, natoms, centers, quats, translations)
+        if (ctx.needs_input_grad[0] or ctx.needs_input_grad[1]) and not gm.binary:
+            ctx.ws = gm.mg_prepare(coords.detach(), None, radii, weights.shape[2], natoms=natoms,
+                                   centers=centers, quats=quats, translations=translations)
+            return gm.mg_forward_vector_prepared(weights.detach(), radii, ctx.ws)
         return gm.mg_forward_vector(coords.detach(), weights.detach(), radii, natoms=natoms,
                                     centers=centers, quats=quats, translations=translations)
 
@@ -48,6 +64,11 @@ class _VectorGrid(torch.autograd.Function):
             raise RuntimeError("a binary GridMaker has no gradient")
         coords, weights, radii, natoms, centers, quats, translations = ctx.saved_tensors
         want_c, want_w = ctx.needs_input_grad[0], ctx.needs_input_grad[1]
+        if ctx.ws is not None and grad_out.dtype == torch.float32:
+            gc, gw = ctx.gm.mg_backward_vector_prepared(
+                weights.detach(), radii, grad_out.contiguous(), ctx.ws, want_coords=True,
+                want_weights=bool(want_w))
+            return (gc if want_c else None, gw if want_w else None) + (None,) * 6
         gc, gw = ctx.gm.mg_backward_vector(
             coords.detach(), weights.detach(), radii, grad_out.contiguous(), natoms=natoms,
             centers=centers, quats=quats, translations=translations,

@@ -70,6 +70,7 @@ namespace mg {
 namespace {
 
 constexpr int kTaskCap = 256;                   // (atom, row) tasks staged per round
+constexpr unsigned kKeepAliveBytes = 256;       // what every wavefront re-reads of the tables by default
 constexpr float kFixedOne = 16777216.0f;        // 2^24
 constexpr float kFixedLimit = 120.0f;           // largest |sum| trusted to fixed point
 
@@ -106,7 +107,8 @@ struct FwdParams {
     int xcd_shift;                  // >= 0: runs of 2^xcd_shift consecutive tiles go to one XCD
     unsigned n_remap;               // workgroups covered by that mapping (the rest map 1:1)
     int debug;
-    unsigned ka_chunks, ka_last;    // keep-alive reads: 1 KB chunks of the tables (0: none), byte offset of the last one
+    unsigned ka_chunks, ka_last;    // keep-alive reads: chunks of the tables (0: none), byte offset of the last one
+    unsigned ka_shift;              // log2 of the chunk size in bytes (8..10)
     float sk;           // sqrt(k), k = 2 log2(e)
     float inv_sk;
     float g2k, c2k;     // g^2 k, c^2 k
@@ -763,7 +765,7 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
         : "=s"(zero)
         : "s"((unsigned long long)p.range), "s"((unsigned long long)p.rec),
           "s"((unsigned long long)p.gcen), "s"((unsigned long long)p.out), "s"(p.tiles_magic),
-          "s"(p.t_magic), "s"(p.div_magic), "s"(p.tiles), "s"(p.pos_major), "s"(p.ka_chunks), "s"(p.ka_last), "s"(p.xcd_shift), "s"(p.n_remap), "s"(D),
+          "s"(p.t_magic), "s"(p.div_magic), "s"(p.tiles), "s"(p.pos_major), "s"(p.ka_chunks), "s"(p.ka_last), "s"(p.ka_shift), "s"(p.xcd_shift), "s"(p.n_remap), "s"(D),
           "s"(T), "s"(N), "s"(p.debug), "s"(gs.half));
     if (p.expect_tag != 0u && *p.tag != p.expect_tag) return;      // not the tables this call expects
     unsigned u = blockIdx.x + zero;
@@ -780,8 +782,9 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     float4 ka = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     if (p.ka_chunks) {
         const unsigned c = __umulhi((blockIdx.x + zero) * 2654435761u, p.ka_chunks);
-        const unsigned off = min(c << 10, p.ka_last) + ((threadIdx.x & 63u) << 4);
-        ka = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(p.rec) + off);
+        const unsigned off = min(c << p.ka_shift, p.ka_last) + ((threadIdx.x & 63u) << 4);
+        if ((threadIdx.x & 63u) < (1u << (p.ka_shift - 4)))     // the chunk's lanes, 16 bytes each
+            ka = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(p.rec) + off);
     }
     const unsigned uq = div_u32(u, p.tiles_magic), ur = u - uq * p.tiles;
     const unsigned chan = p.pos_major ? ur : uq;
@@ -1231,6 +1234,7 @@ static hipError_t launch_forward_vector(const GridSpec &gs, const Batch &bt, con
     p.debug = 0;
     p.ka_chunks = 0;
     p.ka_last = 0;
+    p.ka_shift = 8;
     const double k = 2.8853900817779268;        // 2 / ln 2
     p.sk = (float)std::sqrt(k);
     p.inv_sk = (float)(1.0 / std::sqrt(k));
@@ -1353,10 +1357,13 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
         const size_t bytes = (size_t)((const char *)(ws.gcen + (size_t)bt.B * 4) - (const char *)ws.rec);
         p.ka_chunks = 0;
         p.ka_last = 0;
+        // keep_alive: 0 = none, 1 = the default chunk, else the chunk in bytes (256, 512, 1024)
+        const unsigned chunk = keep_alive == 1 ? kKeepAliveBytes : (unsigned)keep_alive;
+        p.ka_shift = chunk == 1024u ? 10u : (chunk == 512u ? 9u : 8u);
         // (vector types are bound by arithmetic and a grid of doubles by its own stores: measured no gain)
         if (keep_alive && !bt.vec && !out_is_double && bytes >= 1024 && bytes < (1ull << 31)) {
-            p.ka_chunks = (unsigned)((bytes + 1023) >> 10);
-            p.ka_last = (unsigned)(bytes - 1024);
+            p.ka_chunks = (unsigned)((bytes + chunk - 1) >> p.ka_shift);
+            p.ka_last = (unsigned)(bytes - chunk);
         }
     }
     const double k = 2.8853900817779268;        // 2 / ln 2

@@ -105,19 +105,26 @@ def stored(key):
     return None, None
 
 
-def settle(torch, fn, min_gpu_ms=SETTLE_GPU_MS, batch=20):
-    """Repeat fn until at least min_gpu_ms of GPU time (events on the launch stream) has passed."""
+def settle(torch, fn, min_gpu_ms=SETTLE_GPU_MS, batch=20, max_gpu_ms=250.0):
+    """Repeat fn until at least min_gpu_ms of GPU time (events on the launch stream) has passed
+    AND two batches in a row took within 1 % of the batch before them (the clocks have stopped
+    moving), or max_gpu_ms has passed."""
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    total, calls = 0.0, 0
-    while total < min_gpu_ms and calls < 200000:
+    total, calls, prev, steady = 0.0, 0, None, 0
+    while calls < 200000:
         e0.record()
         for _ in range(batch):
             fn()
         e1.record()
         e1.synchronize()
-        total += e0.elapsed_time(e1)
+        t = e0.elapsed_time(e1)
+        total += t
         calls += batch
-    return {"ms": total, "calls": calls}
+        steady = steady + 1 if (prev is not None and abs(t - prev) <= 0.01 * prev) else 0
+        prev = t
+        if (total >= min_gpu_ms and steady >= 2) or total >= max(max_gpu_ms, min_gpu_ms):
+            break
+    return {"ms": total, "calls": calls, "last_batch_ms_per_call": prev / batch}
 
 
 def time_call(torch, molgrid, fn, steps, warmup, timed_kernel=True):
@@ -185,6 +192,7 @@ def main():
                     help="load the measurement build (python -m paper_1912_04822_amd.build --timing-aids)")
     ap.add_argument("--debug", type=int, default=None, help="timing aid (measurement build; wrong output)")
     ap.add_argument("--prep-stop", type=int, default=None, help="timing aid (measurement build; wrong output)")
+    ap.add_argument("--lib", default=None, help="path of another build of libmolgrid_hip.so to load")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain device copy of known size (for scaling rocprofv3 counters)")
     args = ap.parse_args()
@@ -212,7 +220,7 @@ def main():
     from paper_1912_04822_amd import build as hip_build
     from paper_1912_04822_amd import molgrid, workloads
     aids = args.timing_aids or args.debug is not None or args.prep_stop is not None
-    molgrid.lib(hip_build.LIB_TIMING if aids else None)     # raises if the library is missing: no fallback
+    molgrid.lib(args.lib or (hip_build.LIB_TIMING if aids else None))   # raises if the library is missing: no fallback
     for key, val in (("tile_floats", args.tile_floats), ("xcd_run", args.xcd_run),
                      ("tile_order", args.tile_order), ("keep_alive", args.keep_alive),
                      ("lds_floor", args.lds_floor), ("waves_per_tile", args.waves_per_tile),
@@ -267,8 +275,10 @@ def main():
         "config": {"workload": "protein-ligand forward (configs[1]): B=50, N=2040 atoms, T=28, "
                                "48^3 points @0.5A, random rotation + <=2A translation per example",
                    "out_bytes": w.out_bytes},
-        "settle": dict(settled, what="the same forward call repeated until %.0f ms of GPU time had "
-                                     "passed, before the counted warm-up (untimed)" % args.settle_ms),
+        "settle": dict(settled, what="the same forward call repeated, untimed, before the counted "
+                                     "warm-up: at least %.0f ms of GPU time and until two batches of "
+                                     "20 calls in a row took within 1 %% of the batch before them "
+                                     "(at most 250 ms)" % args.settle_ms),
         "roofline": roof,
     }
 
@@ -281,7 +291,7 @@ def main():
         n_slow = max(10, min(args.steps, 30))       # calls of ~1 ms
 
         def row(fn, steps, settle_ms=10.0, **kw):
-            settle(torch, fn, settle_ms, batch=5)
+            settle(torch, fn, settle_ms, batch=5, max_gpu_ms=60.0)
             return time_call(torch, molgrid, fn, steps, 3, **kw)
 
         # for scale: the runtime's memset of the same output buffer (no atoms, no arithmetic)

@@ -28,6 +28,7 @@
 // wavefront per group (example b, type t; vector types: example b) that scans
 // the example's types for its own atoms.
 #include "mg_common.h"
+#include "mg_wave.h"
 #include "mg_xform.h"
 
 namespace mg {
@@ -59,20 +60,13 @@ __global__ __launch_bounds__(256) void transform_kernel(int B, int N, const floa
 }
 
 // Exclusive prefix sum of `v` over the 64 lanes of the wavefront; *total gets the sum.
+// (DPP row shifts and broadcasts: no trips through LDS.)
 __device__ inline int wave_exclusive_scan(int v, int *total)
 {
-    const int lane = threadIdx.x & 63;
-    int incl = v;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int up = __shfl_up(incl, d, 64);
-        if (lane >= d) incl += up;
-    }
+    const int incl = wave_inclusive_scan(v);
     *total = __builtin_amdgcn_readlane(incl, 63);
     return incl - v;
 }
-
-__device__ inline void lds_sync() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); }
 
 struct Culler {
     float org[3];       // grid origin (center - half)
@@ -201,6 +195,10 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
             if (!VECTOR && !gs.radius_type_indexed) my_r[u] = rad_b[a];
         }
     }
+    // (the radius table too: this thread's entry now, into LDS once the loads have landed)
+    const bool rad_table = !VECTOR && gs.radius_type_indexed;
+    float my_rad = 0.0f;
+    if (rad_table && tid < Tg) my_rad = bt.radii[tid];
     int n = N;
     if (bt.natoms) {
         n = bt.natoms[bs];
@@ -227,8 +225,10 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     if (tid < 3) ws.gcen[b * 4 + tid] = gc[tid];
     for (int m = 0; m < 3; ++m) cu.org[m] = gc[m] - gs.half;
 
-    if (!VECTOR && gs.radius_type_indexed)
-        for (int k = tid; k < Tg; k += kExThreads) s_rad[k] = bt.radii[k];
+    if (rad_table) {
+        if (tid < Tg) s_rad[tid] = my_rad;
+        for (int k = tid + kExThreads; k < Tg; k += kExThreads) s_rad[k] = bt.radii[k];
+    }
     if (MG_STOP_IS(stop, 2)) return;
     for (int k = tid; k < K; k += kExThreads) s_cnt[k] = 0;
     for (int k = tid; k < Tg; k += kExThreads) s_rmax[k] = 0;

@@ -433,6 +433,18 @@ def main():
             gmt.mg_forward_index(ct, tt, rt, wt.T, out=outt, workspace=wst)
 
         r = row(tiny_call, 1000, settle_ms=5.0, timed_kernel=False)
+        # the same call straight through the C ABI with its arguments marshalled once: what the
+        # library and the HIP runtime cost per call, without the Python binding's checks
+        L = molgrid.lib()
+        vp = ctypes.c_void_p
+        raw_args = (gmt._h, wt.B, wt.N, wt.T, vp(ct.data_ptr()), vp(tt.data_ptr()), vp(rt.data_ptr()),
+                    None, None, None, None, vp(outt.data_ptr()), vp(wst.data_ptr()), wst.numel(),
+                    vp(torch.cuda.current_stream().cuda_stream))
+
+        def tiny_raw():
+            L.mg_forward_index(*raw_args)
+
+        r_raw = row(tiny_raw, 2000, settle_ms=2.0, timed_kernel=False)
         molgrid.set_option("single_launch", 0)      # for comparison: prep kernel + forward kernel
         r2 = row(tiny_call, 1000, settle_ms=2.0, timed_kernel=False)
         molgrid.set_option("single_launch", 1)
@@ -456,6 +468,7 @@ def main():
         rows["forward_tiny"] = {
             "latency_us_eager": r["ms_per_call"] * 1e3, "latency_us_graph": ms_graph * 1e3,
             "latency_us_eager_two_launches": r2["ms_per_call"] * 1e3,
+            "latency_us_c_abi": r_raw["ms_per_call"] * 1e3,
             "roofline": None,
             "workload": "configs[0]: B=1, N=100, T=4, 24^3 @0.5A (221 KB out): calls back to back, "
                         "one kernel launch per call (every tile looks at the 100 atoms itself); "

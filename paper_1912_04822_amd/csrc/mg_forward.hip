@@ -545,7 +545,6 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
         return;
     }
     Xform X;
-    if (FUSED) load_xform(X, b, p.raw.centers, p.raw.quats, p.raw.translations);
 
     // How the wavefronts share the work: the `nsplit` wavefronts of a set take the atoms of
     // the span in turn (atom e goes to lane e / nsplit of member e % nsplit, round after
@@ -562,34 +561,47 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
     // vector types: the weights of this channel, one per atom of the source example
     const float *wcol = VECTOR ? p.weights + (size_t)source_example(p.subgrids, b) * N * T + t
                                : nullptr;
+    // FUSED: an atom's type, coordinates and radius are requested together (one trip to memory),
+    // whatever the type turns out to be; finish_raw transforms, culls and filters by type with
+    // the prep kernel's arithmetic and tests.
+    struct RawAtom {
+        int te;
+        float cc[3], rad;
+    };
+    auto fetch_raw = [&](int base) {
+        RawAtom ra;
+        const int ec = min(base + lane * nsplit + sub, count - 1);      // count >= 1 here
+        ra.te = p.raw.types[(size_t)b * N + ec];
+        const float *c3 = p.raw.coords + ((size_t)b * N + ec) * 3;
+        ra.cc[0] = c3[0]; ra.cc[1] = c3[1]; ra.cc[2] = c3[2];
+        ra.rad = p.raw.radii[gs.radius_type_indexed ? (size_t)t : (size_t)b * N + ec];
+        return ra;
+    };
+    auto finish_raw = [&](const RawAtom &ra, int e) {
+        Atom at;
+        at.a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        at.w = 1.0f;
+        if (e < count && ra.te == t) {
+            float pp[3];
+            apply_xform(X, ra.cc, pp);
+            const float r = gs.radius_scale * ra.rad;
+            const float reach = BINARY ? r : r * gs.c;
+            const float org[3] = {ox, cx.oy, cx.oz};
+            const float span = (float)(D - 1) * gs.res, pad = 1.0e-3f * gs.res;
+            bool live = (r > 0.0f) && (reach < 1.0e30f);
+            for (int k = 0; k < 3; ++k)     // also false for NaN / infinite coordinates
+                live = live && (pp[k] >= org[k] - reach - pad) && (pp[k] <= org[k] + span + reach + pad);
+            if (live) at.a = make_float4(pp[0], pp[1], pp[2], r);
+        }
+        at.valid = at.a.w > 0.0f;
+        return at;
+    };
     auto load_atom = [&](int base) {
         const int e = base + lane * nsplit + sub;
         Atom at;
         at.a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         at.w = 1.0f;
-        if (FUSED) {
-            // type, coordinates and radius are requested together (one trip to memory), whatever
-            // the type turns out to be
-            const int ec = min(e, count - 1);           // count >= 1 here
-            const int te = p.raw.types[(size_t)b * N + ec];
-            const float *c3 = p.raw.coords + ((size_t)b * N + ec) * 3;
-            const float cc[3] = {c3[0], c3[1], c3[2]};
-            const float rad = p.raw.radii[gs.radius_type_indexed ? (size_t)t : (size_t)b * N + ec];
-            if (e < count && te == t) {
-                float pp[3];
-                apply_xform(X, cc, pp);
-                const float r = gs.radius_scale * rad;
-                const float reach = BINARY ? r : r * gs.c;
-                const float org[3] = {ox, cx.oy, cx.oz};
-                const float span = (float)(D - 1) * gs.res, pad = 1.0e-3f * gs.res;
-                bool live = (r > 0.0f) && (reach < 1.0e30f);
-                for (int k = 0; k < 3; ++k)     // also false for NaN / infinite coordinates
-                    live = live && (pp[k] >= org[k] - reach - pad) && (pp[k] <= org[k] + span + reach + pad);
-                if (live) at.a = make_float4(pp[0], pp[1], pp[2], r);
-            }
-            at.valid = at.a.w > 0.0f;
-            return at;
-        }
+        if (FUSED) return finish_raw(fetch_raw(base), e);
         if (e < count) {
             at.a = rec[e];
             if (VECTOR && at.a.w > 0.0f) at.w = wcol[(size_t)idx[e] * T];
@@ -610,7 +622,15 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
     };
 
     // the loads of the first round are under way; clear the tile meanwhile
-    Atom at0 = load_atom(0);
+    // (FUSED: the first atoms are requested before the pose is waited for and worked out)
+    Atom at0;
+    if (FUSED) {
+        const RawAtom ra0 = fetch_raw(0);
+        load_xform(X, b, p.raw.centers, p.raw.quats, p.raw.translations);
+        at0 = finish_raw(ra0, lane * nsplit + sub);
+    } else {
+        at0 = load_atom(0);
+    }
     {
         const float4 z4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);     // same bits as integer zeros
 #pragma unroll

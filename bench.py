@@ -354,12 +354,37 @@ def main():
         # grid of the same inputs -- a density is positive exactly there), 4 bytes each; the bytes
         # the 128-byte lines of those voxels occupy (FETCH_SIZE of the profile) give the practical
         # bound, streaming the whole gradient grid once the trivial one
+        def kernel_after_forward(fn, n):
+            """The backward kernel's duration when a forward call (619 MB of stores) ran just
+            before it, as in a training step: the gradient grid then comes from HBM, while in a
+            back-to-back loop of backward calls the lines it touches (270 MB of the 619 MB) largely
+            stay in the 256 MB memory-side cache from one call to the next."""
+            ev = Events(n)
+            for i in range(3 + n):
+                step()
+                if i >= 3:
+                    a, b = ev.pairs[i - 3]
+                    molgrid.mg_time_next_kernel(a.value, b.value)
+                fn()
+            torch.cuda.synchronize()
+            k = ev.elapsed_ms()
+            ev.close()
+            return float(np.mean(k)), float(np.min(k))
+
         def bwd_row(name, fn, steps, distinct, fetch_key, valu_key):
             r = row(fn, steps)
-            k = r["kernel_ms_avg"]
+            warm = r["kernel_ms_avg"]
+            k, kmin = kernel_after_forward(fn, min(steps, 30))
+            r["kernel_ms_after_forward"] = k
+            r["kernel_ms_after_forward_min"] = kmin
+            r["kernel_ms_avg_is"] = ("back-to-back backward calls: the gradient grid's lines stay "
+                                     "largely in the memory-side cache between calls")
             r["atoms_per_s"] = w.B * w.N / (r["ms_per_call"] * 1e-3)
             r["roofline"] = hbm_roofline(4 * distinct, k, "distinct in-cutoff voxels of the upstream "
-                                                          "gradient x 4 B (HBM read)")
+                                                          "gradient x 4 B (HBM read); kernel timed "
+                                                          "right after a forward call, gradient grid "
+                                                          "from HBM")
+            r["roofline"]["grid_in_cache_frac"] = 4 * distinct / (warm * 1e-3) / 1e9 / HBM_PEAK_GBS
             fetch, src = stored(fetch_key)
             if fetch is not None:
                 r["roofline"]["line_bound"] = {

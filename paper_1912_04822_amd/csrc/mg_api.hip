@@ -555,7 +555,9 @@ int mg_set_option(const char *key, int value)
         return MG_OK;
     }
     if (std::strcmp(key, "keep_alive") == 0) {
-        if (value != 0 && value != 1 && value != 256 && value != 512 && value != 1024) return MG_EPARAM;
+        if (value != 0 && value != 1 && value != 64 && value != 128 && value != 256 && value != 512 &&
+            value != 1024)
+            return MG_EPARAM;
         g_keep_alive = value;
         return MG_OK;
     }

@@ -274,10 +274,11 @@ __device__ inline void reduce_channel(const BwdParams &p, const GT *G, int t, si
         asm volatile("" : "+v"(t));     // nothing above waits for t
         const GT *Gc = G + (size_t)t * D3;
         // Round k works on slots 64k .. 64k+63, one per lane.  (Issuing the reads of two or three
-        // rounds before the arithmetic of the first was measured slower, 73 against 68 us in the same
-        // session: the kernel fetches every 128-byte line of the gradient grid that holds an
-        // in-cutoff voxel exactly once -- 270 MB on the 48^3 batch -- and runs at the rate those
-        // scattered lines arrive, whatever the wavefronts have in flight.)
+        // rounds before the arithmetic of the first was measured slower -- 69 against 62 us with
+        // the gradient grid partly in the memory-side cache, 102 against 100 us with a grid that
+        // has to come from HBM: the kernel fetches every 128-byte line of the gradient grid that
+        // holds an in-cutoff voxel exactly once, 270 MB on the 48^3 batch, and runs at the rate
+        // those scattered lines arrive, whatever the wavefronts have in flight.)
         int carry = 0;
         for (int base = 0; base < total; base += 64) {
             const int sidx = base + lane;

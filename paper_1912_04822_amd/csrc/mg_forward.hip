@@ -108,7 +108,7 @@ struct FwdParams {
     unsigned n_remap;               // workgroups covered by that mapping (the rest map 1:1)
     int debug;
     unsigned ka_chunks, ka_last;    // keep-alive reads: chunks of the tables (0: none), byte offset of the last one
-    unsigned ka_shift;              // log2 of the chunk size in bytes (8..10)
+    unsigned ka_shift;              // log2 of the chunk size in bytes (6..10)
     float sk;           // sqrt(k), k = 2 log2(e)
     float inv_sk;
     float g2k, c2k;     // g^2 k, c^2 k
@@ -1379,7 +1379,7 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
         p.ka_last = 0;
         // keep_alive: 0 = none, 1 = the default chunk, else the chunk in bytes (256, 512, 1024)
         const unsigned chunk = keep_alive == 1 ? kKeepAliveBytes : (unsigned)keep_alive;
-        p.ka_shift = chunk == 1024u ? 10u : (chunk == 512u ? 9u : 8u);
+        p.ka_shift = chunk == 1024u ? 10u : (chunk == 512u ? 9u : (chunk == 128u ? 7u : (chunk == 64u ? 6u : 8u)));
         // (vector types are bound by arithmetic and a grid of doubles by its own stores: measured no gain)
         if (keep_alive && !bt.vec && !out_is_double && bytes >= 1024 && bytes < (1ull << 31)) {
             p.ka_chunks = (unsigned)((bytes + chunk - 1) >> p.ka_shift);

@@ -188,6 +188,7 @@ def main():
     ap.add_argument("--xcd-run", type=int, default=None, help="forward kernel launch knob")
     ap.add_argument("--tile-order", type=int, default=None, help="forward kernel launch knob")
     ap.add_argument("--keep-alive", type=int, default=None, help="forward kernel launch knob")
+    ap.add_argument("--keep-alive-stride", type=int, default=None, help="forward kernel launch knob")
     ap.add_argument("--timing-aids", action="store_true",
                     help="load the measurement build (python -m paper_1912_04822_amd.build --timing-aids)")
     ap.add_argument("--debug", type=int, default=None, help="timing aid (measurement build; wrong output)")
@@ -223,7 +224,7 @@ def main():
     molgrid.lib(args.lib or (hip_build.LIB_TIMING if aids else None))   # raises if the library is missing: no fallback
     for key, val in (("tile_floats", args.tile_floats), ("xcd_run", args.xcd_run),
                      ("tile_order", args.tile_order), ("keep_alive", args.keep_alive),
-                     ("lds_floor", args.lds_floor), ("waves_per_tile", args.waves_per_tile),
+                     ("lds_floor", args.lds_floor), ("keep_alive_stride", args.keep_alive_stride), ("waves_per_tile", args.waves_per_tile),
                      ("debug", args.debug), ("prep_stop", args.prep_stop)):
         if val is not None:
             molgrid.set_option(key, val)

@@ -316,6 +316,8 @@ int mg_last_hip_error(void);
  *                     wavefront (index types, float grid) also reads that many
  *                     bytes of the workspace tables so that they stay cached while
  *                     the grid is streamed out
+ *   "keep_alive_stride" 1, 2, 4 or 8 (default 1): only one wavefront in that many
+ *                     does the keep-alive read
  *   "single_launch"   0 or 1 (default 1): index types into a float grid with at most
  *                     256 atoms per example and 2048 in the batch run as ONE kernel
  *                     launch (every tile's wavefront transforms, culls and filters the

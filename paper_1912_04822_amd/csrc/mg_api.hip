@@ -33,6 +33,7 @@ std::atomic<int> g_xcd_run{0};
 std::atomic<int> g_lds_floor{-1};        // < 0: chosen by the launcher
 std::atomic<int> g_tile_order{0};
 std::atomic<int> g_keep_alive{1};
+std::atomic<int> g_keep_alive_stride{1};
 std::atomic<int> g_single_launch{1};     // small problems: the forward kernel alone, no prep kernel
 #ifdef MG_TIMING_AIDS
 std::atomic<int> g_debug{0};             // measurement build only: kernel phases switched off
@@ -299,7 +300,8 @@ static int forward_call(const mg_gridmaker *gm, int B, int N, int T, const float
     return hip_status(mg::launch_forward(gm->gs, bt, ws, out, out_is_double, knob(g_tile_floats),
                                          knob(g_waves_per_tile), knob(g_xcd_run), knob(g_lds_floor),
                                          timing_debug(), knob(g_tile_order), knob(g_keep_alive), single,
-                                         expect, take_events(), (hipStream_t)stream));
+                                         expect, take_events(), (hipStream_t)stream,
+                                         knob(g_keep_alive_stride)));
 }
 
 int mg_prepare(const mg_gridmaker *gm, int B, int N, int T, const float *coords,
@@ -559,6 +561,11 @@ int mg_set_option(const char *key, int value)
             value != 1024)
             return MG_EPARAM;
         g_keep_alive = value;
+        return MG_OK;
+    }
+    if (std::strcmp(key, "keep_alive_stride") == 0) {
+        if (value != 1 && value != 2 && value != 4 && value != 8) return MG_EPARAM;
+        g_keep_alive_stride = value;
         return MG_OK;
     }
     if (std::strcmp(key, "single_launch") == 0) {

@@ -176,7 +176,8 @@ bool forward_takes_single_launch(const Batch &bt, bool out_is_double);
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                           void *out, bool out_is_double, int tile_floats, int waves_per_tile,
                           int xcd_run, int lds_floor, int debug, int tile_order, int keep_alive,
-                          bool single_launch, unsigned expect_tag, KernelEvents ev, hipStream_t stream);
+                          bool single_launch, unsigned expect_tag, KernelEvents ev, hipStream_t stream,
+                          int keep_alive_stride = 1);
 hipError_t launch_backward(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                            const void *grad_out, bool grad_is_double, float *grad_coords,
                            float *grad_weights, unsigned expect_tag, KernelEvents ev,

@@ -109,6 +109,7 @@ struct FwdParams {
     int debug;
     unsigned ka_chunks, ka_last;    // keep-alive reads: chunks of the tables (0: none), byte offset of the last one
     unsigned ka_shift;              // log2 of the chunk size in bytes (6..10)
+    unsigned ka_skip;               // 0, 1, 3 or 7: wavefronts whose id has none of these bits set do the read
     float sk;           // sqrt(k), k = 2 log2(e)
     float inv_sk;
     float g2k, c2k;     // g^2 k, c^2 k
@@ -785,7 +786,7 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
         : "=s"(zero)
         : "s"((unsigned long long)p.range), "s"((unsigned long long)p.rec),
           "s"((unsigned long long)p.gcen), "s"((unsigned long long)p.out), "s"(p.tiles_magic),
-          "s"(p.t_magic), "s"(p.div_magic), "s"(p.tiles), "s"(p.pos_major), "s"(p.ka_chunks), "s"(p.ka_last), "s"(p.ka_shift), "s"(p.xcd_shift), "s"(p.n_remap), "s"(D),
+          "s"(p.t_magic), "s"(p.div_magic), "s"(p.tiles), "s"(p.pos_major), "s"(p.ka_chunks), "s"(p.ka_last), "s"(p.ka_shift), "s"(p.ka_skip), "s"(p.xcd_shift), "s"(p.n_remap), "s"(D),
           "s"(T), "s"(N), "s"(p.debug), "s"(gs.half));
     if (p.expect_tag != 0u && *p.tag != p.expect_tag) return;      // not the tables this call expects
     unsigned u = blockIdx.x + zero;
@@ -803,7 +804,8 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     if (p.ka_chunks) {
         const unsigned c = __umulhi((blockIdx.x + zero) * 2654435761u, p.ka_chunks);
         const unsigned off = min(c << p.ka_shift, p.ka_last) + ((threadIdx.x & 63u) << 4);
-        if ((threadIdx.x & 63u) < (1u << (p.ka_shift - 4)))     // the chunk's lanes, 16 bytes each
+        if ((threadIdx.x & 63u) < (1u << (p.ka_shift - 4)) &&   // the chunk's lanes, 16 bytes each
+            ((blockIdx.x + zero) & p.ka_skip) == 0u)            // (every wavefront, or one in 2, 4, 8)
             ka = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(p.rec) + off);
     }
     const unsigned uq = div_u32(u, p.tiles_magic), ur = u - uq * p.tiles;
@@ -1255,6 +1257,7 @@ static hipError_t launch_forward_vector(const GridSpec &gs, const Batch &bt, con
     p.ka_chunks = 0;
     p.ka_last = 0;
     p.ka_shift = 8;
+    p.ka_skip = 0;
     const double k = 2.8853900817779268;        // 2 / ln 2
     p.sk = (float)std::sqrt(k);
     p.inv_sk = (float)(1.0 / std::sqrt(k));
@@ -1305,7 +1308,7 @@ bool forward_takes_single_launch(const Batch &bt, bool out_is_double)
 hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &ws, void *out,
                           bool out_is_double, int tile_floats, int waves_per_tile, int xcd_run,
                           int lds_floor, int debug, int tile_order, int keep_alive, bool single_launch,
-                          unsigned expect_tag, KernelEvents ev, hipStream_t stream)
+                          unsigned expect_tag, KernelEvents ev, hipStream_t stream, int keep_alive_stride)
 {
     if (bt.vec && !gs.binary)
         return launch_forward_vector(gs, bt, ws, out, out_is_double, tile_floats, waves_per_tile, expect_tag, ev,
@@ -1377,6 +1380,7 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
         const size_t bytes = (size_t)((const char *)(ws.gcen + (size_t)bt.B * 4) - (const char *)ws.rec);
         p.ka_chunks = 0;
         p.ka_last = 0;
+        p.ka_skip = keep_alive_stride > 1 ? (unsigned)keep_alive_stride - 1u : 0u;
         // keep_alive: 0 = none, 1 = the default chunk, else the chunk in bytes (256, 512, 1024)
         const unsigned chunk = keep_alive == 1 ? kKeepAliveBytes : (unsigned)keep_alive;
         p.ka_shift = chunk == 1024u ? 10u : (chunk == 512u ? 9u : (chunk == 128u ? 7u : (chunk == 64u ? 6u : 8u)));

@@ -149,7 +149,7 @@ def test_calls_reject_bad_arguments_before_any_launch(L):
                      (b"lds_floor", -2), (b"keep_alive", -1), (b"tile_order", -1)):
         assert L.mg_set_option(key, bad) == -3
     for key, good, bad, default in ((b"keep_alive", 0, 2, 1), (b"tile_order", 1, 2, 0),
-                                    (b"single_launch", 0, 2, 1),
+                                    (b"single_launch", 0, 2, 1), (b"keep_alive_stride", 4, 3, 1),
                                     (b"lds_floor", 8192, 70000, -1), (b"xcd_run", 8, 12, 0)):
         assert L.mg_set_option(key, good) == 0
         assert L.mg_set_option(key, bad) == -3

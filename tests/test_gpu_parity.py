@@ -202,14 +202,15 @@ def test_forward_protein_ligand_subset_and_determinism(mg):
         assert np.abs(other - ref).max() <= GRID_TOL
 
 
-@pytest.mark.parametrize("key,value", [("keep_alive", 0), ("tile_order", 1), ("xcd_run", 8),
+@pytest.mark.parametrize("key,value", [("keep_alive", 0), ("keep_alive", 64), ("keep_alive", 1024),
+                                       ("keep_alive_stride", 4), ("tile_order", 1), ("xcd_run", 8),
                                        ("lds_floor", 0), ("lds_floor", 16384)])
 def test_launch_knobs_do_not_change_a_bit(mg, key, value):
     """Launch order, residency and the keep-alive reads only change when things run: the grid is
     the same to the bit (index types, binary, and an unaligned grid)."""
     cases = [workloads.protein_ligand(B=3, seed=17), workloads.ragged_small()]
     base = [(run_forward_index(mg, w), run_forward_index(mg, w, binary=True)) for w in cases]
-    default = {"keep_alive": 1, "tile_order": 0, "xcd_run": 0, "lds_floor": -1}[key]
+    default = {"keep_alive": 1, "keep_alive_stride": 1, "tile_order": 0, "xcd_run": 0, "lds_floor": -1}[key]
     mg.set_option(key, value)
     try:
         for w, (real, binary) in zip(cases, base):
@@ -353,6 +354,26 @@ def test_forward_vector_negative_weights_large_weights_and_ragged_channel_groups
         assert err <= max(GRID_TOL, 2e-6 * scale_ref), (T, scale, err, scale_ref)
         again = run_forward_vector(mg, w)           # float tiles too repeat bit for bit
         assert np.array_equal(got.view(np.uint32), again.view(np.uint32))
+
+
+def test_forward_and_backward_vector_with_more_channels_than_are_ranked(mg):
+    """Beyond 256 channels the channels are taken as they come instead of in order of radius."""
+    rng = np.random.default_rng(77)
+    w = workloads.ragged_small(B=2, N=40, T=300, D=12)
+    got = run_forward_vector(mg, w)
+    ref = oracle.forward_vector(w.coords, w.weights, w.radii, w.resolution, w.dimension,
+                                centers=w.centers, quats=w.quats, translations=w.translations)
+    assert ref.max() > 0.05
+    assert np.abs(got - ref).max() <= GRID_TOL
+    gm = mg.GridMaker(w.resolution, w.dimension, radius_type_indexed=True)
+    G = rng.standard_normal(ref.shape).astype(np.float32)
+    gc, gw = gm.mg_backward_vector(dev(w.coords), dev(w.weights), dev(w.radii), dev(G),
+                                   centers=dev(w.centers), quats=dev(w.quats),
+                                   translations=dev(w.translations))
+    rc, rw = oracle.backward_vector(w.coords, w.weights, w.radii, w.resolution, w.dimension, G,
+                                    centers=w.centers, quats=w.quats, translations=w.translations)
+    assert np.abs(gc.cpu().numpy() - rc).max() <= GRAD_RTOL * np.abs(rc).max()
+    assert np.abs(gw.cpu().numpy() - rw).max() <= GRAD_RTOL * np.abs(rw).max()
 
 
 def test_forward_vector_binary_is_bit_exact(mg):

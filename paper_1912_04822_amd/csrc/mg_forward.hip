@@ -170,7 +170,7 @@ __device__ inline float fetch(int byte_addr, float v)
 }
 
 // Run the staged tasks [0, ntasks): one (atom, row) chord per lane.
-template <bool VECTOR, bool BINARY, bool FIXED>
+template <bool BINARY, bool FIXED>
 __device__ inline void run_tasks(const TileCtx &cx, const Cand &cd, int ntasks)
 {
     int carry = 0;
@@ -214,9 +214,7 @@ __device__ inline void run_tasks(const TileCtx &cx, const Cand &cd, int ntasks)
                 if (d2 <= r2) rowp[klo + i] = 1.0f;
             }
         } else {
-            const float fy = p0.x, fz = p0.y, stepk = p0.z;
-            const float w = p0.w;                                           // vector types
-            const float inv_stepk = VECTOR ? __builtin_amdgcn_rcpf(stepk) : p0.w;
+            const float fy = p0.x, fz = p0.y, stepk = p0.z, inv_stepk = p0.w;
             const float dyk = (((float)j - cx.hD) - fy) * stepk;
             const float x2b = fmaf(dyk, dyk, px2);
             const float rem = cx.c2k - x2b;
@@ -230,38 +228,20 @@ __device__ inline void run_tasks(const TileCtx &cx, const Cand &cd, int ntasks)
             float cA = cx.cA;
             asm volatile("" : "+v"(cA));        // keep it in a VGPR across the loop
             float fi = 0.0f;
-            if (VECTOR && FIXED) {
-                // weight in fixed-point units (a power of two: exact); the product has the
-                // weight's sign, so adding half a unit of that sign and truncating rounds to
-                // nearest.  The voxel count is kept as a float: one counter less in the loop.
-                const float wK = w * kFixedOne, half = copysignf(0.5f, w);
-                const float fnz = (float)nz;
-                int *q = reinterpret_cast<int *>(rowp) + klo;
-                for (; fi < fnz; fi += 1.0f, ++q) {
-                    const float zs = fmaf(fi, stepk, z0);
-                    const float x2 = fmaf(zs, zs, x2b);
-                    const float e = __builtin_amdgcn_exp2f(-x2);
-                    const float u = fminf(fmaf(__builtin_amdgcn_sqrtf(x2), cx.sA, -cA), 0.0f);
-                    const float rho = x2 <= cx.g2k ? e : u * u;             // 0 beyond the cutoff
-                    __hip_atomic_fetch_add(q, (int)fmaf(rho, wK, half), __ATOMIC_RELAXED,
+            for (int i = 0; i < nz; ++i) {
+                const float zs = fmaf(fi, stepk, z0);
+                fi += 1.0f;
+                const float x2 = fmaf(zs, zs, x2b);
+                const float e = __builtin_amdgcn_exp2f(-x2);
+                const float u = fminf(fmaf(__builtin_amdgcn_sqrtf(x2), cx.sA, -cA), 0.0f);
+                const float rho = x2 <= cx.g2k ? e : u * u;             // 0 beyond the cutoff
+                if (FIXED) {
+                    __hip_atomic_fetch_add(reinterpret_cast<int *>(rowp) + klo + i,
+                                           (int)fmaf(rho, kFixedOne, 0.5f), __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_WORKGROUP);
-                }
-            } else {
-                for (int i = 0; i < nz; ++i) {
-                    const float zs = fmaf(fi, stepk, z0);
-                    fi += 1.0f;
-                    const float x2 = fmaf(zs, zs, x2b);
-                    const float e = __builtin_amdgcn_exp2f(-x2);
-                    const float u = fminf(fmaf(__builtin_amdgcn_sqrtf(x2), cx.sA, -cA), 0.0f);
-                    const float rho = x2 <= cx.g2k ? e : u * u;             // 0 beyond the cutoff
-                    if (FIXED) {
-                        __hip_atomic_fetch_add(reinterpret_cast<int *>(rowp) + klo + i,
-                                               (int)fmaf(rho, kFixedOne, 0.5f), __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_WORKGROUP);
-                    } else {
-                        __hip_atomic_fetch_add(rowp + klo + i, VECTOR ? w * rho : rho, __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_WORKGROUP);
-                    }
+                } else {
+                    __hip_atomic_fetch_add(rowp + klo + i, rho, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_WORKGROUP);
                 }
             }
         }
@@ -307,7 +287,7 @@ struct PairHit {
 };
 
 // One atom per lane against the rows of planes A and B that belong to the tile.
-template <bool VECTOR, bool BINARY>
+template <bool BINARY>
 __device__ inline PairHit pair_test(const TileCtx &cx, const FwdParams &p, const Atom &at, float ox,
                                     int iA, int jaA, int jbA, int jaB, int jbB)
 {
@@ -336,7 +316,7 @@ __device__ inline PairHit pair_test(const TileCtx &cx, const FwdParams &p, const
         const float reach = r + 1.0e-3f * cx.res;
         h.cd.c0 = at.a.y; h.cd.c1 = at.a.z; h.cd.c2 = r * r; h.cd.c3 = reach * reach;
     } else {
-        h.cd.c0 = fy; h.cd.c1 = fz; h.cd.c2 = stepk; h.cd.c3 = VECTOR ? at.w : inv_stepk;
+        h.cd.c0 = fy; h.cd.c1 = fz; h.cd.c2 = stepk; h.cd.c3 = inv_stepk;
     }
     h.cd.start = 0;
     h.cd.pack = jloA | (h.nA << 10) | (jloB << 20);
@@ -358,7 +338,7 @@ __device__ inline int pair_bound(const PairHit &h, const Atom &at)
 // Stage the tasks of the hits (rows of plane A, then rows of plane B, atom after atom)
 // and run them.
 // Returns whether there was any task.
-template <bool VECTOR, bool BINARY>
+template <bool BINARY>
 __device__ inline bool pair_run(const TileCtx &cx, PairHit &h, bool fixed)
 {
     int todo = h.nA + h.nB;         // lanes still to be staged have todo > 0
@@ -381,8 +361,8 @@ __device__ inline bool pair_run(const TileCtx &cx, PairHit &h, bool fixed)
             todo = 0;
         }
         lds_sync();
-        if (fixed) run_tasks<VECTOR, BINARY, true>(cx, h.cd, total);
-        else run_tasks<VECTOR, BINARY, false>(cx, h.cd, total);
+        if (fixed) run_tasks<BINARY, true>(cx, h.cd, total);
+        else run_tasks<BINARY, false>(cx, h.cd, total);
     }
     return true;
 }
@@ -501,7 +481,7 @@ __device__ inline TileGeom tile_geom(const FwdParams &p, int D, unsigned tile_in
 // FUSED (small problems, index types): there are no records; the "records" [r0, r1) are the
 // example's atoms themselves, and a lane transforms, culls and filters by type the atom it takes,
 // with the arithmetic and the tests of the prep kernel.
-template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS, int NW, typename OUT, bool FUSED = false>
+template <bool BINARY, bool ALIGNED, int ITERS, int NW, typename OUT, bool FUSED = false>
 __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b, int t,
                                           const TileGeom &tg, int r0, int r1, const float4 &cen)
 {
@@ -536,10 +516,8 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
     const float ox = cx.cen_x - gs.half;
     cx.oy = cx.cen_y - gs.half;
     cx.oz = cx.cen_z - gs.half;
-    const float r_chan = VECTOR ? gs.radius_scale * p.radii[t] : 0.0f;
 
     const float4 *rec = p.rec + (size_t)b * N + r0;
-    const int *idx = p.idx + (size_t)b * N + r0;
     const int count = r1 - r0;
     if (count <= 0) {           // uniform: nothing can reach this tile
         store_tile<ALIGNED, ITERS, NW, OUT>(cx, dst, false, false);
@@ -559,9 +537,6 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
         pA0 = i_lo + 2 * (wave >> 1);
         pA1 = min(pA0 + 1, i_hi);
     }
-    // vector types: the weights of this channel, one per atom of the source example
-    const float *wcol = VECTOR ? p.weights + (size_t)source_example(p.subgrids, b) * N * T + t
-                               : nullptr;
     // FUSED: an atom's type, coordinates and radius are requested together (one trip to memory),
     // whatever the type turns out to be; finish_raw transforms, culls and filters by type with
     // the prep kernel's arithmetic and tests.
@@ -603,15 +578,8 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
         at.a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         at.w = 1.0f;
         if (FUSED) return finish_raw(fetch_raw(base), e);
-        if (e < count) {
-            at.a = rec[e];
-            if (VECTOR && at.a.w > 0.0f) at.w = wcol[(size_t)idx[e] * T];
-        }
+        if (e < count) at.a = rec[e];
         at.valid = (e < count) && (at.a.w > 0.0f);
-        if (VECTOR) {
-            at.a.w = r_chan;
-            at.valid = at.valid && (r_chan > 0.0f) && (BINARY ? (at.w > 0.0f) : (at.w != 0.0f));
-        }
         return at;
     };
     auto test_pair = [&](const Atom &at, int iA) {
@@ -619,7 +587,7 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
         cx.rowB = cx.rowA + D;
         const int jaA = max(-cx.rowA, 0), jbA = min(R1 - R0 - cx.rowA, D);
         const int jaB = max(-cx.rowB, 0), jbB = iA < i_hi ? min(R1 - R0 - cx.rowB, D) : 0;
-        return pair_test<VECTOR, BINARY>(cx, p, at, ox, iA, jaA, jbA, jaB, jbB);
+        return pair_test<BINARY>(cx, p, at, ox, iA, jaA, jbA, jaB, jbB);
     };
 
     // the loads of the first round are under way; clear the tile meanwhile
@@ -642,59 +610,7 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
     const bool single = count <= 64 * nsplit && pA1 - pA0 <= 1;    // one round, one pair of planes
     const int limit = (int)(kFixedLimit * 256.0f);
     bool any = false, fixed = !BINARY;
-    if (VECTOR && NW == 1 && !single) {
-        // Vector types, one wavefront, several rounds.  As the single pass below, but the loads
-        // run two stages ahead: a weight is gathered through the atom's index, so asking for
-        // the records of the next round and their weights in one go would make every round
-        // wait for a trip to memory between the two.  Records and indices are requested two
-        // rounds ahead, the weights one round ahead, each from values that arrived a round ago.
-        struct Raw {
-            float4 a;
-            int ai;
-        };
-        auto load_raw = [&](int base) {
-            Raw r;
-            r.a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            r.ai = 0;
-            if (base + lane < count) {
-                r.a = rec[base + lane];
-                r.ai = idx[base + lane];
-            }
-            return r;
-        };
-        auto gather = [&](const Raw &r) { return r.a.w > 0.0f ? wcol[(size_t)r.ai * T] : 1.0f; };
-        auto make_atom = [&](const Raw &r, float w) {
-            Atom at;
-            at.a = r.a;
-            at.w = w;
-            at.valid = (r.a.w > 0.0f) && (r_chan > 0.0f) && (BINARY ? (w > 0.0f) : (w != 0.0f));
-            at.a.w = r_chan;
-            return at;
-        };
-        Raw rn = load_raw(64);
-        float wn = gather(rn);
-        int bound = 0;
-        Atom at = at0;
-        for (int base = 0; base < count; base += 64) {
-            const Raw rnn = load_raw(base + 128);
-            for (int iA = pA0; iA <= pA1; iA += 2) {
-                PairHit h = test_pair(at, iA);
-                if (!BINARY && fixed) {
-                    bound += min(pair_bound<VECTOR>(h, at), 1 << 24);
-                    if (bound > limit) {
-                        fixed = false;
-                        for (int o = lane; o < ITERS * 512; o += 64)
-                            cx.tile[o] = (float)reinterpret_cast<int *>(cx.tile)[o] * (1.0f / kFixedOne);
-                        lds_sync();
-                    }
-                }
-                any = pair_run<VECTOR, BINARY>(cx, h, fixed) || any;
-            }
-            at = make_atom(rn, wn);
-            rn = rnn;
-            wn = gather(rn);
-        }
-    } else if (NW == 1 && !single) {
+    if (NW == 1 && !single) {
         // One wavefront, several rounds: a single pass.  The tile starts in fixed point and
         // the bound on what can reach one voxel is kept up round by round; the moment it
         // passes the limit, the tile is turned into floats and stays so.  The records of
@@ -707,7 +623,7 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
             for (int iA = pA0; iA <= pA1; iA += 2) {
                 PairHit h = test_pair(at, iA);
                 if (!BINARY && fixed) {
-                    bound += min(pair_bound<VECTOR>(h, at), 1 << 24);
+                    bound += min(pair_bound<false>(h, at), 1 << 24);
                     if (bound > limit) {
                         fixed = false;
                         for (int o = lane; o < ITERS * 512; o += 64)
@@ -715,7 +631,7 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
                         lds_sync();
                     }
                 }
-                any = pair_run<VECTOR, BINARY>(cx, h, fixed) || any;
+                any = pair_run<BINARY>(cx, h, fixed) || any;
             }
             at = next;
         }
@@ -725,17 +641,17 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
         // pass 1: what can be added to one voxel at most decides fixed point or float (one
         // wavefront keeps the bound in a register, several add theirs up in LDS)
         // (index types: every record adds at most 1 to a voxel, so a short span needs no count)
-        const bool short_span = !VECTOR && count <= (int)kFixedLimit;
+        const bool short_span = count <= (int)kFixedLimit;
         int bound = 0;
         if (single) {
             h0 = test_pair(at0, pA0);
-            if (!BINARY && !short_span) bound = pair_bound<VECTOR>(h0, at0);
+            if (!BINARY && !short_span) bound = pair_bound<false>(h0, at0);
         } else if (!BINARY && !short_span) {
             for (int base = 0; base < count && bound <= limit; base += 64 * nsplit) {
                 const Atom at = base == 0 ? at0 : load_atom(base);
                 for (int iA = pA0; iA <= pA1; iA += 2) {
                     const PairHit h = test_pair(at, iA);
-                    bound += min(pair_bound<VECTOR>(h, at), 1 << 24);   // past the limit the value does not matter
+                    bound += min(pair_bound<false>(h, at), 1 << 24);   // past the limit the value does not matter
                 }
             }
         }
@@ -747,13 +663,13 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
         fixed = !BINARY && bound <= limit;
         // pass 2: the tasks
         if (single) {
-            any = pair_run<VECTOR, BINARY>(cx, h0, fixed);
+            any = pair_run<BINARY>(cx, h0, fixed);
         } else {
             for (int base = 0; base < count; base += 64 * nsplit) {
                 const Atom at = base == 0 ? at0 : load_atom(base);
                 for (int iA = pA0; iA <= pA1; iA += 2) {
                     PairHit h = test_pair(at, iA);
-                    any = pair_run<VECTOR, BINARY>(cx, h, fixed) || any;
+                    any = pair_run<BINARY>(cx, h, fixed) || any;
                 }
             }
         }
@@ -768,7 +684,7 @@ __device__ __forceinline__ void tile_body(const FwdParams &p, float *lds, int b,
 
 
 // One workgroup per tile.  OUT: float, or double for a grid of doubles.
-template <bool VECTOR, bool BINARY, bool ALIGNED, int ITERS, int NW, typename OUT, bool FUSED = false>
+template <bool BINARY, bool ALIGNED, int ITERS, int NW, typename OUT, bool FUSED = false>
 __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];   // tile | marks per wave | shared
@@ -828,10 +744,10 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
             n = p.raw.natoms[b];
             n = n < 0 ? 0 : (n > N ? N : n);
         }
-        tile_body<VECTOR, BINARY, ALIGNED, ITERS, NW, OUT, true>(p, lds, b, t, tgf, 0, n, cenf);
+        tile_body<BINARY, ALIGNED, ITERS, NW, OUT, true>(p, lds, b, t, tgf, 0, n, cenf);
         return;
     }
-    const size_t group = (size_t)b * T + (VECTOR ? 0 : t);
+    const size_t group = (size_t)b * T + t;
     // All the scalar loads of the preamble are issued together (one trip to L2, which is
     // slow while the chip streams stores): the span of records that can reach the planes
     // of the tile (counted from the example's first record) and the grid centre.
@@ -845,7 +761,7 @@ __global__ __launch_bounds__(64 * NW) void forward_kernel(FwdParams p)
     }
     asm volatile("" ::"s"(r0), "s"(r1), "s"(cen.x), "s"(cen.y), "s"(cen.z));  // all in flight before the first wait
     if (MG_DEBUG_IS(p, 2)) r1 = r0;
-    tile_body<VECTOR, BINARY, ALIGNED, ITERS, NW, OUT>(p, lds, b, t, tg, r0, r1, cen);
+    tile_body<BINARY, ALIGNED, ITERS, NW, OUT>(p, lds, b, t, tg, r0, r1, cen);
     asm volatile("" ::"v"(ka.x), "v"(ka.y), "v"(ka.z), "v"(ka.w));     // the keep-alive read is waited for here
 }
 
@@ -876,6 +792,7 @@ struct VecGroup {           // wave-uniform: the channels of this workgroup
     float ratio2[kVecGroup];    // (rmax / r_q)^2
     float sAq[kVecGroup];       // sA rmax / r_q
     float thq[kVecGroup];       // Gaussian region of channel q: x'^2 <= g^2 k / ratio2_q
+    float r2[kVecGroup];        // binary mode: r_q * r_q (float, as the predicate's right-hand side)
     float rmax;
 };
 
@@ -883,7 +800,7 @@ struct VecAtom {            // per atom, per channel of the group
     float lw[kVecGroup];        // log2 |w_q|  (-inf for w_q = 0: the Gaussian is then 0)
     float su[kVecGroup];        // sqrt|w_q| sA ratio_q
     float sc[kVecGroup];        // sqrt|w_q| cA
-    int neg;                    // bit q: w_q < 0
+    int neg;                    // bit q: w_q < 0  (binary mode: bit q: w_q > 0, the atom marks channel q)
 };
 
 // Run the staged tasks [0, ntasks): one (atom, row) chord per lane, kVecGroup channels per voxel.
@@ -963,8 +880,57 @@ __device__ inline void run_tasks_group(const TileCtx &cx, const VecGroup &vg, co
     lds_sync();
 }
 
+// Binary occupancy for a group of channels: the chord of the widest sphere is walked once, d^2 is
+// worked out once per voxel in the fixed float order of the predicate, and channel q is marked
+// where the atom's weight is positive and d^2 <= r_q^2.
+__device__ inline void run_tasks_group_binary(const TileCtx &cx, const VecGroup &vg, const Cand &cd,
+                                              const VecAtom &va, int stride, int ntasks)
+{
+    int carry = 0;
+    for (int base = 0; base < ntasks; base += 64) {
+        const int tau = base + cx.lane;
+        bool act = tau < ntasks;
+        const int owner = max(carry, wave_inclusive_max((int)cx.marks[tau]));
+        carry = bcast(owner, 63);
+        const int src = (act ? owner - 1 : 0) << 2;
+        const float ay = fetch(src, cd.c0), az = fetch(src, cd.c1), reach2 = fetch(src, cd.c3);
+        const float pxA = fetch(src, cd.pxA), pxB = fetch(src, cd.pxB);
+        const int pack = __builtin_amdgcn_ds_bpermute(src, cd.pack);
+        const int k = tau - __builtin_amdgcn_ds_bpermute(src, cd.start);   // row number within the atom
+        const int pos = __builtin_amdgcn_ds_bpermute(src, va.neg);         // channels the atom marks
+        const int nA = (pack >> 10) & 1023;
+        const bool inB = k >= nA;
+        const int j = inB ? (pack >> 20) + (k - nA) : (pack & 1023) + k;   // row in its plane
+        const int trow = (inB ? cx.rowB : cx.rowA) + j;                    // row in the tile
+        const float px2 = inB ? pxB : pxA;                                 // dx^2
+        const int clip_lo = trow == 0 ? cx.c0 : 0;
+        const int clip_hi = trow == cx.nrows - 1 ? cx.c1 : cx.D - 1;
+        float *rowp = cx.tile + (trow * cx.D - cx.c0);
+        const float gy = cx.oy + (float)j * cx.res;
+        const float dy = gy - ay;
+        const float dy2 = dy * dy;
+        const float rem = (reach2 - px2) - dy2;
+        act = act && rem > 0.0f;
+        const float hz = __builtin_amdgcn_sqrtf(fmaxf(rem, 0.0f)) * cx.inv_res + 1.0e-3f;
+        const float fz = (az - cx.oz) * cx.inv_res;
+        const int klo = max(clip_lo, (int)ceilf(fz - hz));
+        const int khi = min(clip_hi, (int)floorf(fz + hz));
+        const int nz = act ? khi - klo + 1 : 0;
+        const float base2 = px2 + dy2;
+        for (int i = 0; i < nz; ++i) {
+            const float gz = cx.oz + (float)(klo + i) * cx.res;
+            const float dz = gz - az;
+            const float d2 = base2 + dz * dz;
+#pragma unroll
+            for (int q = 0; q < kVecGroup; ++q)
+                if (((pos >> q) & 1) && d2 <= vg.r2[q]) rowp[klo + i + q * stride] = 1.0f;
+        }
+    }
+    lds_sync();
+}
+
 // Stage the tasks of the hits and run them (as pair_run, for a group of channels).
-template <bool SIGNED>
+template <bool BINARY, bool SIGNED>
 __device__ inline bool pair_run_group(const TileCtx &cx, const VecGroup &vg, PairHit &h,
                                       const VecAtom &va, int stride, bool fixed)
 {
@@ -988,7 +954,8 @@ __device__ inline bool pair_run_group(const TileCtx &cx, const VecGroup &vg, Pai
             todo = 0;
         }
         lds_sync();
-        if (fixed) run_tasks_group<true, SIGNED>(cx, vg, h.cd, va, stride, total);
+        if (BINARY) run_tasks_group_binary(cx, vg, h.cd, va, stride, total);
+        else if (fixed) run_tasks_group<true, SIGNED>(cx, vg, h.cd, va, stride, total);
         else run_tasks_group<false, SIGNED>(cx, vg, h.cd, va, stride, total);
     }
     return true;
@@ -1000,7 +967,7 @@ __device__ inline bool pair_run_group(const TileCtx &cx, const VecGroup &vg, Pai
 // what can reach one voxel is summed up on the way, and a workgroup whose bound passes the
 // limit at the end (rare) starts over in floats, all records taken by its first wavefront so
 // that the order of the float additions is the same in every run.
-template <bool ALIGNED, int ITERS, int NW, typename OUT>
+template <bool BINARY, bool ALIGNED, int ITERS, int NW, typename OUT>
 __global__ __launch_bounds__(64 * NW) void forward_vector_kernel(FwdParams p)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];   // kVecGroup tiles | marks per wave | bound
@@ -1036,6 +1003,7 @@ __global__ __launch_bounds__(64 * NW) void forward_vector_kernel(FwdParams p)
         vg.ratio2[q] = ratio * ratio;
         vg.sAq[q] = p.sA * ratio;
         vg.thq[q] = p.g2k * __builtin_amdgcn_rcpf(vg.ratio2[q]);
+        vg.r2[q] = vg.live[q] ? rq[q] * rq[q] : -1.0f;     // (nothing is within a dead channel's radius)
     }
 
     TileCtx cx;
@@ -1139,6 +1107,11 @@ __global__ __launch_bounds__(64 * NW) void forward_vector_kernel(FwdParams p)
             va.neg = 0;
 #pragma unroll
             for (int q = 0; q < kVecGroup; ++q) {
+                if (BINARY) {       // the atom marks the channels where its weight is positive
+                    va.lw[q] = 0.0f; va.su[q] = 0.0f; va.sc[q] = 0.0f;
+                    va.neg |= (wc.w[q] > 0.0f ? 1 : 0) << q;
+                    continue;
+                }
                 const float aw = fabsf(wc.w[q]);
                 wmax = fmaxf(wmax, aw);
                 const float sw = __builtin_amdgcn_sqrtf(aw);
@@ -1148,18 +1121,18 @@ __global__ __launch_bounds__(64 * NW) void forward_vector_kernel(FwdParams p)
                 va.neg |= (wc.w[q] < 0.0f ? 1 : 0) << q;
             }
             at.w = wmax;
-            at.valid = (rc.a.w > 0.0f) && (wmax > 0.0f);
+            at.valid = (rc.a.w > 0.0f) && (BINARY ? va.neg != 0 : wmax > 0.0f);
             at.a.w = vg.rmax;
-            const bool any_neg = __ballot(at.valid && va.neg != 0) != 0ull;
+            const bool any_neg = !BINARY && __ballot(at.valid && va.neg != 0) != 0ull;
             for (int iA = tg.i_lo; iA <= tg.i_hi; iA += 2) {
                 cx.rowA = iA * D - tg.R0;
                 cx.rowB = cx.rowA + D;
                 const int jaA = max(-cx.rowA, 0), jbA = min(tg.R1 - tg.R0 - cx.rowA, D);
                 const int jaB = max(-cx.rowB, 0), jbB = iA < tg.i_hi ? min(tg.R1 - tg.R0 - cx.rowB, D) : 0;
-                PairHit h = pair_test<false, false>(cx, p, at, ox, iA, jaA, jbA, jaB, jbB);
-                bound = min(bound + min(pair_bound<true>(h, at), 1 << 24), 1 << 26);
-                const bool ran = any_neg ? pair_run_group<true>(cx, vg, h, va, kTile, fixed)
-                                         : pair_run_group<false>(cx, vg, h, va, kTile, fixed);
+                PairHit h = pair_test<BINARY>(cx, p, at, ox, iA, jaA, jbA, jaB, jbB);
+                if (!BINARY) bound = min(bound + min(pair_bound<true>(h, at), 1 << 24), 1 << 26);
+                const bool ran = any_neg ? pair_run_group<BINARY, true>(cx, vg, h, va, kTile, fixed)
+                                         : pair_run_group<BINARY, false>(cx, vg, h, va, kTile, fixed);
                 any = ran || any;
             }
             rc = rn;
@@ -1172,8 +1145,8 @@ __global__ __launch_bounds__(64 * NW) void forward_vector_kernel(FwdParams p)
 
     const int limit = (int)(kFixedLimit * 256.0f);
     int bound = 0;
-    bool fixed = true;
-    bool any = pass(wave, NW, true, true, bound);
+    bool fixed = !BINARY;       // (binary tiles hold 0.0f / 1.0f as they are)
+    bool any = pass(wave, NW, fixed, true, bound);
     if (NW > 1) {
         if (lane == 0) {
             atomicAdd(&cx.shared[0], bound);
@@ -1183,7 +1156,7 @@ __global__ __launch_bounds__(64 * NW) void forward_vector_kernel(FwdParams p)
         bound = cx.shared[0];
         any = cx.shared[1] != 0;
     }
-    if (bound > limit) {                    // uniform over the workgroup: the sums may not fit; again, in floats
+    if (!BINARY && bound > limit) {         // uniform over the workgroup: the sums may not fit; again, in floats
         if (NW > 1) __syncthreads();        // shared[] has been read by all
         fixed = false;
         clear_tiles();
@@ -1276,9 +1249,15 @@ static hipError_t launch_forward_vector(const GridSpec &gs, const Batch &bt, con
     const size_t lds_bytes = (size_t)kVecGroup * tile_floats * sizeof(float) + (size_t)nw * kTaskCap + 16;
     const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)out & 15u) == 0);
     const dim3 blk(64 * nw), grd((unsigned)wgs);
-#define MG_VEC(Al, It, Nw, Ot) \
-    hipExtLaunchKernelGGL((forward_vector_kernel<Al, It, Nw, Ot>), grd, blk, (uint32_t)lds_bytes, stream, \
-                          ev.start, ev.stop, 0, p)
+#define MG_VEC(Al, It, Nw, Ot)                                                                        \
+    do {                                                                                              \
+        if (gs.binary)                                                                                \
+            hipExtLaunchKernelGGL((forward_vector_kernel<true, Al, It, Nw, Ot>), grd, blk,            \
+                                  (uint32_t)lds_bytes, stream, ev.start, ev.stop, 0, p);              \
+        else                                                                                          \
+            hipExtLaunchKernelGGL((forward_vector_kernel<false, Al, It, Nw, Ot>), grd, blk,           \
+                                  (uint32_t)lds_bytes, stream, ev.start, ev.stop, 0, p);              \
+    } while (0)
 #define MG_VEC_NW(Al, It, Ot) \
     if (nw == 1) MG_VEC(Al, It, 1, Ot); else MG_VEC(Al, It, 2, Ot)
     if (out_is_double) {
@@ -1310,7 +1289,7 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
                           int lds_floor, int debug, int tile_order, int keep_alive, bool single_launch,
                           unsigned expect_tag, KernelEvents ev, hipStream_t stream, int keep_alive_stride)
 {
-    if (bt.vec && !gs.binary)
+    if (bt.vec)
         return launch_forward_vector(gs, bt, ws, out, out_is_double, tile_floats, waves_per_tile, expect_tag, ev,
                                      stream);
     if (tile_floats == 512) tile_floats = 1024;     // the smallest tile of these kernels
@@ -1405,37 +1384,34 @@ hipError_t launch_forward(const GridSpec &gs, const Batch &bt, const Workspace &
     if (lds_floor < 0) lds_floor = (tile_floats == 1024 && nw == 1 && !out_is_double && !bt.vec) ? 6144 : 0;
     if (lds_bytes < (size_t)lds_floor) lds_bytes = (size_t)lds_floor;
     const bool aligned = (gs.D % 4 == 0) && (((uintptr_t)out & 15u) == 0);
-    const bool vec = bt.vec;
     const dim3 blk(64 * nw), grd((unsigned)groups);
-#define MG_LAUNCH5(V, Bn, Al, It, Nw) \
-    hipExtLaunchKernelGGL((forward_kernel<V, Bn, Al, It, Nw, float>), grd, blk, (uint32_t)lds_bytes, \
+#define MG_LAUNCH5(Bn, Al, It, Nw) \
+    hipExtLaunchKernelGGL((forward_kernel<Bn, Al, It, Nw, float>), grd, blk, (uint32_t)lds_bytes, \
                           stream, ev.start, ev.stop, 0, p)
-#define MG_LAUNCH(V, Bn, Al)                                                    \
+#define MG_LAUNCH(Bn, Al)                                                       \
     if (out_is_double) {                                                        \
-        hipExtLaunchKernelGGL((forward_kernel<V, Bn, Al, 1, 1, double>), grd, blk,                 \
+        hipExtLaunchKernelGGL((forward_kernel<Bn, Al, 1, 1, double>), grd, blk,                    \
                               (uint32_t)lds_bytes, stream, ev.start, ev.stop, 0, p);               \
     } else switch (iters * 8 + nw) {                                            \
-    case 2 * 8 + 1: MG_LAUNCH5(V, Bn, Al, 2, 1); break;                         \
-    case 2 * 8 + 2: MG_LAUNCH5(V, Bn, Al, 2, 2); break;                         \
-    case 4 * 8 + 1: MG_LAUNCH5(V, Bn, Al, 4, 1); break;                         \
-    case 4 * 8 + 2: MG_LAUNCH5(V, Bn, Al, 4, 2); break;                         \
-    case 4 * 8 + 4: MG_LAUNCH5(V, Bn, Al, 4, 4); break;                         \
-    case 8 * 8 + 2: MG_LAUNCH5(V, Bn, Al, 8, 2); break;                         \
-    case 8 * 8 + 4: MG_LAUNCH5(V, Bn, Al, 8, 4); break;                         \
+    case 2 * 8 + 1: MG_LAUNCH5(Bn, Al, 2, 1); break;                            \
+    case 2 * 8 + 2: MG_LAUNCH5(Bn, Al, 2, 2); break;                            \
+    case 4 * 8 + 1: MG_LAUNCH5(Bn, Al, 4, 1); break;                            \
+    case 4 * 8 + 2: MG_LAUNCH5(Bn, Al, 4, 2); break;                            \
+    case 4 * 8 + 4: MG_LAUNCH5(Bn, Al, 4, 4); break;                            \
+    case 8 * 8 + 2: MG_LAUNCH5(Bn, Al, 8, 2); break;                            \
+    case 8 * 8 + 4: MG_LAUNCH5(Bn, Al, 8, 4); break;                            \
     default: return hipErrorInvalidValue;                                       \
     }
     if (single_launch) {
 #define MG_FUSED(Bn, Al) \
-    hipExtLaunchKernelGGL((forward_kernel<false, Bn, Al, 2, 1, float, true>), grd, blk, (uint32_t)lds_bytes, \
+    hipExtLaunchKernelGGL((forward_kernel<Bn, Al, 2, 1, float, true>), grd, blk, (uint32_t)lds_bytes, \
                           stream, ev.start, ev.stop, 0, p)
         if (gs.binary) { if (aligned) MG_FUSED(true, true); else MG_FUSED(true, false); }
         else           { if (aligned) MG_FUSED(false, true); else MG_FUSED(false, false); }
 #undef MG_FUSED
-    } else if (vec) {      // binary occupancy with vector types (the real density took the kernel above)
-        if (aligned) MG_LAUNCH(true, true, true) else MG_LAUNCH(true, true, false)
     } else {
-        if (gs.binary) { if (aligned) MG_LAUNCH(false, true, true) else MG_LAUNCH(false, true, false) }
-        else           { if (aligned) MG_LAUNCH(false, false, true) else MG_LAUNCH(false, false, false) }
+        if (gs.binary) { if (aligned) MG_LAUNCH(true, true) else MG_LAUNCH(true, false) }
+        else           { if (aligned) MG_LAUNCH(false, true) else MG_LAUNCH(false, false) }
     }
 #undef MG_LAUNCH
 #undef MG_LAUNCH5

@@ -172,7 +172,7 @@ __device__ inline void reduce_slot(const BwdParams &p, float step, float azs, co
         fsum += gf;
         sz = fmaf(gf, uz, sz);
         if (WANT_VALUE) {
-            const float tl = fminf(fmaf(x2 * rs, p.sAk, -p.cA), 0.0f);     // sqrt(A) (x - c)
+            const float tl = __builtin_amdgcn_fmed3f(fmaf(-(x2 * rs), p.sAk, p.cA), 0.0f, 1.0f);     // sqrt(A) (c - x), clamped to [0, 1]
             const float rho = x2 <= p.g2k ? e : tl * tl;
             sv = fmaf(gv[u], rho, sv);
         }
@@ -450,7 +450,7 @@ __device__ inline void reduce_group(const BwdParams &p, const GT *const (&Gq)[kC
                 const float f = x2 <= p.g2k ? e : ft;       // -f/4
                 F = fmaf(gc.cq[q], d[q].gv[u] * f, F);
                 if (WANT_W) {
-                    const float tl = fminf(fmaf(x2 * rs, p.sAk, -p.cA), 0.0f);     // sqrt(A) (x - c)
+                    const float tl = __builtin_amdgcn_fmed3f(fmaf(-(x2 * rs), p.sAk, p.cA), 0.0f, 1.0f);     // sqrt(A) (c - x), clamped to [0, 1]
                     const float rho = x2 <= p.g2k ? e : tl * tl;
                     sv[q] = fmaf(d[q].gv[u], rho, sv[q]);
                 }

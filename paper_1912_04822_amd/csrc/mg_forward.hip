@@ -233,7 +233,9 @@ __device__ inline void run_tasks(const TileCtx &cx, const Cand &cd, int ntasks)
                 fi += 1.0f;
                 const float x2 = fmaf(zs, zs, x2b);
                 const float e = __builtin_amdgcn_exp2f(-x2);
-                const float u = fminf(fmaf(__builtin_amdgcn_sqrtf(x2), cx.sA, -cA), 0.0f);
+                // sqrt(A) (c - x), at most exp(-g^2) <= 1 where the tail applies: the multiply-add's
+                // clamp to [0, 1] cuts it off at the cutoff
+                const float u = __builtin_amdgcn_fmed3f(fmaf(-__builtin_amdgcn_sqrtf(x2), cx.sA, cA), 0.0f, 1.0f);
                 const float rho = x2 <= cx.g2k ? e : u * u;             // 0 beyond the cutoff
                 if (FIXED) {
                     __hip_atomic_fetch_add(reinterpret_cast<int *>(rowp) + klo + i,
@@ -796,10 +798,17 @@ struct VecGroup {           // wave-uniform: the channels of this workgroup
     float rmax;
 };
 
-struct VecAtom {            // per atom, per channel of the group
-    float lw[kVecGroup];        // log2 |w_q|  (-inf for w_q = 0: the Gaussian is then 0)
-    float su[kVecGroup];        // sqrt|w_q| sA ratio_q
-    float sc[kVecGroup];        // sqrt|w_q| cA
+// Fixed-point tiles: sqrt(|w| rho) of a tail is at most sqrt(kFixedLimit) < 11 wherever the tail is
+// used, so divided by kVecTailScale it lies in [0, 1] and the multiply-add's clamp (to [0, 1], free)
+// replaces the min that cuts the tail off at the cutoff; the Gaussian's exponent carries the same
+// factor (squared), and the conversion to fixed point multiplies it back.
+constexpr float kVecTailScale = 16.0f;
+static_assert(kVecTailScale * kVecTailScale >= kFixedLimit, "the scaled tail root must stay in [0, 1]");
+
+struct VecAtom {            // per atom, per channel of the group (fixed point: see kVecTailScale)
+    float lw[kVecGroup];        // log2 |w_q|  (-inf for w_q = 0: the Gaussian is then 0); fixed: - 8
+    float su[kVecGroup];        // sqrt|w_q| sA ratio_q; fixed: / 16
+    float sc[kVecGroup];        // sqrt|w_q| cA; fixed: / 16
     int neg;                    // bit q: w_q < 0  (binary mode: bit q: w_q > 0, the atom marks channel q)
 };
 
@@ -861,15 +870,18 @@ __device__ inline void run_tasks_group(const TileCtx &cx, const VecGroup &vg, co
 #pragma unroll
             for (int q = 0; q < kVecGroup; ++q) {
                 const float e = __builtin_amdgcn_exp2f(fmaf(-vg.ratio2[q], x2, lw[q]));
-                const float u = fminf(fmaf(sx, su[q], -sc[q]), 0.0f);
+                // FIXED: the atom's constants carry 1/kVecTailScale (see VecAtom), so that the tail's
+                // root stays below 1 and the clamp of the multiply-add cuts it off at the cutoff
+                const float u = FIXED ? __builtin_amdgcn_fmed3f(fmaf(-sx, su[q], sc[q]), 0.0f, 1.0f)
+                                      : fminf(fmaf(sx, su[q], -sc[q]), 0.0f);
                 float val = x2 <= vg.thq[q] ? e : u * u;                    // |w_q| rho_q, 0 beyond the cutoff
                 if (SIGNED) val = __int_as_float(__float_as_int(val) | sb[q]);
                 if (FIXED) {
                     // |val| 2^24 + 1/2, truncated: rounded to the nearest fixed-point step
                     const float half = SIGNED ? __int_as_float(0x3f000000 | sb[q]) : 0.5f;
                     __hip_atomic_fetch_add(reinterpret_cast<int *>(q0) + q * stride,
-                                           (int)fmaf(val, kFixedOne, half), __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_WORKGROUP);
+                                           (int)fmaf(val, kFixedOne * kVecTailScale * kVecTailScale, half),
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 } else {
                     __hip_atomic_fetch_add(q0 + q * stride, val, __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -1114,8 +1126,8 @@ __global__ __launch_bounds__(64 * NW) void forward_vector_kernel(FwdParams p)
                 }
                 const float aw = fabsf(wc.w[q]);
                 wmax = fmaxf(wmax, aw);
-                const float sw = __builtin_amdgcn_sqrtf(aw);
-                va.lw[q] = __builtin_amdgcn_logf(aw);               // log2
+                const float sw = __builtin_amdgcn_sqrtf(aw) * (fixed ? 1.0f / kVecTailScale : 1.0f);
+                va.lw[q] = __builtin_amdgcn_logf(aw) - (fixed ? 8.0f : 0.0f);       // log2; 8 = log2 of the scale squared
                 va.su[q] = sw * vg.sAq[q];
                 va.sc[q] = sw * cx.cA;
                 va.neg |= (wc.w[q] < 0.0f ? 1 : 0) << q;

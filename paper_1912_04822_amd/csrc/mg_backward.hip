@@ -31,6 +31,10 @@
 // are reduced across the wavefront by DPP adds in a fixed order.  Records are grouped by
 // channel (and, within a channel, by x-plane), so neighbouring wavefronts read
 // the same part of the same channel volume.
+// (Consecutive lanes take consecutive slots of a row, so a 64-lane load touches about 25
+// lines.  Two atoms per wavefront with every lane walking the slots of its own rows -- no
+// slot list at all, a quarter fewer instructions -- touches 64 lines per load and measured
+// 74-100 us against 62 us.)
 #include <cmath>
 
 #include "mg_common.h"

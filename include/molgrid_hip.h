@@ -303,16 +303,18 @@ int mg_last_hip_error(void);
  * order of float additions).  Process-wide, each read once per call; setting
  * one while another thread is inside a call affects that call or the next.
  *   "tile_floats"     0, 512, 1024, 2048 or 4096 (default 0 = chosen per call
- *                     from the shapes): consecutive output floats of a channel
+ *                     from the shapes: 1024 or 2048 for index types, 2048 for
+ *                     vector types): consecutive output floats of a channel
  *                     one forward workgroup produces (512: vector types only,
  *                     4096: index types only; otherwise the nearest supported)
  *   "waves_per_tile"  0, 1, 2 or 4 (default 0 = chosen per call: 1 for index
- *                     types, 2 for vector types): wavefronts in that workgroup
+ *                     types, 4 for vector types, whose workgroup produces the
+ *                     tiles of four channels): wavefronts in that workgroup
  *                     (never more than tile_floats / 512; 4096-float tiles
- *                     take at least 2; vector types at most 2)
+ *                     take at least 2)
  *   "xcd_run"         0 or a power of two (default 0): runs of this many
  *                     consecutive tiles go to one XCD
- *   "keep_alive"      0, 1, 256, 512 or 1024 (default 1 = 256): every forward
+ *   "keep_alive"      0, 1, 64, 128, 256, 512 or 1024 (default 1 = 256): every forward
  *                     wavefront (index types, float grid) also reads that many
  *                     bytes of the workspace tables so that they stay cached while
  *                     the grid is streamed out

@@ -1201,7 +1201,8 @@ unsigned long long magic64(unsigned d)      // ceil(2^64 / d); 0 stands for d ==
 }
 }  // namespace
 
-// Vector types, real density: one wavefront per (example, group of kVecGroup channels, tile).
+// Vector types (real density and binary occupancy): one workgroup per (example, group of kVecGroup
+// channels, tile).
 static hipError_t launch_forward_vector(const GridSpec &gs, const Batch &bt, const Workspace &ws,
                                         void *out, bool out_is_double, int tile_floats,
                                         int waves_per_tile, unsigned expect_tag, KernelEvents ev,
@@ -1209,9 +1210,9 @@ static hipError_t launch_forward_vector(const GridSpec &gs, const Batch &bt, con
 {
     // 2048-float tiles and four wavefronts per workgroup: the four channel tiles of a group take
     // 33 KB of LDS, so four workgroups (sixteen wavefronts, what 111 registers allow) fit a CU.
-    // Measured on the 48^3 batch of 50 x 2040 atoms x 28 channels: 0.52 ms; 1024 floats x 2
-    // wavefronts 0.57 ms (each tile tests the atoms in reach anew); 2048 x 2 0.74 ms and 1024 x 1
-    // 0.75 ms (too few wavefronts); 512 x 1 0.69 ms.  A grid of doubles takes 512 voxels per tile.
+    // Measured on the 48^3 batch of 50 x 2040 atoms x 28 channels: 0.50 ms; relative to it, 1024
+    // floats x 2 wavefronts +10 % (each tile tests the atoms in reach anew), 2048 x 2 and 1024 x 1
+    // +43 % (too few wavefronts), 512 x 1 +33 %.  A grid of doubles takes 512 voxels per tile.
     if (tile_floats != 512 && tile_floats != 1024 && tile_floats != 2048) tile_floats = 2048;
     if (out_is_double) tile_floats = 512;
     const ForwardGeometry fg = forward_geometry(gs.D, tile_floats);
@@ -1252,7 +1253,7 @@ static hipError_t launch_forward_vector(const GridSpec &gs, const Batch &bt, con
     p.cA = (float)((double)gs.c * std::sqrt((double)gs.A));
     const unsigned long long wgs = (unsigned long long)bt.B * p.groups * fg.tiles;
     if (wgs > 0x7fffffffULL) return hipErrorInvalidValue;
-    // two wavefronts per workgroup by default: they share the tiles, so twice as many
+    // four wavefronts per workgroup by default: they share the tiles, so four times as many
     // wavefronts are resident for the same LDS (the kernel is bound by vector arithmetic and
     // needs them to keep the SIMDs busy)
     int nw = waves_per_tile == 0 ? 4 : waves_per_tile;

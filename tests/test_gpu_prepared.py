@@ -114,3 +114,35 @@ def test_tables_of_another_shape_leave_the_outputs_untouched(mg):
     ref = gm.mg_forward_index(co, ty, ra, w.T, **kw)
     torch.cuda.synchronize()
     assert np.array_equal(bits(good), bits(ref))
+
+
+def test_calls_on_two_streams_keep_their_tables_apart(mg):
+    """One GridMaker used from two streams at once: the binding keeps a workspace per stream, so
+    the tables of one call are not overwritten by the other while its kernels still read them.
+    Different inputs go down each stream several times over; every result equals the one the
+    same call gives alone."""
+    wa = workloads.protein_ligand(B=6, seed=11)
+    wb = workloads.protein_ligand(B=6, seed=12)
+    gm = mg.GridMaker(wa.resolution, wa.dimension, radius_type_indexed=True)
+
+    def args(w):
+        return (dev(w.coords), dev(w.types), dev(w.radii), w.T), dict(
+            centers=dev(w.centers), quats=dev(w.quats), translations=dev(w.translations))
+
+    (pa, ka), (pb, kb) = args(wa), args(wb)
+    alone_a = gm.mg_forward_index(*pa, **ka)
+    alone_b = gm.mg_forward_index(*pb, **kb)
+    torch.cuda.synchronize()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()       # default priority
+    outs_a, outs_b = [], []
+    for _ in range(4):
+        with torch.cuda.stream(sa):
+            outs_a.append(gm.mg_forward_index(*pa, **ka))
+        with torch.cuda.stream(sb):
+            outs_b.append(gm.mg_forward_index(*pb, **kb))
+    torch.cuda.synchronize()
+    assert len(gm._ws) >= 3        # the default stream's and one per side stream
+    for o in outs_a:
+        assert np.array_equal(bits(o), bits(alone_a))
+    for o in outs_b:
+        assert np.array_equal(bits(o), bits(alone_b))

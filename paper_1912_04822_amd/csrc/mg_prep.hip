@@ -16,8 +16,8 @@
 // Culling is exact: the density is identically zero beyond c(grm)*r, so an
 // atom whose cutoff cube misses the grid box contributes nothing.
 //
-// Usual sizes: one 1024-thread workgroup per example does a counting sort of
-// the example's atoms by (type, x-plane bin) in LDS:
+// Usual sizes: one workgroup per example (512 threads up to 2048 atoms, 1024
+// beyond) does a counting sort of the example's atoms by (type, x-plane bin) in LDS:
 //   1. every atom: transform, cull, key = type * bins + bin (bins 0 and D+1 are
 //      the atoms left / right of the grid, bin D+2 the culled ones), count;
 //   2. exclusive scan of the counts = where each (type, bin) starts;
@@ -137,7 +137,7 @@ __device__ inline void rank_channels(const Batch &bt, const Workspace &ws, int b
 // ---------------------------------------------------------------------------
 // One workgroup per example: counting sort by (type, x-bin) in LDS.
 // ---------------------------------------------------------------------------
-constexpr int kExThreads = 1024;
+constexpr int kExThreads = 1024;            // the larger of the two block sizes
 constexpr int kExMaxAtoms = 8192;           // 8 atoms per thread (4 in the kernel for N <= 4096)
 constexpr int kExMaxKeys = 12288;
 
@@ -152,8 +152,8 @@ struct ExLayout {       // LDS, in ints
     __host__ __device__ int ints() const { return order() + (N + 1) / 2; }
 };
 
-template <bool VECTOR, int kPer>
-__global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, Batch bt,
+template <bool VECTOR, int kPer, int NT>
+__global__ __launch_bounds__(NT) void prep_example_kernel(GridSpec gs, Batch bt,
                                                                   Workspace ws, unsigned tag,
                                                                   int stop)
 {
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     float my_c[kPer][3], my_r[kPer];
 #pragma unroll
     for (int u = 0; u < kPer; ++u) {
-        const int a = tid + u * kExThreads;
+        const int a = tid + u * NT;
         my_t[u] = -1;
         my_c[u][0] = 0.0f; my_c[u][1] = 0.0f; my_c[u][2] = 0.0f;
         my_r[u] = 0.0f;
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     if (b == 0 && tid == 0) *ws.tag = tag;
     float vec_reach = 0.0f;         // reach of the widest channel, for vector types
     if (VECTOR) {
-        rank_channels(bt, ws, b, tid, kExThreads);
+        rank_channels(bt, ws, b, tid, NT);
         for (int k = 0; k < T; ++k) {
             const float r = gs.radius_scale * bt.radii[k];
             if (r > vec_reach) vec_reach = r;
@@ -227,11 +227,11 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
 
     if (rad_table) {
         if (tid < Tg) s_rad[tid] = my_rad;
-        for (int k = tid + kExThreads; k < Tg; k += kExThreads) s_rad[k] = bt.radii[k];
+        for (int k = tid + NT; k < Tg; k += NT) s_rad[k] = bt.radii[k];
     }
     if (MG_STOP_IS(stop, 2)) return;
-    for (int k = tid; k < K; k += kExThreads) s_cnt[k] = 0;
-    for (int k = tid; k < Tg; k += kExThreads) s_rmax[k] = 0;
+    for (int k = tid; k < K; k += NT) s_cnt[k] = 0;
+    for (int k = tid; k < Tg; k += NT) s_rmax[k] = 0;
     __syncthreads();
 
     // ---- 1. key and a slot inside its bin for every atom ----
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     float my_p[kPer][3], my_w[kPer];        // transformed position, radius (0: culled)
 #pragma unroll
     for (int u = 0; u < kPer; ++u) {
-        const int a = tid + u * kExThreads;
+        const int a = tid + u * NT;
         my_key[u] = 0xFFFF;
         my_slot[u] = 0;
         my_w[u] = 0.0f;
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     if (MG_STOP_IS(stop, 3)) return;
 
     // ---- 2. exclusive scan of the counts ----
-    const int chunk = (K + kExThreads - 1) / kExThreads;
+    const int chunk = (K + NT - 1) / NT;
     const int k0 = min(K, tid * chunk), k1 = min(K, k0 + chunk);
     int mine = 0;
     for (int k = k0; k < k1; ++k) mine += s_cnt[k];
@@ -289,14 +289,14 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     __syncthreads();
     if (tid < 64) {
         int t16;
-        const int v = tid < kExThreads / 64 ? s_part[tid] : 0;
+        const int v = tid < NT / 64 ? s_part[tid] : 0;
         const int ex = wave_exclusive_scan(v, &t16);
-        if (tid < kExThreads / 64) s_part[tid] = ex;
-        if (tid == 0) s_part[kExThreads / 64] = t16;
+        if (tid < NT / 64) s_part[tid] = ex;
+        if (tid == 0) s_part[NT / 64] = t16;
     }
     __syncthreads();
     run += s_part[tid >> 6];
-    const int total = s_part[kExThreads / 64];      // atoms that belong to a group
+    const int total = s_part[NT / 64];      // atoms that belong to a group
     for (int k = k0; k < k1; ++k) {
         s_pos[k] = run;
         run += s_cnt[k];
@@ -307,14 +307,14 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     // ---- 3. atoms into their bins in any order; group descriptors and spans meanwhile ----
 #pragma unroll
     for (int u = 0; u < kPer; ++u)
-        if (my_key[u] != 0xFFFF) s_order[s_pos[my_key[u]] + my_slot[u]] = (unsigned short)(tid + u * kExThreads);
-    for (int tg = tid; tg < Tg; tg += kExThreads) {
+        if (my_key[u] != 0xFFFF) s_order[s_pos[my_key[u]] + my_slot[u]] = (unsigned short)(tid + u * NT);
+    for (int tg = tid; tg < Tg; tg += NT) {
         const int first = s_pos[tg * nb];
         const int dead = s_pos[tg * nb + D + 2];
         const int end = tg + 1 < Tg ? s_pos[(tg + 1) * nb] : total;
         ws.meta[(size_t)b * T + tg] = make_int4(first, dead - first, end - first, 1);
     }
-    for (int e = tid; e < Tg * D; e += kExThreads) {
+    for (int e = tid; e < Tg * D; e += NT) {
         const int tg = e / D, i = e - tg * D;
         // plane i is reached from bins [i - Rv, i + Rv + 1]
         const float rmax = VECTOR ? vec_reach
@@ -333,7 +333,7 @@ __global__ __launch_bounds__(kExThreads) void prep_example_kernel(GridSpec gs, B
     for (int u = 0; u < kPer; ++u) {
         const int key = my_key[u];
         if (key == 0xFFFF) continue;
-        const int a = tid + u * kExThreads;
+        const int a = tid + u * NT;
         const int lo = s_pos[key];
         int rank = my_slot[u];
         if (key - (key / nb) * nb != D + 2) {
@@ -660,20 +660,34 @@ hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
     L.K = (int)(K <= kExMaxKeys ? K : 0);
     const size_t lds_bytes = (size_t)L.ints() * sizeof(int);
     if (K <= kExMaxKeys && bt.N <= kExMaxAtoms && lds_bytes <= 64 * 1024) {
-        const dim3 grd(bt.B), blk(kExThreads);
-        if (bt.N <= 4 * kExThreads) {
+        const dim3 grd(bt.B);
+        // 512 threads while they still hold all the atoms four apiece: half as many wavefronts
+        // behind every barrier (1 us less per call at 2040 atoms; 256 threads with eight atoms
+        // apiece measured 4 us more)
+        if (bt.N <= 4 * 512) {
+            const dim3 blk(512);
             if (vec)
-                hipLaunchKernelGGL((prep_example_kernel<true, 4>), grd, blk, lds_bytes, stream, gs, bt,
+                hipLaunchKernelGGL((prep_example_kernel<true, 4, 512>), grd, blk, lds_bytes, stream, gs, bt,
                                    ws, tag, stop);
             else
-                hipLaunchKernelGGL((prep_example_kernel<false, 4>), grd, blk, lds_bytes, stream, gs,
+                hipLaunchKernelGGL((prep_example_kernel<false, 4, 512>), grd, blk, lds_bytes, stream, gs,
+                                   bt, ws, tag, stop);
+            return hipGetLastError();
+        }
+        const dim3 blk(kExThreads);
+        if (bt.N <= 4 * kExThreads) {
+            if (vec)
+                hipLaunchKernelGGL((prep_example_kernel<true, 4, kExThreads>), grd, blk, lds_bytes, stream, gs, bt,
+                                   ws, tag, stop);
+            else
+                hipLaunchKernelGGL((prep_example_kernel<false, 4, kExThreads>), grd, blk, lds_bytes, stream, gs,
                                    bt, ws, tag, stop);
         } else {
             if (vec)
-                hipLaunchKernelGGL((prep_example_kernel<true, 8>), grd, blk, lds_bytes, stream, gs, bt,
+                hipLaunchKernelGGL((prep_example_kernel<true, 8, kExThreads>), grd, blk, lds_bytes, stream, gs, bt,
                                    ws, tag, stop);
             else
-                hipLaunchKernelGGL((prep_example_kernel<false, 8>), grd, blk, lds_bytes, stream, gs,
+                hipLaunchKernelGGL((prep_example_kernel<false, 8, kExThreads>), grd, blk, lds_bytes, stream, gs,
                                    bt, ws, tag, stop);
         }
         return hipGetLastError();

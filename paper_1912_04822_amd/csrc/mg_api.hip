@@ -112,7 +112,7 @@ int check_shape(const mg_gridmaker *gm, int B, int N, int T)
 
 int check_workspace(const mg_gridmaker *gm, int B, int N, int T, void *ws, size_t ws_bytes)
 {
-        if (!ws) return MG_EWORKSPACE;
+    if (!ws) return MG_EWORKSPACE;
     if (((uintptr_t)ws & 31u) != 0) return MG_EWORKSPACE;
     if (ws_bytes < mg::workspace_bytes(gm->gs, gm->sub.count, B * gm->sub.count, N, T)) return MG_EWORKSPACE;
     return MG_OK;

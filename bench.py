@@ -357,9 +357,8 @@ def main():
         # bound, streaming the whole gradient grid once the trivial one
         def kernel_after_forward(fn, n):
             """The backward kernel's duration when a forward call (619 MB of stores) ran just
-            before it, as in a training step: the gradient grid then comes from HBM, while in a
-            back-to-back loop of backward calls the lines it touches (270 MB of the 619 MB) largely
-            stay in the 256 MB memory-side cache from one call to the next."""
+            before it, as in a training step: the gradient grid comes from HBM and the last part
+            of the forward's stores still sits dirty in the 256 MB memory-side cache."""
             ev = Events(n)
             for i in range(3 + n):
                 step()
@@ -399,8 +398,7 @@ def main():
             kc, kcmin = kernel_after_read(fn, min(steps, 30))
             r["kernel_ms_after_read_of_another_buffer"] = kc
             r["kernel_ms_after_read_of_another_buffer_min"] = kcmin
-            r["kernel_ms_avg_is"] = ("back-to-back backward calls: the gradient grid's lines stay "
-                                     "largely in the memory-side cache between calls")
+            r["kernel_ms_avg_is"] = "back-to-back backward calls"
             r["atoms_per_s"] = w.B * w.N / (r["ms_per_call"] * 1e-3)
             r["roofline"] = hbm_roofline(4 * distinct, kc, "distinct in-cutoff voxels of the upstream "
                                                            "gradient x 4 B (HBM read); kernel timed "
@@ -411,10 +409,11 @@ def main():
             r["roofline"]["grid_in_cache_frac"] = 4 * distinct / (warm * 1e-3) / 1e9 / HBM_PEAK_GBS
             r["roofline"]["after_forward_frac"] = 4 * distinct / (k * 1e-3) / 1e9 / HBM_PEAK_GBS
             r["roofline"]["after_forward_is"] = (
-                "the kernel timed right after a forward call: the forward's last ~256 MB of stores "
-                "are still dirty in the memory-side cache and are written back while this kernel "
-                "reads (a read-only probe of the same 270 MB of lines takes 45 us after a read "
-                "pass and 90-97 us after a 619 MB fill)")
+                "the kernel timed right after a forward call, whose last ~256 MB of stores are "
+                "still dirty in the memory-side cache (a read-only probe of the same 270 MB of "
+                "lines takes 45 us after a read pass and 90-97 us after a 619 MB fill; the "
+                "index-type kernel's loads carry the non-temporal hint so that they do not push "
+                "those lines out: 74 us, 100 us without the hint)")
             fetch, src = stored(fetch_key)
             if fetch is not None:
                 r["roofline"]["line_bound"] = {

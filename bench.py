@@ -406,7 +406,7 @@ def main():
                                                            "buffer: gradient grid from HBM, no dirty "
                                                            "lines of an earlier kernel being written "
                                                            "back meanwhile")
-            r["roofline"]["grid_in_cache_frac"] = 4 * distinct / (warm * 1e-3) / 1e9 / HBM_PEAK_GBS
+            r["roofline"]["back_to_back_frac"] = 4 * distinct / (warm * 1e-3) / 1e9 / HBM_PEAK_GBS
             r["roofline"]["after_forward_frac"] = 4 * distinct / (k * 1e-3) / 1e9 / HBM_PEAK_GBS
             r["roofline"]["after_forward_is"] = (
                 "the kernel timed right after a forward call, whose last ~256 MB of stores are "
@@ -415,11 +415,19 @@ def main():
                 "index-type kernel's loads carry the non-temporal hint so that they do not push "
                 "those lines out: 74 us, 100 us without the hint)")
             fetch, src = stored(fetch_key)
+            lines, lsrc = stored(fetch_key.replace("fetch_bytes", "distinct_line_bytes"))
             if fetch is not None:
+                r["roofline"]["traffic"] = fetch
+                r["roofline"]["traffic_source"] = (
+                    "%s (FETCH_SIZE x 2.00 per launch, stored from that profile, not measured in "
+                    "this run)" % src)
+            bound = lines if lines is not None else fetch
+            if bound is not None:
                 r["roofline"]["line_bound"] = {
-                    "bytes": fetch, "frac": fetch / (kc * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                    "source": "%s (FETCH_SIZE x 2.00, stored from that profile, not measured in "
-                              "this run): the 128-byte lines those voxels touch" % src}
+                    "bytes": bound, "frac": bound / (kc * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                    "what": ("the distinct 128-byte lines those voxels lie in, counted on the host (%s)"
+                             % lsrc) if lines is not None else
+                            "the bytes the kernel fetches (see traffic): its distinct lines were not counted"}
             r["roofline"]["stream_whole_grid_frac"] = w.out_bytes / (kc * 1e-3) / 1e9 / HBM_PEAK_GBS
             r["alu"] = alu_roofline(valu_key, warm)
             rows[name] = r

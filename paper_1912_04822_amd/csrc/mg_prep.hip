@@ -16,8 +16,8 @@
 // Culling is exact: the density is identically zero beyond c(grm)*r, so an
 // atom whose cutoff cube misses the grid box contributes nothing.
 //
-// Usual sizes: one workgroup per example (512 threads up to 2048 atoms, 1024
-// beyond) does a counting sort of the example's atoms by (type, x-plane bin) in LDS:
+// Usual sizes: one workgroup per example (512 threads up to 2048 atoms of index
+// types, 1024 otherwise) does a counting sort of the example's atoms by (type, x-plane bin) in LDS:
 //   1. every atom: transform, cull, key = type * bins + bin (bins 0 and D+1 are
 //      the atoms left / right of the grid, bin D+2 the culled ones), count;
 //   2. exclusive scan of the counts = where each (type, bin) starts;
@@ -664,14 +664,9 @@ hipError_t launch_prep(const GridSpec &gs, const Batch &bt, const Workspace &ws,
         // 512 threads while they still hold all the atoms four apiece: half as many wavefronts
         // behind every barrier (1 us less per call at 2040 atoms; 256 threads with eight atoms
         // apiece measured 4 us more)
-        if (bt.N <= 4 * 512) {
-            const dim3 blk(512);
-            if (vec)
-                hipLaunchKernelGGL((prep_example_kernel<true, 4, 512>), grd, blk, lds_bytes, stream, gs, bt,
-                                   ws, tag, stop);
-            else
-                hipLaunchKernelGGL((prep_example_kernel<false, 4, 512>), grd, blk, lds_bytes, stream, gs,
-                                   bt, ws, tag, stop);
+        if (bt.N <= 4 * 512 && !vec) {      // (vector types, which also rank the channels: 1024 is 1.5 us quicker)
+            hipLaunchKernelGGL((prep_example_kernel<false, 4, 512>), grd, dim3(512), lds_bytes, stream, gs,
+                               bt, ws, tag, stop);
             return hipGetLastError();
         }
         const dim3 blk(kExThreads);
